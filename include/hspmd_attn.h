@@ -1,0 +1,178 @@
+/*
+ * libhspmd_attn -- causal self-attention forward and backward over packed
+ * variable-length sequences on ONE GPU's share of the attention heads,
+ * written for AMD MI355X (gfx950).
+ *
+ * Where this sits in the paper (HSPMD / Hetu v2): it is the device-level work
+ * behind the AttentionFwd / AttentionBwd operators of the forward and backward
+ * executable subgraphs (Appendix "Implementation Details", subsection
+ * "Execution").  What reaches such an operator at run time is what the
+ * arguments below carry:
+ *   - packed mixed-length sequences whose concrete shapes are only resolved
+ *     when the inputs arrive on the device (Section 6.3 "Execution"; Appendix,
+ *     "Symbolic shape extension"; Evaluations, scenario (c) "Mixed-length
+ *     data")                                      -> cu_seqlens;
+ *   - a shard of the hidden dimension whose size may differ between sharding
+ *     subgroups (Section 4.2, HDim / HSize and its footnote: the shape of each
+ *     shard can vary and is determined at runtime)
+ *                                                 -> local_q_heads, local_kv_heads;
+ *   - optional grouped KV heads (model table "Query Groups")
+ *                                                 -> local_q_heads / local_kv_heads.
+ * The paper does not write the attention formula; it is the standard causal
+ * scaled-dot-product attention (Section 2.1 cites it), per sequence:
+ *
+ *   S_rj = scale <q_r, k_j>  (j <= r),   P = softmax_j S,   O_r = sum_j P_rj v_j,
+ *   LSE_r = ln sum_{j<=r} exp(S_rj);
+ *   dP_rj = <dO_r, v_j>, D_r = <dO_r, O_r>, dS = P (dP - D),
+ *   dQ_r = scale sum_j dS_rj k_j,  dK_j = scale sum_{h,r} dS_rj q_r,  dV_j = sum_{h,r} P_rj dO_r
+ *   (h runs over the query heads that share the KV head; query head h uses KV
+ *   head h / (local_q_heads / local_kv_heads)).
+ *
+ * Conventions for every entry point
+ *   - Device pointers are plain `void*` / `float*` to memory the CALLER owns
+ *     (allocate it with anything: hipMalloc, a PyTorch tensor).  Host pointers
+ *     are marked "host".
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *     Forward and backward only enqueue work; they never synchronise and never
+ *     allocate.  Plan creation allocates the plan's small index arrays and
+ *     copies them to the device before returning.
+ *   - Every call returns an hspmd_status; no exception crosses this boundary
+ *     and nothing aborts.  Arguments are validated on the host before any
+ *     launch.  hspmd_last_error() returns a thread-local description of the
+ *     last failure on the calling thread.
+ *   - bf16 tensors are raw 16-bit bfloat16 values.
+ */
+#ifndef HSPMD_ATTN_H
+#define HSPMD_ATTN_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    HSPMD_OK = 0,
+    HSPMD_ERR_INVALID_ARG = 1,        /* null pointer, bad lengths, bad strides, heads not a whole number of groups */
+    HSPMD_ERR_UNSUPPORTED = 2,        /* head_dim other than 64 or 128, unknown dtype */
+    HSPMD_ERR_WORKSPACE_TOO_SMALL = 3,
+    HSPMD_ERR_HIP = 4                 /* a HIP runtime call failed; see hspmd_last_error() */
+} hspmd_status;
+
+/* dtype of the gradients written by hspmd_attn_varlen_bwd */
+typedef enum { HSPMD_GRAD_BF16 = 0, HSPMD_GRAD_F32 = 1 } hspmd_grad_dtype;
+
+/* which work list of a plan (see hspmd_attn_schedule) */
+typedef enum {
+    HSPMD_LIST_FWD = 0,   /* items (sequence, q tile, q head): forward kernel          */
+    HSPMD_LIST_DQ = 1,    /* items (sequence, q tile, q head): backward dQ pass        */
+    HSPMD_LIST_DKV = 2    /* items (sequence, k tile, kv head): backward dK/dV pass    */
+} hspmd_list_kind;
+
+/* One unit of work for one workgroup.  tile < 0 marks a padding slot that does nothing. */
+typedef struct {
+    int32_t token_start;  /* first packed token of the sequence (cu_seqlens[seq])      */
+    int32_t seq_len;      /* L of that sequence                                          */
+    int32_t tile;         /* q tile index (FWD, DQ) or k tile index (DKV) within it      */
+    int32_t head;         /* local q head (FWD, DQ) or local kv head (DKV)               */
+} hspmd_work_item;
+
+/* Never NULL.  Thread-local. */
+const char* hspmd_last_error(void);
+
+/* Rows per tile of each list kind (q rows for FWD/DQ, key rows for DKV). */
+int32_t hspmd_attn_tile_rows(hspmd_list_kind kind);
+
+/*
+ * Packed-sequence offsets (run-time shapes; Section 6.3, Appendix "Symbolic
+ * shape extension").  Host only.
+ *   lengths      host, [num_seqs], each >= 0 (zero-length sequences are legal)
+ *   cu_seqlens   host, [num_seqs + 1], caller-owned, receives the exclusive prefix sum
+ *   max_seqlen   host, may be NULL
+ *   total_tokens host, may be NULL
+ * Fails with INVALID_ARG on a null pointer, num_seqs < 0, a negative length, or a
+ * running sum above INT32_MAX.
+ */
+hspmd_status hspmd_build_cu_seqlens(const int32_t* lengths, int32_t num_seqs, int32_t* cu_seqlens,
+                                    int32_t* max_seqlen, int64_t* total_tokens);
+
+/*
+ * The cost-sorted work list, host only (no GPU needed).  This is the on-device
+ * counterpart of the paper's cost-model-driven dispatch of mixed-length
+ * sequences (Appendix "Scenario-specific Planning", mixed-length case): the
+ * unit here is one tile of one sequence and head, its cost the number of tile
+ * pairs it visits under the causal mask.
+ *
+ * Items are emitted in launch order: slot p is executed by workgroup p.  Slots
+ * p with equal p % num_queues form one queue; a queue keeps tiles that share
+ * K/V (FWD, DQ) or Q/dO (DKV) together, queues are balanced by total cost and
+ * each queue runs its expensive items first.  Shorter queues are padded with
+ * tile = -1 slots so that every queue has the same length.
+ *
+ *   cu_seqlens   host, [num_seqs + 1], cu[0] == 0, non-decreasing
+ *   num_queues   >= 1 (the library uses 8, the number of XCDs of an MI355X)
+ *   items        host, caller-owned, capacity entries; may be NULL when capacity == 0
+ *   count        receives the number of slots the list needs; if it exceeds capacity
+ *                nothing is written and INVALID_ARG is returned (call with capacity 0
+ *                first to size the buffer: that call returns OK)
+ */
+hspmd_status hspmd_attn_schedule(hspmd_list_kind kind, const int32_t* cu_seqlens, int32_t num_seqs,
+                                 int32_t local_q_heads, int32_t local_kv_heads, int32_t num_queues,
+                                 hspmd_work_item* items, int64_t capacity, int64_t* count);
+
+/*
+ * Plan: the three device-resident work lists for one pack and one local head
+ * configuration.  One plan serves every layer and both passes of a micro-batch.
+ * Opaque, library-owned; destroy it with hspmd_attn_plan_destroy.  Creating a
+ * plan needs a GPU; it synchronises `stream` before returning.
+ *   local_q_heads   query heads held by this GPU (any positive count: an uneven share is fine)
+ *   local_kv_heads  KV heads held by this GPU; local_q_heads % local_kv_heads must be 0
+ *   head_dim        64 or 128
+ */
+typedef struct hspmd_attn_plan hspmd_attn_plan;
+hspmd_status hspmd_attn_plan_create(const int32_t* cu_seqlens_host, int32_t num_seqs, int32_t local_q_heads,
+                                    int32_t local_kv_heads, int32_t head_dim, void* stream,
+                                    hspmd_attn_plan** out);
+hspmd_status hspmd_attn_plan_destroy(hspmd_attn_plan* plan);      /* NULL is accepted */
+int64_t hspmd_attn_plan_total_tokens(const hspmd_attn_plan* plan); /* -1 on NULL */
+int64_t hspmd_attn_plan_num_items(const hspmd_attn_plan* plan, hspmd_list_kind kind); /* slots incl. padding */
+
+/* Bytes of device workspace hspmd_attn_varlen_bwd needs: D[local_q_heads, T] in fp32. */
+size_t hspmd_attn_bwd_workspace_bytes(const hspmd_attn_plan* plan);
+
+/*
+ * Forward (AttentionFwd).  All tensors device memory.
+ *   q   bf16 [T, local_q_heads, head_dim]; token t, head h at q + t*q_token_stride + h*head_dim
+ *   k,v bf16 [T, local_kv_heads, head_dim]; token stride kv_token_stride (same for k and v)
+ *       Strides are in elements and let q/k/v be views into a fused QKV projection output;
+ *       they must be multiples of 8 (16-byte rows) and >= heads*head_dim; base pointers 16-byte aligned.
+ *   softmax_scale   <= 0 selects 1/sqrt(head_dim)
+ *   o   bf16 [T, local_q_heads, head_dim], contiguous, written
+ *   lse fp32 [local_q_heads, T], natural-log logsumexp of the scaled scores, written
+ * T == 0 returns OK without launching.
+ */
+hspmd_status hspmd_attn_varlen_fwd(const hspmd_attn_plan* plan, const void* q, const void* k, const void* v,
+                                   int64_t q_token_stride, int64_t kv_token_stride, float softmax_scale,
+                                   void* o, float* lse, void* stream);
+
+/*
+ * Backward (AttentionBwd): three launches on `stream` -- D = rowsum(dO * O); the dQ
+ * pass; the dK/dV pass.  Both passes recompute P from the stored lse.  No atomics:
+ * results are run-to-run bit-identical.
+ *   o, d_o  bf16 [T, local_q_heads, head_dim], contiguous
+ *   lse     fp32 [local_q_heads, T] as written by the forward
+ *   dq      [T, local_q_heads, head_dim]; dk, dv [T, local_kv_heads, head_dim]; contiguous,
+ *           bf16 or fp32 according to grad_dtype; fully overwritten
+ *   workspace  device, at least hspmd_attn_bwd_workspace_bytes(plan) bytes, 16-byte aligned
+ */
+hspmd_status hspmd_attn_varlen_bwd(const hspmd_attn_plan* plan, const void* q, const void* k, const void* v,
+                                   const void* o, const float* lse, const void* d_o,
+                                   int64_t q_token_stride, int64_t kv_token_stride, float softmax_scale,
+                                   void* dq, void* dk, void* dv, hspmd_grad_dtype grad_dtype,
+                                   void* workspace, size_t workspace_bytes, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* HSPMD_ATTN_H */

@@ -1,0 +1,11 @@
+"""Thin Python binding of libhspmd_attn (argument marshalling only).
+
+Every step of the hot path runs inside the HIP library; PyTorch appears here only as the owner
+of device memory and streams.  There is no CPU fallback: if the shared library is missing or no
+GPU is present, the compute calls raise.
+"""
+from .binding import (  # noqa: F401
+    HspmdError, Plan, LIST_FWD, LIST_DQ, LIST_DKV, GRAD_BF16, GRAD_F32,
+    library_path, load_library, build_cu_seqlens, schedule, tile_rows,
+    attn_varlen_fwd, attn_varlen_bwd,
+)

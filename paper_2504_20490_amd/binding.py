@@ -1,0 +1,195 @@
+"""ctypes binding of the C ABI declared in include/hspmd_attn.h (same names, no arithmetic)."""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import List, Optional, Sequence, Tuple
+
+import numpy as np
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(HERE, "libhspmd_attn.so")
+
+LIST_FWD, LIST_DQ, LIST_DKV = 0, 1, 2
+GRAD_BF16, GRAD_F32 = 0, 1
+
+_STATUS = {0: "OK", 1: "INVALID_ARG", 2: "UNSUPPORTED", 3: "WORKSPACE_TOO_SMALL", 4: "HIP"}
+
+
+class HspmdError(RuntimeError):
+    def __init__(self, status: int, message: str):
+        super().__init__(f"hspmd status {_STATUS.get(status, status)}: {message}")
+        self.status = status
+
+
+class WorkItem(ctypes.Structure):
+    _fields_ = [("token_start", ctypes.c_int32), ("seq_len", ctypes.c_int32),
+                ("tile", ctypes.c_int32), ("head", ctypes.c_int32)]
+
+
+_lib = None
+
+
+def library_path() -> str:
+    return _LIB_PATH
+
+
+def load_library():
+    """Load the built library.  Raises if it has not been built: there is no fallback."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_LIB_PATH):
+        raise FileNotFoundError(
+            f"{_LIB_PATH} is missing: build it first (python -m paper_2504_20490_amd.build "
+            "or __graft_entry__.build())")
+    lib = ctypes.CDLL(_LIB_PATH)
+    i32p = ctypes.POINTER(ctypes.c_int32)
+    i64p = ctypes.POINTER(ctypes.c_int64)
+    vp = ctypes.c_void_p
+    lib.hspmd_last_error.restype = ctypes.c_char_p
+    lib.hspmd_last_error.argtypes = []
+    lib.hspmd_attn_tile_rows.restype = ctypes.c_int32
+    lib.hspmd_attn_tile_rows.argtypes = [ctypes.c_int]
+    lib.hspmd_build_cu_seqlens.restype = ctypes.c_int
+    lib.hspmd_build_cu_seqlens.argtypes = [i32p, ctypes.c_int32, i32p, i32p, i64p]
+    lib.hspmd_attn_schedule.restype = ctypes.c_int
+    lib.hspmd_attn_schedule.argtypes = [ctypes.c_int, i32p, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32,
+                                        ctypes.c_int32, ctypes.POINTER(WorkItem), ctypes.c_int64, i64p]
+    lib.hspmd_attn_plan_create.restype = ctypes.c_int
+    lib.hspmd_attn_plan_create.argtypes = [i32p, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32,
+                                           vp, ctypes.POINTER(vp)]
+    lib.hspmd_attn_plan_destroy.restype = ctypes.c_int
+    lib.hspmd_attn_plan_destroy.argtypes = [vp]
+    lib.hspmd_attn_plan_total_tokens.restype = ctypes.c_int64
+    lib.hspmd_attn_plan_total_tokens.argtypes = [vp]
+    lib.hspmd_attn_plan_num_items.restype = ctypes.c_int64
+    lib.hspmd_attn_plan_num_items.argtypes = [vp, ctypes.c_int]
+    lib.hspmd_attn_bwd_workspace_bytes.restype = ctypes.c_size_t
+    lib.hspmd_attn_bwd_workspace_bytes.argtypes = [vp]
+    lib.hspmd_attn_varlen_fwd.restype = ctypes.c_int
+    lib.hspmd_attn_varlen_fwd.argtypes = [vp, vp, vp, vp, ctypes.c_int64, ctypes.c_int64, ctypes.c_float,
+                                          vp, vp, vp]
+    lib.hspmd_attn_varlen_bwd.restype = ctypes.c_int
+    lib.hspmd_attn_varlen_bwd.argtypes = [vp, vp, vp, vp, vp, vp, vp, ctypes.c_int64, ctypes.c_int64,
+                                          ctypes.c_float, vp, vp, vp, ctypes.c_int, vp, ctypes.c_size_t, vp]
+    _lib = lib
+    return lib
+
+
+def _check(status: int) -> None:
+    if status != 0:
+        raise HspmdError(status, load_library().hspmd_last_error().decode())
+
+
+def _i32(a: Sequence[int]) -> np.ndarray:
+    return np.ascontiguousarray(np.asarray(a, dtype=np.int32))
+
+
+def _ptr32(a: np.ndarray):
+    return a.ctypes.data_as(ctypes.POINTER(ctypes.c_int32))
+
+
+def tile_rows(kind: int) -> int:
+    return int(load_library().hspmd_attn_tile_rows(kind))
+
+
+def build_cu_seqlens(lengths: Sequence[int]) -> Tuple[np.ndarray, int, int]:
+    """Returns (cu_seqlens int32 [B+1], max_seqlen, total_tokens)."""
+    lib = load_library()
+    raw = np.asarray(lengths, dtype=np.int64)
+    if raw.size and (raw.max() > np.iinfo(np.int32).max or raw.min() < np.iinfo(np.int32).min):
+        raise HspmdError(1, "sequence length does not fit int32")
+    lens = _i32(lengths)
+    cu = np.zeros(len(lens) + 1, dtype=np.int32)
+    mx = ctypes.c_int32(0)
+    tot = ctypes.c_int64(0)
+    _check(lib.hspmd_build_cu_seqlens(_ptr32(lens), len(lens), _ptr32(cu), ctypes.byref(mx), ctypes.byref(tot)))
+    return cu, int(mx.value), int(tot.value)
+
+
+def schedule(kind: int, cu_seqlens: Sequence[int], q_heads: int, kv_heads: int, num_queues: int = 8) -> np.ndarray:
+    """Host-only: the launch-ordered work list as an int32 array [slots, 4]
+    (token_start, seq_len, tile, head); padding slots have tile == -1."""
+    lib = load_library()
+    cu = _i32(cu_seqlens)
+    n = ctypes.c_int64(0)
+    _check(lib.hspmd_attn_schedule(kind, _ptr32(cu), len(cu) - 1, q_heads, kv_heads, num_queues, None, 0,
+                                   ctypes.byref(n)))
+    out = np.zeros((n.value, 4), dtype=np.int32)
+    if n.value:
+        _check(lib.hspmd_attn_schedule(kind, _ptr32(cu), len(cu) - 1, q_heads, kv_heads, num_queues,
+                                       out.ctypes.data_as(ctypes.POINTER(WorkItem)), n.value, ctypes.byref(n)))
+    return out
+
+
+class Plan:
+    """Device-resident work lists for one pack and one local head configuration."""
+
+    def __init__(self, cu_seqlens: Sequence[int], q_heads: int, kv_heads: int, head_dim: int, stream: int = 0):
+        lib = load_library()
+        cu = _i32(cu_seqlens)
+        handle = ctypes.c_void_p(None)
+        _check(lib.hspmd_attn_plan_create(_ptr32(cu), len(cu) - 1, q_heads, kv_heads, head_dim,
+                                          ctypes.c_void_p(stream), ctypes.byref(handle)))
+        self._h = handle
+        self.q_heads, self.kv_heads, self.head_dim = q_heads, kv_heads, head_dim
+        self.total_tokens = int(lib.hspmd_attn_plan_total_tokens(handle))
+
+    @property
+    def handle(self) -> ctypes.c_void_p:
+        if self._h is None:
+            raise HspmdError(1, "plan already destroyed")
+        return self._h
+
+    def num_items(self, kind: int) -> int:
+        return int(load_library().hspmd_attn_plan_num_items(self.handle, kind))
+
+    def bwd_workspace_bytes(self) -> int:
+        return int(load_library().hspmd_attn_bwd_workspace_bytes(self.handle))
+
+    def destroy(self) -> None:
+        if self._h is not None:
+            h, self._h = self._h, None
+            _check(load_library().hspmd_attn_plan_destroy(h))
+
+    def __del__(self):
+        try:
+            self.destroy()
+        except Exception:
+            pass
+
+
+def _dev_ptr(t) -> ctypes.c_void_p:
+    return ctypes.c_void_p(t.data_ptr())
+
+
+def _stream_handle(stream) -> ctypes.c_void_p:
+    if stream is None:
+        import torch
+        stream = torch.cuda.current_stream()
+    return ctypes.c_void_p(stream.cuda_stream if hasattr(stream, "cuda_stream") else int(stream))
+
+
+def attn_varlen_fwd(plan: Plan, q, k, v, o, lse, softmax_scale: float = 0.0, stream=None) -> None:
+    """q [T,Hq,d] / k,v [T,Hkv,d] bf16 device tensors (token stride = stride(0), unit inner strides);
+    o bf16 [T,Hq,d] contiguous and lse fp32 [Hq,T] are written."""
+    lib = load_library()
+    _check(lib.hspmd_attn_varlen_fwd(plan.handle, _dev_ptr(q), _dev_ptr(k), _dev_ptr(v),
+                                     q.stride(0) if q.dim() == 3 and q.shape[0] > 1 else plan.q_heads * plan.head_dim,
+                                     k.stride(0) if k.dim() == 3 and k.shape[0] > 1 else plan.kv_heads * plan.head_dim,
+                                     float(softmax_scale), _dev_ptr(o), _dev_ptr(lse), _stream_handle(stream)))
+
+
+def attn_varlen_bwd(plan: Plan, q, k, v, o, lse, d_o, dq, dk, dv, workspace, softmax_scale: float = 0.0,
+                    grad_dtype: int = GRAD_BF16, stream=None) -> None:
+    """dq/dk/dv (bf16 or fp32 according to grad_dtype) are fully overwritten; workspace is any device
+    tensor of at least plan.bwd_workspace_bytes() bytes."""
+    lib = load_library()
+    _check(lib.hspmd_attn_varlen_bwd(plan.handle, _dev_ptr(q), _dev_ptr(k), _dev_ptr(v), _dev_ptr(o), _dev_ptr(lse),
+                                     _dev_ptr(d_o),
+                                     q.stride(0) if q.dim() == 3 and q.shape[0] > 1 else plan.q_heads * plan.head_dim,
+                                     k.stride(0) if k.dim() == 3 and k.shape[0] > 1 else plan.kv_heads * plan.head_dim,
+                                     float(softmax_scale), _dev_ptr(dq), _dev_ptr(dk), _dev_ptr(dv), int(grad_dtype),
+                                     _dev_ptr(workspace), workspace.numel() * workspace.element_size(),
+                                     _stream_handle(stream)))

@@ -1,0 +1,148 @@
+// Device-side building blocks shared by the forward and backward kernels (gfx950 only).
+//
+// Register layouts of v_mfma_f32_32x32x16_bf16 (D = A * B + C, A is 32 x 16, B is 16 x 32), lane l:
+//   A operand: row  l % 32, k = 8 * (l / 32) .. + 7          (8 bf16 in 4 VGPRs)
+//   B operand: col  l % 32, k = 8 * (l / 32) .. + 7
+//   C / D    : col  l % 32, register i holds row 8 * (i / 4) + 4 * (l / 32) + i % 4   (16 fp32)
+// Every kernel here computes transposed products (keys or head-dim along the rows, the wave's
+// own 32 queries -- or keys, in the dK/dV pass -- along the columns), so that
+//   * one lane owns one query (key): row max / row sum are in-lane reductions plus ONE exchange
+//     with lane l ^ 32, and the per-row scalars (max, sum, LSE, D) are plain lane scalars;
+//   * an accumulator fragment, converted to bf16, is directly the B operand of the next
+//     product: registers 8t .. 8t+7 of a block hold the k-slice {16t + 8*(ii/4) + 4*(l/32) + ii%4}.
+//     A contraction does not care about the order of k as long as A uses the same order, so the
+//     A operand of that product is fetched with the matching permutation.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace hspmd {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+typedef __attribute__((ext_vector_type(4))) short s16x4;
+typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
+typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
+
+constexpr int kThreads = 256;   // 4 waves of 64
+constexpr float kLog2e = 1.4426950408889634f;
+constexpr float kLn2 = 0.6931471805599453f;
+
+// ---- LDS tiles --------------------------------------------------------------------------
+// A tile is ROWS x D bf16, row pitch D*2 bytes, no padding.  16-byte chunks of a row are
+// XOR-swizzled with a function of the row so that both access patterns below are free of
+// bank conflicts (64 banks x 4 B):
+//   * 16 lanes reading the same logical chunk of 16 consecutive rows (MFMA operand whose k
+//     runs along the row), and
+//   * the transpose read, where a 32-lane half reads 64 contiguous bytes of each of 4
+//     consecutive rows (MFMA operand whose k runs down the rows).
+template <int D>
+__device__ __forceinline__ int swizzle(int row, int chunk) {
+    if constexpr (D == 128) {
+        return chunk ^ (((row & 3) << 2) | ((row >> 2) & 3));
+    } else {
+        return chunk ^ ((((row >> 1) & 1) << 2) | ((row >> 2) & 3));
+    }
+}
+
+// byte offset of element (row, col) inside a tile; col is a multiple of 4
+template <int D>
+__device__ __forceinline__ int tile_offset(int row, int col) {
+    return row * (D * 2) + (swizzle<D>(row, col >> 3) << 4) + ((col & 7) << 1);
+}
+
+// Global -> registers -> LDS staging of a ROWS x D tile by 256 threads, 16 B per access.
+template <int D, int ROWS>
+struct TileStage {
+    static constexpr int kChunksPerRow = D / 8;
+    static constexpr int kPerThread = ROWS * kChunksPerRow / kThreads;
+    static_assert(ROWS * kChunksPerRow % kThreads == 0, "tile must divide over the workgroup");
+    u32x4 v[kPerThread];
+
+    // rows row0 .. row0+ROWS-1 of a [seq_len, D] slab with the given token stride (elements);
+    // rows at or beyond seq_len read as zero and touch no memory.
+    __device__ __forceinline__ void load(const uint16_t* slab, int64_t stride, int row0, int seq_len, int tid) {
+#pragma unroll
+        for (int i = 0; i < kPerThread; ++i) {
+            const int id = tid + i * kThreads;
+            const int r = id / kChunksPerRow, c = id % kChunksPerRow;
+            const int row = row0 + r;
+            u32x4 z = {0u, 0u, 0u, 0u};
+            if (row < seq_len) z = *reinterpret_cast<const u32x4*>(slab + (int64_t)row * stride + c * 8);
+            v[i] = z;
+        }
+    }
+    __device__ __forceinline__ void store(char* tile, int tid) const {
+#pragma unroll
+        for (int i = 0; i < kPerThread; ++i) {
+            const int id = tid + i * kThreads;
+            const int r = id / kChunksPerRow, c = id % kChunksPerRow;
+            *reinterpret_cast<u32x4*>(tile + tile_offset<D>(r, c * 8)) = v[i];
+        }
+    }
+};
+
+// A operand whose k runs along the tile's rows' columns: 8 consecutive elements of one row.
+//   rows: 32-row block `rb`; k-step kk covers columns 16*kk .. 16*kk+15
+template <int D>
+__device__ __forceinline__ bf16x8 read_rowmajor_frag(const char* tile, int rb, int kk, int lane) {
+    const int row = rb * 32 + (lane & 31);
+    return *reinterpret_cast<const bf16x8*>(tile + tile_offset<D>(row, kk * 16 + ((lane >> 5) << 3)));
+}
+
+// ds_read_b64_tr_b16: within each group of 16 lanes, lane 4*i + c supplies the address of 4
+// consecutive 16-bit elements (row i, columns 4c .. 4c+3 of a 4 x 16 block); lane n of the group
+// receives column n of that block, i.e. elements (0,n), (1,n), (2,n), (3,n).
+__device__ __forceinline__ s16x4 lds_transpose_read(const char* p) {
+    return __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+        (__attribute__((address_space(3))) s16x4*)(uintptr_t)(p));
+}
+
+// A operand whose k runs DOWN the tile's rows (the tile is used transposed):
+//   result row (MFMA M index) = column 32*cb + lane%32 of the tile,
+//   k = the 16 tile rows 16*t .. 16*t+15 in the order of an accumulator fragment
+//       (lane half hh gets rows 16t + 4hh + {0..3} and 16t + 8 + 4hh + {0..3}).
+template <int D>
+__device__ __forceinline__ bf16x8 read_transposed_frag(const char* tile, int cb, int t, int lane) {
+    const int c16 = lane & 15;
+    const int col = cb * 32 + (((lane >> 4) & 1) << 4) + ((c16 & 3) << 2);
+    const int row = t * 16 + ((lane >> 5) << 2) + (c16 >> 2);
+    const s16x4 lo = lds_transpose_read(tile + tile_offset<D>(row, col));
+    const s16x4 hi = lds_transpose_read(tile + tile_offset<D>(row + 8, col));
+    union { struct { s16x4 a, b; } s; bf16x8 v; } u;
+    u.s.a = lo;
+    u.s.b = hi;
+    return u.v;
+}
+
+__device__ __forceinline__ f32x16 mfma(bf16x8 a, bf16x8 b, f32x16 c) {
+    return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
+}
+
+// value held by lane l ^ 32 (the lane that owns the other half of this lane's column)
+__device__ __forceinline__ float partner32(float x) { return __shfl_xor(x, 32, 64); }
+
+__device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {
+    bf16x2 p = {(__bf16)lo, (__bf16)hi};
+    return *reinterpret_cast<uint32_t*>(&p);
+}
+
+// registers 8*tt .. 8*tt+7 of an accumulator block as a bf16 B operand
+__device__ __forceinline__ bf16x8 frag_to_bf16(const f32x16& c, int tt) {
+    union { u32x4 u; bf16x8 v; } r;
+    r.u[0] = pack_bf16(c[8 * tt + 0], c[8 * tt + 1]);
+    r.u[1] = pack_bf16(c[8 * tt + 2], c[8 * tt + 3]);
+    r.u[2] = pack_bf16(c[8 * tt + 4], c[8 * tt + 5]);
+    r.u[3] = pack_bf16(c[8 * tt + 6], c[8 * tt + 7]);
+    return r.v;
+}
+
+// row (MFMA M index within a 32-block) held in accumulator register i by this lane
+__device__ __forceinline__ int acc_row(int i, int lane) { return ((i >> 2) << 3) + ((lane >> 5) << 2) + (i & 3); }
+
+__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+
+}  // namespace hspmd

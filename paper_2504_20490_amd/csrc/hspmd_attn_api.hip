@@ -1,0 +1,250 @@
+// C-ABI entry points of libhspmd_attn: argument validation, plan management, launches.
+#include <hip/hip_runtime.h>
+
+#include <cmath>
+#include <cstdio>
+#include <cstring>
+#include <limits>
+#include <new>
+#include <string>
+#include <vector>
+
+#include "../../include/hspmd_attn.h"
+#include "kernels.hpp"
+#include "schedule.hpp"
+
+namespace {
+
+thread_local std::string g_last_error;
+
+hspmd_status fail(hspmd_status code, const std::string& what) {
+    g_last_error = what;
+    return code;
+}
+
+hspmd_status fail_hip(hipError_t e, const char* where) {
+    g_last_error = std::string(where) + ": " + hipGetErrorString(e);
+    return HSPMD_ERR_HIP;
+}
+
+bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+}  // namespace
+
+struct hspmd_attn_plan {
+    int32_t num_seqs = 0;
+    int32_t q_heads = 0, kv_heads = 0, head_dim = 0;
+    int64_t total_tokens = 0;
+    int64_t count[3] = {0, 0, 0};
+    hspmd_work_item* items[3] = {nullptr, nullptr, nullptr};   // device
+};
+
+extern "C" {
+
+const char* hspmd_last_error(void) { return g_last_error.c_str(); }
+
+int32_t hspmd_attn_tile_rows(hspmd_list_kind kind) {
+    return kind == HSPMD_LIST_DKV ? hspmd::kDkvKTile : hspmd::kFwdQTile;
+}
+
+hspmd_status hspmd_build_cu_seqlens(const int32_t* lengths, int32_t num_seqs, int32_t* cu_seqlens,
+                                    int32_t* max_seqlen, int64_t* total_tokens) {
+    if (num_seqs < 0) return fail(HSPMD_ERR_INVALID_ARG, "num_seqs is negative");
+    if (!cu_seqlens || (!lengths && num_seqs > 0)) return fail(HSPMD_ERR_INVALID_ARG, "null pointer");
+    int64_t running = 0;
+    int32_t longest = 0;
+    cu_seqlens[0] = 0;
+    for (int32_t i = 0; i < num_seqs; ++i) {
+        if (lengths[i] < 0) return fail(HSPMD_ERR_INVALID_ARG, "negative sequence length");
+        running += lengths[i];
+        if (running > std::numeric_limits<int32_t>::max())
+            return fail(HSPMD_ERR_INVALID_ARG, "total token count exceeds INT32_MAX");
+        cu_seqlens[i + 1] = (int32_t)running;
+        if (lengths[i] > longest) longest = lengths[i];
+    }
+    if (max_seqlen) *max_seqlen = longest;
+    if (total_tokens) *total_tokens = running;
+    return HSPMD_OK;
+}
+
+hspmd_status hspmd_attn_schedule(hspmd_list_kind kind, const int32_t* cu_seqlens, int32_t num_seqs,
+                                 int32_t local_q_heads, int32_t local_kv_heads, int32_t num_queues,
+                                 hspmd_work_item* items, int64_t capacity, int64_t* count) {
+    if (kind != HSPMD_LIST_FWD && kind != HSPMD_LIST_DQ && kind != HSPMD_LIST_DKV)
+        return fail(HSPMD_ERR_INVALID_ARG, "unknown list kind");
+    if (!count) return fail(HSPMD_ERR_INVALID_ARG, "count is NULL");
+    if (num_queues < 1) return fail(HSPMD_ERR_INVALID_ARG, "num_queues must be >= 1");
+    if (capacity < 0 || (capacity > 0 && !items)) return fail(HSPMD_ERR_INVALID_ARG, "items is NULL");
+    const std::string why = hspmd::check_pack(cu_seqlens, num_seqs, local_q_heads, local_kv_heads);
+    if (!why.empty()) return fail(HSPMD_ERR_INVALID_ARG, why);
+    std::vector<hspmd_work_item> list;
+    try {
+        list = hspmd::build_work_list(kind, cu_seqlens, num_seqs, local_q_heads, local_kv_heads, num_queues);
+    } catch (const std::bad_alloc&) {
+        return fail(HSPMD_ERR_INVALID_ARG, "out of host memory while building the work list");
+    }
+    *count = (int64_t)list.size();
+    if (capacity == 0) return HSPMD_OK;
+    if ((int64_t)list.size() > capacity) return fail(HSPMD_ERR_INVALID_ARG, "items buffer too small");
+    if (!list.empty()) std::memcpy(items, list.data(), list.size() * sizeof(hspmd_work_item));
+    return HSPMD_OK;
+}
+
+hspmd_status hspmd_attn_plan_create(const int32_t* cu_seqlens_host, int32_t num_seqs, int32_t local_q_heads,
+                                    int32_t local_kv_heads, int32_t head_dim, void* stream,
+                                    hspmd_attn_plan** out) {
+    if (!out) return fail(HSPMD_ERR_INVALID_ARG, "out is NULL");
+    *out = nullptr;
+    const std::string why = hspmd::check_pack(cu_seqlens_host, num_seqs, local_q_heads, local_kv_heads);
+    if (!why.empty()) return fail(HSPMD_ERR_INVALID_ARG, why);
+    if (head_dim != 64 && head_dim != 128) return fail(HSPMD_ERR_UNSUPPORTED, "head_dim must be 64 or 128");
+    hspmd_attn_plan* plan = new (std::nothrow) hspmd_attn_plan();
+    if (!plan) return fail(HSPMD_ERR_INVALID_ARG, "out of host memory");
+    plan->num_seqs = num_seqs;
+    plan->q_heads = local_q_heads;
+    plan->kv_heads = local_kv_heads;
+    plan->head_dim = head_dim;
+    plan->total_tokens = cu_seqlens_host[num_seqs];
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    for (int kind = 0; kind < 3; ++kind) {
+        std::vector<hspmd_work_item> list;
+        try {
+            list = hspmd::build_work_list((hspmd_list_kind)kind, cu_seqlens_host, num_seqs, local_q_heads,
+                                          local_kv_heads, hspmd::kNumXcd);
+        } catch (const std::bad_alloc&) {
+            hspmd_attn_plan_destroy(plan);
+            return fail(HSPMD_ERR_INVALID_ARG, "out of host memory while building the work list");
+        }
+        plan->count[kind] = (int64_t)list.size();
+        if (list.empty()) continue;
+        const size_t bytes = list.size() * sizeof(hspmd_work_item);
+        hipError_t e = hipMalloc(reinterpret_cast<void**>(&plan->items[kind]), bytes);
+        if (e != hipSuccess) {
+            hspmd_attn_plan_destroy(plan);
+            return fail_hip(e, "hipMalloc(work list)");
+        }
+        e = hipMemcpyAsync(plan->items[kind], list.data(), bytes, hipMemcpyHostToDevice, s);
+        if (e == hipSuccess) e = hipStreamSynchronize(s);   // `list` dies at the end of this iteration
+        if (e != hipSuccess) {
+            hspmd_attn_plan_destroy(plan);
+            return fail_hip(e, "hipMemcpyAsync(work list)");
+        }
+    }
+    *out = plan;
+    return HSPMD_OK;
+}
+
+hspmd_status hspmd_attn_plan_destroy(hspmd_attn_plan* plan) {
+    if (!plan) return HSPMD_OK;
+    hspmd_status rc = HSPMD_OK;
+    for (int kind = 0; kind < 3; ++kind) {
+        if (plan->items[kind]) {
+            const hipError_t e = hipFree(plan->items[kind]);
+            if (e != hipSuccess) rc = fail_hip(e, "hipFree(work list)");
+        }
+    }
+    delete plan;
+    return rc;
+}
+
+int64_t hspmd_attn_plan_total_tokens(const hspmd_attn_plan* plan) { return plan ? plan->total_tokens : -1; }
+
+int64_t hspmd_attn_plan_num_items(const hspmd_attn_plan* plan, hspmd_list_kind kind) {
+    if (!plan || kind < 0 || kind > 2) return -1;
+    return plan->count[kind];
+}
+
+size_t hspmd_attn_bwd_workspace_bytes(const hspmd_attn_plan* plan) {
+    if (!plan) return 0;
+    return (size_t)plan->q_heads * (size_t)plan->total_tokens * sizeof(float);
+}
+
+static hspmd_status check_strides(const hspmd_attn_plan* plan, int64_t q_token_stride, int64_t kv_token_stride) {
+    if (q_token_stride < (int64_t)plan->q_heads * plan->head_dim || q_token_stride % 8 != 0)
+        return fail(HSPMD_ERR_INVALID_ARG, "q_token_stride must be a multiple of 8 and >= local_q_heads*head_dim");
+    if (kv_token_stride < (int64_t)plan->kv_heads * plan->head_dim || kv_token_stride % 8 != 0)
+        return fail(HSPMD_ERR_INVALID_ARG, "kv_token_stride must be a multiple of 8 and >= local_kv_heads*head_dim");
+    return HSPMD_OK;
+}
+
+hspmd_status hspmd_attn_varlen_fwd(const hspmd_attn_plan* plan, const void* q, const void* k, const void* v,
+                                   int64_t q_token_stride, int64_t kv_token_stride, float softmax_scale,
+                                   void* o, float* lse, void* stream) {
+    if (!plan) return fail(HSPMD_ERR_INVALID_ARG, "plan is NULL");
+    if (plan->total_tokens == 0) return HSPMD_OK;
+    if (!q || !k || !v || !o || !lse) return fail(HSPMD_ERR_INVALID_ARG, "null tensor pointer");
+    if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(o))
+        return fail(HSPMD_ERR_INVALID_ARG, "q, k, v, o must be 16-byte aligned");
+    if (hspmd_status rc = check_strides(plan, q_token_stride, kv_token_stride)) return rc;
+    if (!(softmax_scale <= 0.f) && !std::isfinite(softmax_scale)) return fail(HSPMD_ERR_INVALID_ARG, "softmax_scale is not finite");
+    const float scale = softmax_scale > 0.f ? softmax_scale : 1.0f / std::sqrt((float)plan->head_dim);
+    hspmd::FwdParams p{};
+    p.q = static_cast<const uint16_t*>(q);
+    p.k = static_cast<const uint16_t*>(k);
+    p.v = static_cast<const uint16_t*>(v);
+    p.o = static_cast<uint16_t*>(o);
+    p.lse = lse;
+    p.items = plan->items[HSPMD_LIST_FWD];
+    p.q_stride = q_token_stride;
+    p.kv_stride = kv_token_stride;
+    p.total_tokens = plan->total_tokens;
+    p.q_heads = plan->q_heads;
+    p.group = plan->q_heads / plan->kv_heads;
+    p.scale_log2 = scale * 1.4426950408889634f;
+    const hipError_t e = hspmd::launch_fwd(p, plan->head_dim, plan->count[HSPMD_LIST_FWD], static_cast<hipStream_t>(stream));
+    if (e != hipSuccess) return fail_hip(e, "forward launch");
+    return HSPMD_OK;
+}
+
+hspmd_status hspmd_attn_varlen_bwd(const hspmd_attn_plan* plan, const void* q, const void* k, const void* v,
+                                   const void* o, const float* lse, const void* d_o,
+                                   int64_t q_token_stride, int64_t kv_token_stride, float softmax_scale,
+                                   void* dq, void* dk, void* dv, hspmd_grad_dtype grad_dtype,
+                                   void* workspace, size_t workspace_bytes, void* stream) {
+    if (!plan) return fail(HSPMD_ERR_INVALID_ARG, "plan is NULL");
+    if (grad_dtype != HSPMD_GRAD_BF16 && grad_dtype != HSPMD_GRAD_F32)
+        return fail(HSPMD_ERR_UNSUPPORTED, "grad_dtype must be HSPMD_GRAD_BF16 or HSPMD_GRAD_F32");
+    if (plan->total_tokens == 0) return HSPMD_OK;
+    if (!q || !k || !v || !o || !lse || !d_o || !dq || !dk || !dv || !workspace)
+        return fail(HSPMD_ERR_INVALID_ARG, "null tensor pointer");
+    if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(o) || !aligned16(d_o) || !aligned16(dq) ||
+        !aligned16(dk) || !aligned16(dv) || !aligned16(workspace))
+        return fail(HSPMD_ERR_INVALID_ARG, "tensors and workspace must be 16-byte aligned");
+    if (hspmd_status rc = check_strides(plan, q_token_stride, kv_token_stride)) return rc;
+    if (workspace_bytes < hspmd_attn_bwd_workspace_bytes(plan))
+        return fail(HSPMD_ERR_WORKSPACE_TOO_SMALL, "workspace smaller than hspmd_attn_bwd_workspace_bytes(plan)");
+    if (!(softmax_scale <= 0.f) && !std::isfinite(softmax_scale)) return fail(HSPMD_ERR_INVALID_ARG, "softmax_scale is not finite");
+    const float scale = softmax_scale > 0.f ? softmax_scale : 1.0f / std::sqrt((float)plan->head_dim);
+    hspmd::BwdParams p{};
+    p.q = static_cast<const uint16_t*>(q);
+    p.k = static_cast<const uint16_t*>(k);
+    p.v = static_cast<const uint16_t*>(v);
+    p.o = static_cast<const uint16_t*>(o);
+    p.d_o = static_cast<const uint16_t*>(d_o);
+    p.lse = lse;
+    p.dsum = static_cast<float*>(workspace);
+    p.dq = dq;
+    p.dk = dk;
+    p.dv = dv;
+    p.q_stride = q_token_stride;
+    p.kv_stride = kv_token_stride;
+    p.total_tokens = plan->total_tokens;
+    p.q_heads = plan->q_heads;
+    p.kv_heads = plan->kv_heads;
+    p.group = plan->q_heads / plan->kv_heads;
+    p.grad_f32 = grad_dtype == HSPMD_GRAD_F32 ? 1 : 0;
+    p.scale = scale;
+    p.scale_log2 = scale * 1.4426950408889634f;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    hipError_t e = hspmd::launch_bwd_dsum(p, plan->head_dim, s);
+    if (e != hipSuccess) return fail_hip(e, "backward D launch");
+    p.items = plan->items[HSPMD_LIST_DQ];
+    e = hspmd::launch_bwd_dq(p, plan->head_dim, plan->count[HSPMD_LIST_DQ], s);
+    if (e != hipSuccess) return fail_hip(e, "backward dQ launch");
+    p.items = plan->items[HSPMD_LIST_DKV];
+    e = hspmd::launch_bwd_dkv(p, plan->head_dim, plan->count[HSPMD_LIST_DKV], s);
+    if (e != hipSuccess) return fail_hip(e, "backward dK/dV launch");
+    return HSPMD_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,48 @@
+// Kernel parameter blocks and host-callable launchers (internal to the library).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "../../include/hspmd_attn.h"
+
+namespace hspmd {
+
+struct FwdParams {
+    const uint16_t* q;
+    const uint16_t* k;
+    const uint16_t* v;
+    uint16_t* o;
+    float* lse;
+    const hspmd_work_item* items;
+    int64_t q_stride, kv_stride;   // token strides in elements
+    int64_t total_tokens;
+    int32_t q_heads, group;
+    float scale_log2;              // softmax_scale * log2(e)
+};
+
+struct BwdParams {
+    const uint16_t* q;
+    const uint16_t* k;
+    const uint16_t* v;
+    const uint16_t* o;
+    const uint16_t* d_o;
+    const float* lse;
+    float* dsum;                   // D[Hq, T] = rowsum(dO * O), fp32 workspace
+    void* dq;
+    void* dk;
+    void* dv;
+    const hspmd_work_item* items;
+    int64_t q_stride, kv_stride;
+    int64_t total_tokens;
+    int32_t q_heads, kv_heads, group;
+    int32_t grad_f32;              // 1: gradients are fp32, 0: bf16
+    float scale;                   // softmax_scale
+    float scale_log2;              // softmax_scale * log2(e)
+};
+
+hipError_t launch_fwd(const FwdParams& p, int head_dim, int64_t num_items, hipStream_t stream);
+hipError_t launch_bwd_dsum(const BwdParams& p, int head_dim, hipStream_t stream);
+hipError_t launch_bwd_dq(const BwdParams& p, int head_dim, int64_t num_items, hipStream_t stream);
+hipError_t launch_bwd_dkv(const BwdParams& p, int head_dim, int64_t num_items, hipStream_t stream);
+
+}  // namespace hspmd

@@ -1,0 +1,28 @@
+// Host-side construction of the cost-sorted work lists (no GPU code in here).
+#pragma once
+#include <cstdint>
+#include <string>
+#include <vector>
+
+#include "../../include/hspmd_attn.h"
+
+namespace hspmd {
+
+// Tile geometry shared by the scheduler and the kernels.
+constexpr int kFwdQTile = 128;   // q rows per forward / dQ work item (4 waves x 32 rows)
+constexpr int kFwdKTile = 64;    // keys per inner step of the forward / dQ kernels
+constexpr int kDkvKTile = 128;   // keys per dK/dV work item (4 waves x 32 keys)
+constexpr int kDkvQTile = 64;    // q rows per inner step of the dK/dV kernel
+constexpr int kNumXcd = 8;       // XCDs of an MI355X: workgroup p lands on XCD p % 8
+
+// Validates cu_seqlens / head counts; returns an empty string when fine.
+std::string check_pack(const int32_t* cu, int32_t num_seqs, int32_t hq, int32_t hkv);
+
+// Cost (number of inner steps) of one item.
+int64_t item_cost(hspmd_list_kind kind, int32_t seq_len, int32_t tile, int32_t group);
+
+// Builds the launch-ordered list (see hspmd_attn_schedule in the public header).
+std::vector<hspmd_work_item> build_work_list(hspmd_list_kind kind, const int32_t* cu, int32_t num_seqs,
+                                             int32_t hq, int32_t hkv, int32_t num_queues);
+
+}  // namespace hspmd
