@@ -1,0 +1,202 @@
+#!/usr/bin/env python3
+"""Benchmark of libhspmd_attn on one MI355X.
+
+One step = one pass of the whole hot path over one pack: packed-sequence offsets and the
+cost-sorted work lists (host, built from the length list), forward, and backward (D, dQ pass,
+dK/dV pass).  Inputs are resident in HBM before the timed region starts.  The workload is the
+32768-token log-normal pack on an uneven head share (24 of 40 heads, head_dim 128), the
+configuration the headline metric is quoted on.
+
+Prints ONE JSON line.  `value` is useful causal TFLOP/s for forward+backward, with
+forward FLOPs = 2 * sum L(L+1) * d * heads and backward counted as 2.5x forward.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import math
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA peak (no sparsity)
+
+# GEMMs (2*d flops per visible (query, key) pair and head each) that each kernel's pass needs
+GEMMS = {"fwd_kernel": 2, "bwd_dq_kernel": 3, "bwd_dkv_kernel": 4}
+
+
+def read_traffic(kernel: str, workload: str):
+    """HBM bytes per launch from the committed rocprofv3 counter summary, if there is one."""
+    path = os.path.join(ROOT, "profiles", f"{kernel}_{workload}_hbm_traffic.txt")
+    try:
+        with open(path) as f:
+            for line in f:
+                if line.startswith("traffic_bytes_per_launch:"):
+                    return float(line.split(":", 1)[1])
+    except OSError:
+        pass
+    return None
+
+
+def cpu_baseline(cfg, lengths, q, k, v, do):
+    """The fp64 oracle, as it stands, on a bounded sample of the same pack: whole sequences of the
+    pack (shortest first, up to a pair budget) and eight KV groups, forward + backward."""
+    import numpy as np
+    import hspmd_workloads as w
+    import oracle
+
+    cu = np.concatenate([[0], np.cumsum(lengths)])
+    budget = 7.0e7          # visible (query, key) pairs per head in the sample: ~10-20 s of CPU work
+    order = sorted(range(len(lengths)), key=lambda i: lengths[i])
+    chosen, pairs = [], 0
+    for i in order:
+        p = lengths[i] * (lengths[i] + 1) // 2
+        if chosen and pairs + p > budget:
+            break
+        chosen.append(i)
+        pairs += p
+    heads = min(cfg.q_heads, 8 * (cfg.q_heads // cfg.kv_heads))
+    kvh = heads // (cfg.q_heads // cfg.kv_heads)
+    tok = np.concatenate([np.arange(cu[i], cu[i + 1]) for i in chosen])
+    f64 = lambda bits: w.bits_to_f32(bits).astype(np.float64)
+    qs, ks, vs, dos = f64(q[tok][:, :heads]), f64(k[tok][:, :kvh]), f64(v[tok][:, :kvh]), f64(do[tok][:, :heads])
+    sl = [lengths[i] for i in chosen]
+    s = 1.0 / math.sqrt(cfg.head_dim)
+    t0 = time.perf_counter()
+    oracle.attn_fwd(qs, ks, vs, sl, s)
+    oracle.attn_bwd(qs, ks, vs, dos, sl, s)
+    dt = time.perf_counter() - t0
+    flops = 3.5 * w.fwd_flops(sl, heads, cfg.head_dim)
+    return {"value": flops / dt / 1e12, "unit": "TFLOP/s", "cores": oracle.num_threads(), "kind": "oracle",
+            "sample": f"sequences of lengths {sl} of the same pack, {heads} q heads / {kvh} kv heads, "
+                      f"fwd+bwd in fp64, {dt:.1f} s"}
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="C4", help="C1..C5 (default: the 32768-token asymmetric-head pack)")
+    ap.add_argument("--grad-dtype", default="f32", choices=["f32", "bf16"])
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py measures one GPU's share of the batch on one GPU; --gpus above 1 is not part of this "
+              "build (no collectives, no sharding across GPUs).", file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+    import hspmd_workloads as w
+    import paper_2504_20490_amd as A
+
+    if not torch.cuda.is_available():
+        print("bench.py needs a GPU", file=sys.stderr)
+        return 2
+    A.load_library()     # no fallback: raises if the HIP library is missing
+
+    cfg = w.config_by_name(args.workload)
+    lengths, q, k, v, do = w.make_inputs(cfg)
+    T, hq, hkv, d = cfg.total_tokens, cfg.q_heads, cfg.kv_heads, cfg.head_dim
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+
+    def bf(bits):
+        return torch.from_numpy(bits.view(np.int16)).view(torch.bfloat16).to(dev)
+
+    tq, tk, tv, tdo = bf(q), bf(k), bf(v), bf(do)
+    o = torch.empty_like(tq)
+    lse = torch.empty(hq, T, dtype=torch.float32, device=dev)
+    grad = A.GRAD_F32 if args.grad_dtype == "f32" else A.GRAD_BF16
+    gd = torch.float32 if grad == A.GRAD_F32 else torch.bfloat16
+    dq = torch.empty(T, hq, d, dtype=gd, device=dev)
+    dk = torch.empty(T, hkv, d, dtype=gd, device=dev)
+    dv = torch.empty_like(dk)
+    ws = torch.empty(hq * T * 4 + 16, dtype=torch.uint8, device=dev)
+    stream = torch.cuda.current_stream()
+
+    def step():
+        cu, _, _ = A.build_cu_seqlens(lengths)                 # packed offsets
+        plan = A.Plan(cu, hq, hkv, d, stream.cuda_stream)       # cost-sorted work lists
+        A.attn_varlen_fwd(plan, tq, tk, tv, o, lse, stream=stream)
+        A.attn_varlen_bwd(plan, tq, tk, tv, o, lse, tdo, dq, dk, dv, ws, grad_dtype=grad, stream=stream)
+        return plan
+
+    plans = []
+    for _ in range(args.warmup):
+        plans.append(step())
+    torch.cuda.synchronize()
+    for p in plans:
+        p.destroy()
+    plans = []
+    A.profile_enable(True)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        plans.append(step())
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    A.profile_enable(False)
+    prof = A.profile_read()
+    for p in plans:
+        p.destroy()
+
+    # host-only share of a step (offsets + work lists + upload), timed separately for the record
+    t1 = time.perf_counter()
+    for _ in range(5):
+        cu, _, _ = A.build_cu_seqlens(lengths)
+        A.Plan(cu, hq, hkv, d, stream.cuda_stream).destroy()
+    plan_ms = (time.perf_counter() - t1) / 5 * 1e3
+
+    ms_per_step = elapsed / args.steps * 1e3
+    fwd = w.fwd_flops(lengths, hq, d)
+    useful = 3.5 * fwd
+    tflops = useful / (ms_per_step * 1e-3) / 1e12
+    pair_flops = fwd / 2.0          # one GEMM over the visible pairs: 2*d flops per pair and head
+
+    kern = {name: (ms / n if n else 0.0) for name, (ms, n) in prof.items()}
+    dominant = max(GEMMS, key=lambda name: kern.get(name, 0.0))
+    dom_ms = kern[dominant]
+    achieved = GEMMS[dominant] * pair_flops / (dom_ms * 1e-3) / 1e12 if dom_ms > 0 else 0.0
+
+    out = {
+        "metric": "varlen causal attn fwd+bwd TFLOP/s and % bf16 MFMA peak, 32k-token mix",
+        "value": round(tflops, 2),
+        "unit": "TFLOP/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "bf16",
+        "data": "synthetic",
+        "config": {"workload": f"{cfg.name}: {cfg.note}", "total_tokens": T, "q_heads": hq, "kv_heads": hkv,
+                   "head_dim": d, "num_seqs": len(lengths), "lengths": lengths,
+                   "sum_L_Lplus1": 2 * w.causal_pairs(lengths), "fwd_useful_flops": fwd,
+                   "grad_dtype": args.grad_dtype,
+                   "step": "build_cu_seqlens + work lists + fwd + bwd(D, dQ, dK/dV)"},
+        "pct_of_bf16_mfma_peak": round(100.0 * tflops / PEAK_BF16_TFLOPS, 2),
+        "kernel_ms": {name: round(ms, 4) for name, ms in kern.items()},
+        "host_plan_ms": round(plan_ms, 4),
+        "roofline": {"bound": "mfma", "kernel": dominant, "achieved": round(achieved, 2), "peak": PEAK_BF16_TFLOPS,
+                     "unit": "TFLOP/s", "frac": round(achieved / PEAK_BF16_TFLOPS, 4),
+                     "traffic": read_traffic(dominant, cfg.name.split("_")[0]),
+                     "flops_per_launch": GEMMS[dominant] * pair_flops,
+                     "note": f"{GEMMS[dominant]} GEMMs over the visible pairs; avg of {prof[dominant][1]} launches "
+                             "timed with HIP events on the launch stream"},
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(cfg, lengths, q, k, v, do)
+    print(json.dumps(out))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -172,6 +172,22 @@ hspmd_status hspmd_attn_varlen_bwd(const hspmd_attn_plan* plan, const void* q, c
                                    void* dq, void* dk, void* dv, hspmd_grad_dtype grad_dtype,
                                    void* workspace, size_t workspace_bytes, void* stream);
 
+/*
+ * Per-kernel timing for measurement (the evidence the kernels are tuned against; not part of
+ * the paper's method).  While enabled, every kernel launch made by forward / backward on the
+ * calling process is bracketed by a pair of HIP events recorded on the launch stream.
+ * hspmd_profile_read waits for the recorded events, adds each kernel's elapsed time and launch
+ * count to the caller's arrays and forgets the records.
+ *   kernel index: 0 forward, 1 backward D = rowsum(dO*O), 2 backward dQ pass, 3 backward dK/dV pass
+ *   ms, launches  host, [HSPMD_NUM_KERNELS] each, accumulated into (the caller zeroes them)
+ * Not thread-safe: enable, launch and read from one thread.  Events are created on first use and
+ * reused; enabling allocates nothing on the device.
+ */
+#define HSPMD_NUM_KERNELS 4
+hspmd_status hspmd_profile_enable(int32_t on);
+hspmd_status hspmd_profile_read(double* ms, int64_t* launches);
+const char* hspmd_kernel_name(int32_t kernel);   /* symbol-like name, NULL if out of range */
+
 #ifdef __cplusplus
 }
 #endif

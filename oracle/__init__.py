@@ -30,6 +30,12 @@ def _load():
         lib.oracle_attn_bwd.restype = ctypes.c_int
         lib.oracle_attn_bwd.argtypes = [dp, dp, dp, dp, ip, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32,
                                         ctypes.c_int32, ctypes.c_double, dp, dp, dp]
+        lib.oracle_attn_rows.restype = ctypes.c_int
+        lib.oracle_attn_rows.argtypes = [dp, dp, dp, dp, ip, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32,
+                                         ctypes.c_int32, ctypes.c_double, ctypes.c_int32, ip, ip, dp, dp, dp]
+        lib.oracle_attn_keys.restype = ctypes.c_int
+        lib.oracle_attn_keys.argtypes = [dp, dp, dp, dp, ip, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32,
+                                         ctypes.c_int32, ctypes.c_double, ctypes.c_int32, ip, ip, dp, dp]
         lib.oracle_num_threads.restype = ctypes.c_int
         _lib = lib
     return _lib
@@ -105,3 +111,44 @@ def attn_bwd(q: np.ndarray, k: np.ndarray, v: np.ndarray, d_o: np.ndarray, lengt
     if rc != 0:
         raise RuntimeError(f"oracle_attn_bwd failed with status {rc}")
     return dq, dk, dv
+
+
+def _iptr(a: np.ndarray):
+    return a.ctypes.data_as(ctypes.POINTER(ctypes.c_int32))
+
+
+def attn_rows(q, k, v, d_o, lengths: Sequence[int], scale: float, tokens: Sequence[int], heads: Sequence[int]):
+    """Sampled query rows: for each (packed token, q head) pair returns
+    ``(o [n,d], lse [n], dq [n,d])`` without evaluating the other rows."""
+    lib = _load()
+    T, Hq, d = q.shape
+    Hkv = k.shape[1]
+    q = _as_f64(q, (T, Hq, d)); k = _as_f64(k, (T, Hkv, d)); v = _as_f64(v, (T, Hkv, d))
+    d_o = _as_f64(d_o, (T, Hq, d))
+    cu = _cu(lengths)
+    tok = np.ascontiguousarray(tokens, dtype=np.int32); hd = np.ascontiguousarray(heads, dtype=np.int32)
+    n = len(tok)
+    o = np.empty((n, d)); lse = np.empty(n); dq = np.empty((n, d))
+    rc = lib.oracle_attn_rows(_dptr(q), _dptr(k), _dptr(v), _dptr(d_o), _iptr(cu), len(lengths), Hq, Hkv, d,
+                              float(scale), n, _iptr(tok), _iptr(hd), _dptr(o), _dptr(lse), _dptr(dq))
+    if rc != 0:
+        raise RuntimeError(f"oracle_attn_rows failed with status {rc}")
+    return o, lse, dq
+
+
+def attn_keys(q, k, v, d_o, lengths: Sequence[int], scale: float, tokens: Sequence[int], kv_heads: Sequence[int]):
+    """Sampled keys: for each (packed token, kv head) pair returns ``(dk [n,d], dv [n,d])``."""
+    lib = _load()
+    T, Hq, d = q.shape
+    Hkv = k.shape[1]
+    q = _as_f64(q, (T, Hq, d)); k = _as_f64(k, (T, Hkv, d)); v = _as_f64(v, (T, Hkv, d))
+    d_o = _as_f64(d_o, (T, Hq, d))
+    cu = _cu(lengths)
+    tok = np.ascontiguousarray(tokens, dtype=np.int32); hd = np.ascontiguousarray(kv_heads, dtype=np.int32)
+    n = len(tok)
+    dk = np.empty((n, d)); dv = np.empty((n, d))
+    rc = lib.oracle_attn_keys(_dptr(q), _dptr(k), _dptr(v), _dptr(d_o), _iptr(cu), len(lengths), Hq, Hkv, d,
+                              float(scale), n, _iptr(tok), _iptr(hd), _dptr(dk), _dptr(dv))
+    if rc != 0:
+        raise RuntimeError(f"oracle_attn_keys failed with status {rc}")
+    return dk, dv

@@ -40,6 +40,11 @@
  * contiguous doubles, token-major.  lse is [Hq, T].  cu[B+1] are the packed
  * sequence offsets (cu[0] = 0, cu[B] = T).
  *
+ * oracle_attn_rows / oracle_attn_keys evaluate the same per-row and per-key
+ * routines for sampled (token, head) pairs only, so that single outputs of packs
+ * too large for a full evaluation can be checked; they are pinned by equality
+ * with the full functions.
+ *
  * Pins (tests/test_oracle_pins.py): closed forms for Q = 0, length-1
  * sequences, softmax row sums, shift invariance, packed == unpacked,
  * permutation of sequences, GQA == repeated-KV MHA, central finite
@@ -101,6 +106,80 @@ static double score_row(const double *q_row, const double *k, int64_t k_tok_stri
     return m;
 }
 
+/* One query row, forward: p[0..r] receives P_rj, o_row (may be NULL) receives O_r.
+ * kh / vh point at the row's kv head in token 0.  Returns LSE_r. */
+static double row_forward(const double *q_row, const double *kh, const double *vh, int64_t ks,
+                          int64_t t0, int32_t r, int32_t d, double scale, double *p, double *o_row) {
+    const double m = score_row(q_row, kh, ks, t0, r, d, scale, p);
+    double Z = 0.0;
+    for (int32_t j = 0; j <= r; ++j) {
+        p[j] = exp(p[j] - m);
+        Z += p[j];
+    }
+    for (int32_t j = 0; j <= r; ++j) p[j] /= Z;
+    if (o_row) {
+        for (int32_t c = 0; c < d; ++c) o_row[c] = 0.0;
+        for (int32_t j = 0; j <= r; ++j) {
+            const double *v_row = vh + (t0 + j) * ks;
+            for (int32_t c = 0; c < d; ++c) o_row[c] += p[j] * v_row[c];
+        }
+    }
+    return m + log(Z);
+}
+
+/* One query row, backward, given its P row: dp[0..r] is scratch; dq_row (may be NULL)
+ * receives dQ_r.  Returns D_r = sum_j P_rj dP_rj. */
+static double row_backward(const double *do_row, const double *kh, const double *vh, int64_t ks,
+                           int64_t t0, int32_t r, int32_t d, double scale, const double *p,
+                           double *dp, double *dq_row) {
+    double Dsum = 0.0;
+    for (int32_t j = 0; j <= r; ++j) {
+        dp[j] = dot(do_row, vh + (t0 + j) * ks, d);
+        Dsum += p[j] * dp[j];
+    }
+    if (dq_row) {
+        for (int32_t c = 0; c < d; ++c) dq_row[c] = 0.0;
+        for (int32_t j = 0; j <= r; ++j) {
+            const double ds = p[j] * (dp[j] - Dsum);
+            const double *k_row = kh + (t0 + j) * ks;
+            for (int32_t c = 0; c < d; ++c) dq_row[c] += ds * k_row[c];
+        }
+        for (int32_t c = 0; c < d; ++c) dq_row[c] *= scale;
+    }
+    return Dsum;
+}
+
+/* One key j of kv head g, backward: sums over the group's query heads and the rows r >= j.
+ * lse / Dr are indexed [head_in_group * stat_stride + (r - stat_row0)]. */
+static void key_backward(const double *q, const double *d_o, const double *k_row, const double *v_row,
+                         int64_t qs, int64_t t0, int32_t L, int32_t j, int32_t g, int32_t G, int32_t d,
+                         double scale, const double *lse, const double *Dr, int64_t stat_stride,
+                         int32_t stat_row0, double *dk_row, double *dv_row) {
+    for (int32_t c = 0; c < d; ++c) { dk_row[c] = 0.0; dv_row[c] = 0.0; }
+    for (int32_t hg = 0; hg < G; ++hg) {
+        const int32_t h = g * G + hg;
+        for (int32_t r = j; r < L; ++r) {
+            const double *q_row = q + (t0 + r) * qs + (int64_t)h * d;
+            const double *do_row = d_o + (t0 + r) * qs + (int64_t)h * d;
+            const int64_t st = (int64_t)hg * stat_stride + (r - stat_row0);
+            const double p = exp(scale * dot(q_row, k_row, d) - lse[st]);
+            const double ds = p * (dot(do_row, v_row, d) - Dr[st]);
+            for (int32_t c = 0; c < d; ++c) {
+                dv_row[c] += p * do_row[c];
+                dk_row[c] += ds * q_row[c];
+            }
+        }
+    }
+    for (int32_t c = 0; c < d; ++c) dk_row[c] *= scale;
+}
+
+static int32_t longest(const int32_t *cu, int32_t B) {
+    int32_t max_len = 0;
+    for (int32_t i = 0; i < B; ++i)
+        if (cu[i + 1] - cu[i] > max_len) max_len = cu[i + 1] - cu[i];
+    return max_len > 0 ? max_len : 1;
+}
+
 /* Forward.  o [T,Hq,d], lse [Hq,T].  probs (may be NULL): only legal with B == 1;
  * receives P for every head as [Hq, L, L] (entries above the diagonal are 0). */
 int oracle_attn_fwd(const double *q, const double *k, const double *v, const int32_t *cu,
@@ -113,15 +192,12 @@ int oracle_attn_fwd(const double *q, const double *k, const double *v, const int
     const int64_t T = cu[B];
     const int32_t G = Hq / Hkv;
     const int64_t qs = (int64_t)Hq * d, ks = (int64_t)Hkv * d;
-    int32_t max_len = 0;
-    for (int32_t i = 0; i < B; ++i)
-        if (cu[i + 1] - cu[i] > max_len) max_len = cu[i + 1] - cu[i];
-    const size_t row_len = (size_t)(max_len > 0 ? max_len : 1);
+    const size_t row_len = (size_t)longest(cu, B);
     double *scratch = (double *)malloc(sizeof(double) * row_len * (size_t)oracle_num_threads());
     if (!scratch) return ORACLE_NO_MEM;
 #pragma omp parallel
     {
-        double *s = scratch + row_len * (size_t)thread_index();
+        double *p = scratch + row_len * (size_t)thread_index();
         for (int32_t i = 0; i < B; ++i) {
             const int64_t t0 = cu[i];
             const int32_t L = cu[i + 1] - cu[i];
@@ -131,23 +207,12 @@ int oracle_attn_fwd(const double *q, const double *k, const double *v, const int
 #pragma omp for schedule(dynamic, 4) nowait
                 for (int32_t r = 0; r < L; ++r) {
                     const double *q_row = q + (t0 + r) * qs + (int64_t)h * d;
-                    const double m = score_row(q_row, kh, ks, t0, r, d, scale, s);
-                    double Z = 0.0;
-                    for (int32_t j = 0; j <= r; ++j) {
-                        s[j] = exp(s[j] - m);
-                        Z += s[j];
-                    }
                     double *o_row = o + (t0 + r) * qs + (int64_t)h * d;
-                    for (int32_t c = 0; c < d; ++c) o_row[c] = 0.0;
-                    for (int32_t j = 0; j <= r; ++j) {
-                        const double p = s[j] / Z;
-                        const double *v_row = vh + (t0 + j) * ks;
-                        for (int32_t c = 0; c < d; ++c) o_row[c] += p * v_row[c];
-                        if (probs) probs[((int64_t)h * L + r) * L + j] = p;
+                    lse[(int64_t)h * T + t0 + r] = row_forward(q_row, kh, vh, ks, t0, r, d, scale, p, o_row);
+                    if (probs) {
+                        double *dst = probs + ((int64_t)h * L + r) * L;
+                        for (int32_t j = 0; j < L; ++j) dst[j] = j <= r ? p[j] : 0.0;
                     }
-                    if (probs)
-                        for (int32_t j = r + 1; j < L; ++j) probs[((int64_t)h * L + r) * L + j] = 0.0;
-                    lse[(int64_t)h * T + t0 + r] = m + log(Z);
                 }
             }
         }
@@ -167,20 +232,17 @@ int oracle_attn_bwd(const double *q, const double *k, const double *v, const dou
     const int64_t T = cu[B];
     const int32_t G = Hq / Hkv;
     const int64_t qs = (int64_t)Hq * d, ks = (int64_t)Hkv * d;
-    int32_t max_len = 0;
-    for (int32_t i = 0; i < B; ++i)
-        if (cu[i + 1] - cu[i] > max_len) max_len = cu[i + 1] - cu[i];
     if (T == 0) return ORACLE_OK;
     /* per (head, token): LSE_r and D_r, kept for the key-major pass */
     double *lse = (double *)malloc(sizeof(double) * (size_t)Hq * (size_t)T);
     double *Dr = (double *)malloc(sizeof(double) * (size_t)Hq * (size_t)T);
-    const size_t row_len = (size_t)(max_len > 0 ? max_len : 1);
+    const size_t row_len = (size_t)longest(cu, B);
     double *scratch = (double *)malloc(sizeof(double) * 2 * row_len * (size_t)oracle_num_threads());
     if (!lse || !Dr || !scratch) { free(lse); free(Dr); free(scratch); return ORACLE_NO_MEM; }
 #pragma omp parallel
     {
-        double *s = scratch + 2 * row_len * (size_t)thread_index();
-        double *dp = s + row_len;
+        double *p = scratch + 2 * row_len * (size_t)thread_index();
+        double *dp = p + row_len;
         /* pass 1, query-major: P row, dP row, D, dS row, dQ row */
         for (int32_t i = 0; i < B; ++i) {
             const int64_t t0 = cu[i];
@@ -192,28 +254,9 @@ int oracle_attn_bwd(const double *q, const double *k, const double *v, const dou
                 for (int32_t r = 0; r < L; ++r) {
                     const double *q_row = q + (t0 + r) * qs + (int64_t)h * d;
                     const double *do_row = d_o + (t0 + r) * qs + (int64_t)h * d;
-                    const double m = score_row(q_row, kh, ks, t0, r, d, scale, s);
-                    double Z = 0.0;
-                    for (int32_t j = 0; j <= r; ++j) {
-                        s[j] = exp(s[j] - m);
-                        Z += s[j];
-                    }
-                    double Dsum = 0.0;
-                    for (int32_t j = 0; j <= r; ++j) {
-                        s[j] /= Z; /* P_rj */
-                        dp[j] = dot(do_row, vh + (t0 + j) * ks, d);
-                        Dsum += s[j] * dp[j];
-                    }
                     double *dq_row = dq + (t0 + r) * qs + (int64_t)h * d;
-                    for (int32_t c = 0; c < d; ++c) dq_row[c] = 0.0;
-                    for (int32_t j = 0; j <= r; ++j) {
-                        const double ds = s[j] * (dp[j] - Dsum);
-                        const double *k_row = kh + (t0 + j) * ks;
-                        for (int32_t c = 0; c < d; ++c) dq_row[c] += ds * k_row[c];
-                    }
-                    for (int32_t c = 0; c < d; ++c) dq_row[c] *= scale;
-                    lse[(int64_t)h * T + t0 + r] = m + log(Z);
-                    Dr[(int64_t)h * T + t0 + r] = Dsum;
+                    lse[(int64_t)h * T + t0 + r] = row_forward(q_row, kh, vh, ks, t0, r, d, scale, p, NULL);
+                    Dr[(int64_t)h * T + t0 + r] = row_backward(do_row, kh, vh, ks, t0, r, d, scale, p, dp, dq_row);
                 }
             }
         }
@@ -225,28 +268,103 @@ int oracle_attn_bwd(const double *q, const double *k, const double *v, const dou
             for (int32_t g = 0; g < Hkv; ++g) {
 #pragma omp for schedule(dynamic, 4) nowait
                 for (int32_t j = 0; j < L; ++j) {
-                    const double *k_row = k + (t0 + j) * ks + (int64_t)g * d;
-                    const double *v_row = v + (t0 + j) * ks + (int64_t)g * d;
-                    double *dk_row = dk + (t0 + j) * ks + (int64_t)g * d;
-                    double *dv_row = dv + (t0 + j) * ks + (int64_t)g * d;
-                    for (int32_t c = 0; c < d; ++c) { dk_row[c] = 0.0; dv_row[c] = 0.0; }
-                    for (int32_t h = g * G; h < (g + 1) * G; ++h) {
-                        for (int32_t r = j; r < L; ++r) {
-                            const double *q_row = q + (t0 + r) * qs + (int64_t)h * d;
-                            const double *do_row = d_o + (t0 + r) * qs + (int64_t)h * d;
-                            const double p = exp(scale * dot(q_row, k_row, d) - lse[(int64_t)h * T + t0 + r]);
-                            const double dpv = dot(do_row, v_row, d);
-                            const double ds = p * (dpv - Dr[(int64_t)h * T + t0 + r]);
-                            for (int32_t c = 0; c < d; ++c) {
-                                dv_row[c] += p * do_row[c];
-                                dk_row[c] += ds * q_row[c];
-                            }
-                        }
-                    }
-                    for (int32_t c = 0; c < d; ++c) dk_row[c] *= scale;
+                    const int64_t kv = (t0 + j) * ks + (int64_t)g * d;
+                    key_backward(q, d_o, k + kv, v + kv, qs, t0, L, j, g, G, d, scale,
+                                 lse + (int64_t)g * G * T + t0, Dr + (int64_t)g * G * T + t0, T, 0,
+                                 dk + kv, dv + kv);
                 }
             }
         }
+    }
+    free(scratch);
+    free(lse);
+    free(Dr);
+    return ORACLE_OK;
+}
+
+/* Sampled rows: for n (token, q head) pairs, O_r [n,d], LSE_r [n] and dQ_r [n,d].
+ * Same per-row routines as the full functions; cost O(r d) per sample. */
+int oracle_attn_rows(const double *q, const double *k, const double *v, const double *d_o,
+                     const int32_t *cu, int32_t B, int32_t Hq, int32_t Hkv, int32_t d, double scale,
+                     int32_t n, const int32_t *tokens, const int32_t *heads,
+                     double *o_rows, double *lse_rows, double *dq_rows) {
+    int rc = check_args(cu, B, Hq, Hkv, d);
+    if (rc) return rc;
+    if (!q || !k || !v || !d_o || n < 0 || (n > 0 && (!tokens || !heads || !o_rows || !lse_rows || !dq_rows)))
+        return ORACLE_BAD_ARG;
+    const int32_t G = Hq / Hkv;
+    const int64_t qs = (int64_t)Hq * d, ks = (int64_t)Hkv * d;
+    for (int32_t x = 0; x < n; ++x)
+        if (tokens[x] < 0 || tokens[x] >= cu[B] || heads[x] < 0 || heads[x] >= Hq) return ORACLE_BAD_ARG;
+    const size_t row_len = (size_t)longest(cu, B);
+    double *scratch = (double *)malloc(sizeof(double) * 2 * row_len * (size_t)oracle_num_threads());
+    if (!scratch) return ORACLE_NO_MEM;
+#pragma omp parallel
+    {
+        double *p = scratch + 2 * row_len * (size_t)thread_index();
+        double *dp = p + row_len;
+#pragma omp for schedule(dynamic, 1)
+        for (int32_t x = 0; x < n; ++x) {
+            int32_t i = 0;
+            while (cu[i + 1] <= tokens[x]) ++i;   /* the sequence that holds this token */
+            const int64_t t0 = cu[i];
+            const int32_t r = tokens[x] - cu[i], h = heads[x];
+            const double *kh = k + (int64_t)(h / G) * d;
+            const double *vh = v + (int64_t)(h / G) * d;
+            const double *q_row = q + (t0 + r) * qs + (int64_t)h * d;
+            const double *do_row = d_o + (t0 + r) * qs + (int64_t)h * d;
+            lse_rows[x] = row_forward(q_row, kh, vh, ks, t0, r, d, scale, p, o_rows + (int64_t)x * d);
+            row_backward(do_row, kh, vh, ks, t0, r, d, scale, p, dp, dq_rows + (int64_t)x * d);
+        }
+    }
+    free(scratch);
+    return ORACLE_OK;
+}
+
+/* Sampled keys: for n (token, kv head) pairs, dK_j [n,d] and dV_j [n,d].  LSE_r and D_r of
+ * the rows r >= j are evaluated row by row first; cost O((L - j) L d G) per sample. */
+int oracle_attn_keys(const double *q, const double *k, const double *v, const double *d_o,
+                     const int32_t *cu, int32_t B, int32_t Hq, int32_t Hkv, int32_t d, double scale,
+                     int32_t n, const int32_t *tokens, const int32_t *kv_heads,
+                     double *dk_rows, double *dv_rows) {
+    int rc = check_args(cu, B, Hq, Hkv, d);
+    if (rc) return rc;
+    if (!q || !k || !v || !d_o || n < 0 || (n > 0 && (!tokens || !kv_heads || !dk_rows || !dv_rows)))
+        return ORACLE_BAD_ARG;
+    const int32_t G = Hq / Hkv;
+    const int64_t qs = (int64_t)Hq * d, ks = (int64_t)Hkv * d;
+    for (int32_t x = 0; x < n; ++x)
+        if (tokens[x] < 0 || tokens[x] >= cu[B] || kv_heads[x] < 0 || kv_heads[x] >= Hkv) return ORACLE_BAD_ARG;
+    const size_t row_len = (size_t)longest(cu, B);
+    double *scratch = (double *)malloc(sizeof(double) * 2 * row_len * (size_t)oracle_num_threads());
+    double *lse = (double *)malloc(sizeof(double) * row_len * (size_t)G);
+    double *Dr = (double *)malloc(sizeof(double) * row_len * (size_t)G);
+    if (!scratch || !lse || !Dr) { free(scratch); free(lse); free(Dr); return ORACLE_NO_MEM; }
+    for (int32_t x = 0; x < n; ++x) {
+        int32_t i = 0;
+        while (cu[i + 1] <= tokens[x]) ++i;
+        const int64_t t0 = cu[i];
+        const int32_t L = cu[i + 1] - cu[i], j = tokens[x] - cu[i], g = kv_heads[x];
+        const double *kh = k + (int64_t)g * d;
+        const double *vh = v + (int64_t)g * d;
+#pragma omp parallel
+        {
+            double *p = scratch + 2 * row_len * (size_t)thread_index();
+            double *dp = p + row_len;
+            for (int32_t hg = 0; hg < G; ++hg) {
+                const int32_t h = g * G + hg;
+#pragma omp for schedule(dynamic, 4) nowait
+                for (int32_t r = j; r < L; ++r) {
+                    const double *q_row = q + (t0 + r) * qs + (int64_t)h * d;
+                    const double *do_row = d_o + (t0 + r) * qs + (int64_t)h * d;
+                    lse[(int64_t)hg * row_len + (r - j)] = row_forward(q_row, kh, vh, ks, t0, r, d, scale, p, NULL);
+                    Dr[(int64_t)hg * row_len + (r - j)] = row_backward(do_row, kh, vh, ks, t0, r, d, scale, p, dp, NULL);
+                }
+            }
+        }
+        const int64_t kv = (t0 + j) * ks + (int64_t)g * d;
+        key_backward(q, d_o, k + kv, v + kv, qs, t0, L, j, g, G, d, scale, lse, Dr, (int64_t)row_len, j,
+                     dk_rows + (int64_t)x * d, dv_rows + (int64_t)x * d);
     }
     free(scratch);
     free(lse);

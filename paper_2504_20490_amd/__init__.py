@@ -7,5 +7,5 @@ GPU is present, the compute calls raise.
 from .binding import (  # noqa: F401
     HspmdError, Plan, LIST_FWD, LIST_DQ, LIST_DKV, GRAD_BF16, GRAD_F32,
     library_path, load_library, build_cu_seqlens, schedule, tile_rows,
-    attn_varlen_fwd, attn_varlen_bwd,
+    attn_varlen_fwd, attn_varlen_bwd, profile_enable, profile_read,
 )

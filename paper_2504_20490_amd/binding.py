@@ -73,6 +73,12 @@ def load_library():
     lib.hspmd_attn_varlen_bwd.restype = ctypes.c_int
     lib.hspmd_attn_varlen_bwd.argtypes = [vp, vp, vp, vp, vp, vp, vp, ctypes.c_int64, ctypes.c_int64,
                                           ctypes.c_float, vp, vp, vp, ctypes.c_int, vp, ctypes.c_size_t, vp]
+    lib.hspmd_profile_enable.restype = ctypes.c_int
+    lib.hspmd_profile_enable.argtypes = [ctypes.c_int32]
+    lib.hspmd_profile_read.restype = ctypes.c_int
+    lib.hspmd_profile_read.argtypes = [ctypes.POINTER(ctypes.c_double), i64p]
+    lib.hspmd_kernel_name.restype = ctypes.c_char_p
+    lib.hspmd_kernel_name.argtypes = [ctypes.c_int32]
     _lib = lib
     return lib
 
@@ -193,3 +199,19 @@ def attn_varlen_bwd(plan: Plan, q, k, v, o, lse, d_o, dq, dk, dv, workspace, sof
                                      float(softmax_scale), _dev_ptr(dq), _dev_ptr(dk), _dev_ptr(dv), int(grad_dtype),
                                      _dev_ptr(workspace), workspace.numel() * workspace.element_size(),
                                      _stream_handle(stream)))
+
+
+NUM_KERNELS = 4
+
+
+def profile_enable(on: bool) -> None:
+    _check(load_library().hspmd_profile_enable(1 if on else 0))
+
+
+def profile_read():
+    """Returns {kernel name: (total ms, launches)} for the launches recorded since the last read."""
+    lib = load_library()
+    ms = (ctypes.c_double * NUM_KERNELS)()
+    n = (ctypes.c_int64 * NUM_KERNELS)()
+    _check(lib.hspmd_profile_read(ms, n))
+    return {lib.hspmd_kernel_name(i).decode(): (float(ms[i]), int(n[i])) for i in range(NUM_KERNELS)}

@@ -29,6 +29,43 @@ hspmd_status fail_hip(hipError_t e, const char* where) {
 
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
+// ---- optional per-kernel event timing ------------------------------------------------------
+struct ProfileRecord {
+    int kernel;
+    hipEvent_t start, stop;
+};
+bool g_profile_on = false;
+std::vector<ProfileRecord> g_records;
+std::vector<hipEvent_t> g_event_pool;
+
+hipError_t take_event(hipEvent_t* ev) {
+    if (!g_event_pool.empty()) {
+        *ev = g_event_pool.back();
+        g_event_pool.pop_back();
+        return hipSuccess;
+    }
+    return hipEventCreate(ev);
+}
+
+// Runs `launch` on `stream`; when profiling is on, brackets it with two events.
+template <typename F>
+hipError_t timed_launch(int kernel, hipStream_t stream, F&& launch) {
+    if (!g_profile_on) return launch();
+    ProfileRecord r{kernel, nullptr, nullptr};
+    hipError_t e = take_event(&r.start);
+    if (e != hipSuccess) return e;
+    e = take_event(&r.stop);
+    if (e != hipSuccess) return e;
+    e = hipEventRecord(r.start, stream);
+    if (e != hipSuccess) return e;
+    e = launch();
+    if (e != hipSuccess) return e;
+    e = hipEventRecord(r.stop, stream);
+    if (e != hipSuccess) return e;
+    g_records.push_back(r);
+    return hipSuccess;
+}
+
 }  // namespace
 
 struct hspmd_attn_plan {
@@ -191,7 +228,8 @@ hspmd_status hspmd_attn_varlen_fwd(const hspmd_attn_plan* plan, const void* q, c
     p.q_heads = plan->q_heads;
     p.group = plan->q_heads / plan->kv_heads;
     p.scale_log2 = scale * 1.4426950408889634f;
-    const hipError_t e = hspmd::launch_fwd(p, plan->head_dim, plan->count[HSPMD_LIST_FWD], static_cast<hipStream_t>(stream));
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const hipError_t e = timed_launch(0, s, [&] { return hspmd::launch_fwd(p, plan->head_dim, plan->count[HSPMD_LIST_FWD], s); });
     if (e != hipSuccess) return fail_hip(e, "forward launch");
     return HSPMD_OK;
 }
@@ -236,15 +274,46 @@ hspmd_status hspmd_attn_varlen_bwd(const hspmd_attn_plan* plan, const void* q, c
     p.scale = scale;
     p.scale_log2 = scale * 1.4426950408889634f;
     hipStream_t s = static_cast<hipStream_t>(stream);
-    hipError_t e = hspmd::launch_bwd_dsum(p, plan->head_dim, s);
+    hipError_t e = timed_launch(1, s, [&] { return hspmd::launch_bwd_dsum(p, plan->head_dim, s); });
     if (e != hipSuccess) return fail_hip(e, "backward D launch");
     p.items = plan->items[HSPMD_LIST_DQ];
-    e = hspmd::launch_bwd_dq(p, plan->head_dim, plan->count[HSPMD_LIST_DQ], s);
+    e = timed_launch(2, s, [&] { return hspmd::launch_bwd_dq(p, plan->head_dim, plan->count[HSPMD_LIST_DQ], s); });
     if (e != hipSuccess) return fail_hip(e, "backward dQ launch");
     p.items = plan->items[HSPMD_LIST_DKV];
-    e = hspmd::launch_bwd_dkv(p, plan->head_dim, plan->count[HSPMD_LIST_DKV], s);
+    e = timed_launch(3, s, [&] { return hspmd::launch_bwd_dkv(p, plan->head_dim, plan->count[HSPMD_LIST_DKV], s); });
     if (e != hipSuccess) return fail_hip(e, "backward dK/dV launch");
     return HSPMD_OK;
+}
+
+hspmd_status hspmd_profile_enable(int32_t on) {
+    g_profile_on = on != 0;
+    return HSPMD_OK;
+}
+
+hspmd_status hspmd_profile_read(double* ms, int64_t* launches) {
+    if (!ms || !launches) return fail(HSPMD_ERR_INVALID_ARG, "null pointer");
+    hspmd_status rc = HSPMD_OK;
+    for (const ProfileRecord& r : g_records) {
+        hipError_t e = hipEventSynchronize(r.stop);
+        float t = 0.f;
+        if (e == hipSuccess) e = hipEventElapsedTime(&t, r.start, r.stop);
+        if (e == hipSuccess) {
+            ms[r.kernel] += (double)t;
+            launches[r.kernel] += 1;
+        } else {
+            rc = fail_hip(e, "profile read");
+        }
+        g_event_pool.push_back(r.start);
+        g_event_pool.push_back(r.stop);
+    }
+    g_records.clear();
+    return rc;
+}
+
+const char* hspmd_kernel_name(int32_t kernel) {
+    static const char* const names[HSPMD_NUM_KERNELS] = {"fwd_kernel", "bwd_dsum_kernel", "bwd_dq_kernel",
+                                                         "bwd_dkv_kernel"};
+    return (kernel >= 0 && kernel < HSPMD_NUM_KERNELS) ? names[kernel] : nullptr;
 }
 
 }  // extern "C"

@@ -1,0 +1,94 @@
+"""Helpers shared by the GPU parity tests: run the C ABI on seeded bf16 inputs, compare with the oracle."""
+from __future__ import annotations
+
+import math
+
+import numpy as np
+
+import hspmd_workloads as w
+
+MAX_ABS = 2e-2      # tolerance stated for O, dQ, dK, dV: max-abs error ...
+REL_FRO = 1e-2      # ... and relative Frobenius error (bf16 inputs, fp32 accumulation)
+LSE_ABS = 1e-3
+
+
+def f64(bits: np.ndarray) -> np.ndarray:
+    return w.bits_to_f32(bits).astype(np.float64)
+
+
+def to_dev(bits: np.ndarray):
+    import torch
+    return torch.from_numpy(np.ascontiguousarray(bits).view(np.int16)).view(torch.bfloat16).cuda()
+
+
+def make_case(lengths, hq, hkv, d, seed, value_scale=1.0):
+    T = int(sum(lengths))
+    q = w.make_tensor(seed, "q", T * hq * d, value_scale).reshape(T, hq, d)
+    k = w.make_tensor(seed, "k", T * hkv * d, value_scale).reshape(T, hkv, d)
+    v = w.make_tensor(seed, "v", T * hkv * d, value_scale).reshape(T, hkv, d)
+    do = w.make_tensor(seed, "do", T * hq * d, value_scale).reshape(T, hq, d)
+    return q, k, v, do
+
+
+class GpuRun:
+    """Forward + backward through the C ABI; keeps the device tensors for inspection."""
+
+    def __init__(self, lengths, q_bits, k_bits, v_bits, do_bits, grad_dtype=None, scale=0.0,
+                 q_dev=None, k_dev=None, v_dev=None):
+        import torch
+        import paper_2504_20490_amd as A
+        self.A = A
+        T, hq, d = q_bits.shape
+        hkv = k_bits.shape[1]
+        self.shape = (T, hq, hkv, d)
+        grad_dtype = A.GRAD_F32 if grad_dtype is None else grad_dtype
+        cu, _, total = A.build_cu_seqlens(lengths)
+        assert total == T
+        self.plan = A.Plan(cu, hq, hkv, d)
+        self.q = to_dev(q_bits) if q_dev is None else q_dev
+        self.k = to_dev(k_bits) if k_dev is None else k_dev
+        self.v = to_dev(v_bits) if v_dev is None else v_dev
+        self.do = to_dev(do_bits)
+        self.o = torch.full((T, hq, d), float("nan"), dtype=torch.bfloat16, device="cuda")
+        self.lse = torch.full((hq, T), float("nan"), dtype=torch.float32, device="cuda")
+        gd = torch.float32 if grad_dtype == A.GRAD_F32 else torch.bfloat16
+        self.dq = torch.full((T, hq, d), float("nan"), dtype=gd, device="cuda")
+        self.dk = torch.full((T, hkv, d), float("nan"), dtype=gd, device="cuda")
+        self.dv = torch.full((T, hkv, d), float("nan"), dtype=gd, device="cuda")
+        self.ws = torch.empty(max(self.plan.bwd_workspace_bytes(), 16), dtype=torch.uint8, device="cuda")
+        self.scale = scale
+        self.grad_dtype = grad_dtype
+
+    def forward(self):
+        self.A.attn_varlen_fwd(self.plan, self.q, self.k, self.v, self.o, self.lse, self.scale)
+
+    def backward(self):
+        self.A.attn_varlen_bwd(self.plan, self.q, self.k, self.v, self.o, self.lse, self.do, self.dq, self.dk,
+                               self.dv, self.ws, self.scale, self.grad_dtype)
+
+    def run(self):
+        import torch
+        self.forward()
+        self.backward()
+        torch.cuda.synchronize()
+        return self
+
+    def host(self, name):
+        return getattr(self, name).float().cpu().numpy().astype(np.float64)
+
+
+def errors(got: np.ndarray, ref: np.ndarray):
+    diff = got - ref
+    return float(np.max(np.abs(diff))) if diff.size else 0.0, \
+        float(np.linalg.norm(diff) / max(np.linalg.norm(ref), 1e-300)) if diff.size else 0.0
+
+
+def assert_close(name, got, ref, max_abs=MAX_ABS, rel_fro=REL_FRO):
+    assert not np.isnan(got).any(), f"{name}: NaN in GPU output (unwritten or invalid elements)"
+    ma, rf = errors(got, ref)
+    assert ma <= max_abs and rf <= rel_fro, f"{name}: max_abs {ma:.3e} (<= {max_abs}), rel_fro {rf:.3e} (<= {rel_fro})"
+    return ma, rf
+
+
+def default_scale(d):
+    return 1.0 / math.sqrt(d)

@@ -1,0 +1,161 @@
+"""Host-side tests of the C-ABI boundary: symbol export, cu_seqlens, the cost-sorted work list
+and argument validation.  No GPU is touched."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+import hspmd_workloads as w
+import paper_2504_20490_amd as A
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_library_exports_every_declared_symbol():
+    header = open(os.path.join(ROOT, "include", "hspmd_attn.h")).read()
+    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+    names = set(re.findall(r"\b(hspmd_[a-z_0-9]+)\s*\(", header))
+    assert {"hspmd_build_cu_seqlens", "hspmd_attn_varlen_fwd", "hspmd_attn_varlen_bwd",
+            "hspmd_attn_plan_create", "hspmd_attn_schedule"} <= names
+    lib = ctypes.CDLL(A.library_path())
+    for n in sorted(names):
+        assert hasattr(lib, n), n
+    assert A.load_library().hspmd_last_error() is not None
+
+
+def test_build_cu_seqlens():
+    cu, mx, tot = A.build_cu_seqlens([17, 64, 111])
+    assert cu.tolist() == [0, 17, 81, 192] and mx == 111 and tot == 192
+    cu, mx, tot = A.build_cu_seqlens([0, 5, 0])
+    assert cu.tolist() == [0, 0, 5, 5] and mx == 5 and tot == 5
+    cu, mx, tot = A.build_cu_seqlens([])
+    assert cu.tolist() == [0] and mx == 0 and tot == 0
+    with pytest.raises(A.HspmdError) as e:
+        A.build_cu_seqlens([4, -1])
+    assert e.value.status == 1 and "negative" in str(e.value)
+    with pytest.raises(A.HspmdError):
+        A.build_cu_seqlens([2 ** 30, 2 ** 30, 5])      # running sum above INT32_MAX
+    cu, _, tot = A.build_cu_seqlens([2 ** 30, 2 ** 30 - 1])
+    assert tot == 2 ** 31 - 1 and cu[-1] == 2 ** 31 - 1
+
+
+def _cost(kind, L, tile, G):
+    if kind == A.LIST_DKV:
+        return -(-(L - tile * 128) // 64) * G
+    return -(-min(L, (tile + 1) * 128) // 64)
+
+
+@pytest.mark.parametrize("name", ["C1", "C2", "C3", "C4", "C5"])
+@pytest.mark.parametrize("kind", [A.LIST_FWD, A.LIST_DQ, A.LIST_DKV])
+def test_work_list_invariants(name, kind):
+    cfg = w.config_by_name(name)
+    lengths = w.lengths_for(cfg)
+    cu, _, _ = A.build_cu_seqlens(lengths)
+    hq, hkv = cfg.q_heads, cfg.kv_heads
+    G = hq // hkv
+    items = A.schedule(kind, cu, hq, hkv, 8)
+    assert items.shape[0] % 8 == 0
+    real = items[items[:, 2] >= 0]
+    rows = A.tile_rows(kind)
+    heads = hkv if kind == A.LIST_DKV else hq
+    # every (sequence, tile, head) exactly once; tiles cover [0, L)
+    want = set()
+    for s, L in enumerate(lengths):
+        for t in range(-(-L // rows)):
+            for h in range(heads):
+                want.add((int(cu[s]), L, t, h))
+    got = [tuple(int(x) for x in r) for r in real]
+    assert len(got) == len(set(got)) == len(want) and set(got) == want
+    # queues (slots with equal p % 8) are balanced by cost
+    loads = np.zeros(8)
+    for p, r in enumerate(items):
+        if r[2] >= 0:
+            loads[p % 8] += _cost(kind, int(r[1]), int(r[2]), G)
+    biggest = max(_cost(kind, int(r[1]), int(r[2]), G) for r in real)
+    if len(real) >= 64:
+        assert loads.max() - loads.min() <= max(0.08 * loads.mean(), 2 * biggest), loads
+    # items that share K/V (or Q/dO) stay in one queue unless their chain was cut for balance,
+    # and inside a queue one chain's items appear most expensive first
+    by_chain = {}
+    for p, r in enumerate(items):
+        if r[2] < 0:
+            continue
+        kvh = int(r[3]) if kind == A.LIST_DKV else int(r[3]) // G
+        by_chain.setdefault((int(r[0]), kvh, p % 8), []).append(_cost(kind, int(r[1]), int(r[2]), G))
+    for costs in by_chain.values():
+        assert costs == sorted(costs, reverse=True)
+    # padding only at the tail of a queue
+    for x in range(8):
+        tiles = items[x::8, 2]
+        pad = np.flatnonzero(tiles < 0)
+        if pad.size:
+            assert np.all(tiles[pad[0]:] < 0)
+
+
+def test_work_list_gqa_heads_of_one_tile_are_adjacent():
+    cu, _, _ = A.build_cu_seqlens([1000, 3000])
+    items = A.schedule(A.LIST_FWD, cu, 8, 2, 8)
+    for x in range(8):
+        q = items[x::8]
+        q = q[q[:, 2] >= 0]
+        # consecutive items of a queue that share (sequence, tile) walk through the heads of one KV group
+        for a, b in zip(q[:-1], q[1:]):
+            if a[0] == b[0] and a[2] == b[2]:
+                assert a[3] // 4 == b[3] // 4
+
+
+def test_work_list_single_long_sequence_is_spread():
+    # one sequence, one head: the chain must be cut so that all 8 queues get work
+    cu, _, _ = A.build_cu_seqlens([32768])
+    for kind in (A.LIST_FWD, A.LIST_DKV):
+        items = A.schedule(kind, cu, 1, 1, 8)
+        loads = np.zeros(8)
+        for p, r in enumerate(items):
+            if r[2] >= 0:
+                loads[p % 8] += _cost(kind, int(r[1]), int(r[2]), 1)
+        assert loads.min() > 0.8 * loads.mean(), loads
+
+
+def test_work_list_empty_and_zero_length():
+    assert A.schedule(A.LIST_FWD, [0], 4, 4).shape == (0, 4)
+    assert A.schedule(A.LIST_DKV, [0, 0, 0], 4, 2).shape == (0, 4)
+    items = A.schedule(A.LIST_FWD, [0, 0, 5, 5], 1, 1, 8)
+    real = items[items[:, 2] >= 0]
+    assert real.tolist() == [[0, 5, 0, 0]]
+
+
+def test_schedule_rejects_bad_arguments():
+    for bad, frag in ((dict(cu=[0, 4], hq=3, hkv=2), "multiple"), (dict(cu=[1, 4], hq=2, hkv=2), "cu_seqlens[0]"),
+                      (dict(cu=[0, 4, 3], hq=2, hkv=2), "non-decreasing"), (dict(cu=[0, 4], hq=0, hkv=1), "positive")):
+        with pytest.raises(A.HspmdError) as e:
+            A.schedule(A.LIST_FWD, bad["cu"], bad["hq"], bad["hkv"])
+        assert e.value.status == 1 and frag in str(e.value)
+    with pytest.raises(A.HspmdError):
+        A.schedule(7, [0, 4], 2, 2)
+    with pytest.raises(A.HspmdError):
+        A.schedule(A.LIST_FWD, [0, 4], 2, 2, num_queues=0)
+    # capacity too small: nothing written, INVALID_ARG, count still reported
+    lib = A.load_library()
+    cu = np.array([0, 300], dtype=np.int32)
+    n = ctypes.c_int64(0)
+    from paper_2504_20490_amd.binding import WorkItem
+    buf = (WorkItem * 2)()
+    rc = lib.hspmd_attn_schedule(0, cu.ctypes.data_as(ctypes.POINTER(ctypes.c_int32)), 1, 2, 2, 8, buf, 2, ctypes.byref(n))
+    assert rc == 1 and n.value == 8
+
+
+def test_plan_create_validates_before_touching_the_gpu():
+    lib = A.load_library()
+    cu = np.array([0, 8], dtype=np.int32)
+    p = cu.ctypes.data_as(ctypes.POINTER(ctypes.c_int32))
+    out = ctypes.c_void_p()
+    assert lib.hspmd_attn_plan_create(p, 1, 2, 2, 100, None, ctypes.byref(out)) == 2      # head_dim 100: UNSUPPORTED
+    assert b"head_dim" in lib.hspmd_last_error()
+    assert lib.hspmd_attn_plan_create(p, 1, 3, 2, 128, None, ctypes.byref(out)) == 1      # 3 q heads on 2 kv heads
+    assert lib.hspmd_attn_plan_create(p, 1, 2, 2, 128, None, None) == 1
+    assert out.value is None
+    assert lib.hspmd_attn_plan_destroy(None) == 0
+    assert lib.hspmd_attn_varlen_fwd(None, None, None, None, 0, 0, 0.0, None, None, None) == 1
+    assert lib.hspmd_attn_plan_total_tokens(None) == -1 and lib.hspmd_attn_bwd_workspace_bytes(None) == 0

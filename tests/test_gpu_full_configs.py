@@ -1,0 +1,78 @@
+"""GPU parity at the full benchmark sizes, in the launch configuration bench.py times.
+
+The fp64 oracle cannot evaluate a 32K-token pack in seconds, so each configuration is checked on
+ (a) one whole medium-length sequence and one KV group (every O, LSE, dQ, dK, dV element of it), and
+ (b) sampled query rows of the longest sequence (first rows, tile edges, last row) and sampled keys
+     near its end, each computed one by one by the oracle's per-row / per-key routines,
+plus properties that hold at any size (no NaN anywhere, row 0 of every sequence has dQ ~ 0,
+O of row 0 equals V of row 0)."""
+import numpy as np
+import pytest
+
+import hspmd_workloads as w
+import oracle
+from gpu_util import GpuRun, LSE_ABS, assert_close, default_scale, f64
+
+pytestmark = pytest.mark.gpu
+
+
+def _pick_medium(lengths, lo=400, hi=2300):
+    cand = [i for i, L in enumerate(lengths) if lo <= L <= hi]
+    if not cand:
+        cand = [int(np.argmin([abs(L - 1500) for L in lengths]))]
+    return max(cand, key=lambda i: lengths[i])
+
+
+@pytest.mark.parametrize("name", ["C2", "C3", "C4", "C5"])
+def test_full_size_config(name):
+    import torch
+    cfg = w.config_by_name(name)
+    lengths, q, k, v, do = w.make_inputs(cfg)
+    hq, hkv, d = cfg.q_heads, cfg.kv_heads, cfg.head_dim
+    G = hq // hkv
+    s = default_scale(d)
+    run = GpuRun(lengths, q, k, v, do).run()
+    cu = np.concatenate([[0], np.cumsum(lengths)])
+    for t in (run.o, run.lse, run.dq, run.dk, run.dv):
+        assert not torch.isnan(t).any()
+    first = torch.from_numpy(cu[:-1][np.asarray(lengths) > 0]).cuda()
+    assert float(run.dq[first].abs().max()) < 1e-5      # sum_j dS_0j = 0 up to fp32 rounding of P, dP, D
+    for g in range(hkv):
+        assert torch.equal(run.o[first][:, g * G:(g + 1) * G], run.v[first][:, g:g + 1].expand(-1, G, -1))
+
+    # (a) one medium sequence, one KV group, every element
+    i = _pick_medium(lengths)
+    g = hkv // 2
+    sl = slice(int(cu[i]), int(cu[i + 1]))
+    hs = slice(g * G, (g + 1) * G)
+    qs, ks, vs, dos = f64(q[sl, hs]), f64(k[sl, g:g + 1]), f64(v[sl, g:g + 1]), f64(do[sl, hs])
+    ro, rlse = oracle.attn_fwd(qs, ks, vs, [lengths[i]], s)
+    rdq, rdk, rdv = oracle.attn_bwd(qs, ks, vs, dos, [lengths[i]], s)
+    assert_close("O", run.host("o")[sl, hs], ro)
+    assert np.max(np.abs(run.host("lse")[hs, sl] - rlse)) <= LSE_ABS
+    assert_close("dQ", run.host("dq")[sl, hs], rdq)
+    assert_close("dK", run.host("dk")[sl, g:g + 1], rdk)
+    assert_close("dV", run.host("dv")[sl, g:g + 1], rdv)
+
+    # (b) the longest sequence: sampled rows and keys, computed one by one
+    j = int(np.argmax(lengths))
+    L = lengths[j]
+    sl = slice(int(cu[j]), int(cu[j + 1]))
+    g = hkv - 1
+    hs = slice(g * G, (g + 1) * G)
+    qs, ks, vs, dos = f64(q[sl, hs]), f64(k[sl, g:g + 1]), f64(v[sl, g:g + 1]), f64(do[sl, hs])
+    rows = sorted({0, 1, 63, 64, 127, 128, 129, L // 3, L // 2, (L // 128) * 128 - 1, (L // 128) * 128 % L, L - 2, L - 1})
+    rows = [r for r in rows if 0 <= r < L]
+    tok = np.repeat(rows, G)
+    hd = np.tile(np.arange(G), len(rows))
+    o_r, lse_r, dq_r = oracle.attn_rows(qs, ks, vs, dos, [L], s, tok, hd)
+    got_o = run.host("o")[sl, hs][tok, hd]
+    got_dq = run.host("dq")[sl, hs][tok, hd]
+    got_lse = run.host("lse")[hs, sl][hd, tok]
+    assert_close("O rows", got_o, o_r)
+    assert_close("dQ rows", got_dq, dq_r)
+    assert np.max(np.abs(got_lse - lse_r)) <= LSE_ABS
+    keys = sorted({L - 1, L - 2, L - 64, L - 129, L - 200} & set(range(L)))
+    dk_r, dv_r = oracle.attn_keys(qs, ks, vs, dos, [L], s, keys, [0] * len(keys))
+    assert_close("dK keys", run.host("dk")[sl, g][keys], dk_r)
+    assert_close("dV keys", run.host("dv")[sl, g][keys], dv_r)

@@ -236,6 +236,21 @@ def test_dense_library_evaluation_with_autodiff():
     np.testing.assert_allclose(dv, tv.grad.numpy(), rtol=0, atol=1e-11)
 
 
+def test_sampled_rows_and_keys_equal_the_full_evaluation():
+    lengths, hq, hkv, d, s = [6, 0, 23, 1, 12], 4, 2, 8, 0.37
+    q, k, v, do = _inputs(lengths, hq, hkv, d, 130)
+    o, lse = oracle.attn_fwd(q, k, v, lengths, s)
+    dq, dk, dv = oracle.attn_bwd(q, k, v, do, lengths, s)
+    T = sum(lengths)
+    tok = np.repeat(np.arange(T), hq); hd = np.tile(np.arange(hq), T)
+    o_r, lse_r, dq_r = oracle.attn_rows(q, k, v, do, lengths, s, tok, hd)
+    assert np.array_equal(o_r.reshape(T, hq, d), o) and np.array_equal(dq_r.reshape(T, hq, d), dq)
+    assert np.array_equal(lse_r.reshape(T, hq).T, lse)
+    tok = np.repeat(np.arange(T), hkv); hd = np.tile(np.arange(hkv), T)
+    dk_r, dv_r = oracle.attn_keys(q, k, v, do, lengths, s, tok, hd)
+    assert np.array_equal(dk_r.reshape(T, hkv, d), dk) and np.array_equal(dv_r.reshape(T, hkv, d), dv)
+
+
 def test_zero_length_sequences_and_empty_pack():
     lengths, H, d, s = [0, 4, 0, 3, 0], 2, 4, 0.5
     q, k, v, do = _inputs(lengths, H, H, d, 110)
