@@ -84,6 +84,9 @@ def main() -> int:
     ap.add_argument("--workload", default="C4", help="C1..C5 (default: the 32768-token asymmetric-head pack)")
     ap.add_argument("--grad-dtype", default="f32", choices=["f32", "bf16"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="before the steps, run one plain device copy of 1 GiB (a kernel of known HBM traffic "
+                         "that scales the FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU's share of the batch on one GPU; --gpus above 1 is not part of this "
@@ -126,6 +129,13 @@ def main() -> int:
         A.attn_varlen_fwd(plan, tq, tk, tv, o, lse, stream=stream)
         A.attn_varlen_bwd(plan, tq, tk, tv, o, lse, tdo, dq, dk, dv, ws, grad_dtype=grad, stream=stream)
         return plan
+
+    if args.calibrate_copy:
+        src = torch.empty(1 << 30, dtype=torch.uint8, device=dev).fill_(1)
+        dst = torch.empty_like(src)
+        dst.copy_(src)              # reads 1 GiB, writes 1 GiB
+        torch.cuda.synchronize()
+        del src, dst
 
     plans = []
     for _ in range(args.warmup):

@@ -54,36 +54,33 @@ __device__ __forceinline__ int tile_offset(int row, int col) {
     return row * (D * 2) + (swizzle<D>(row, col >> 3) << 4) + ((col & 7) << 1);
 }
 
-// Global -> registers -> LDS staging of a ROWS x D tile by 256 threads, 16 B per access.
+// Global -> LDS copy of a ROWS x D tile without a trip through registers (global_load_lds_dwordx4).
+// One wave instruction moves 64 x 16 B into 1024 consecutive LDS bytes (lane i lands at base + 16 i),
+// so the swizzle is applied on the global side: the lane that owns physical chunk p of row r
+// fetches logical chunk p ^ f(r).  Rows at or beyond seq_len are replaced by the last valid row:
+// they only ever meet a zero weight, and a finite duplicate keeps 0 * x = 0.
+// The copies are asynchronous: wait_tile_loads() + a workgroup barrier make them visible.
 template <int D, int ROWS>
-struct TileStage {
-    static constexpr int kChunksPerRow = D / 8;
-    static constexpr int kPerThread = ROWS * kChunksPerRow / kThreads;
-    static_assert(ROWS * kChunksPerRow % kThreads == 0, "tile must divide over the workgroup");
-    u32x4 v[kPerThread];
+__device__ __forceinline__ void tile_load_async(char* tile, const uint16_t* slab, int64_t stride, int row0,
+                                                int seq_len, int wave, int lane) {
+    constexpr int kChunksPerRow = D / 8;
+    constexpr int kRowsPerInstr = 64 / kChunksPerRow;
+    constexpr int kInstr = ROWS / kRowsPerInstr;
+    static_assert(kInstr % 4 == 0, "tile must divide over 4 waves");
+#pragma unroll
+    for (int i = 0; i < kInstr / 4; ++i) {
+        const int blk = i * 4 + wave;
+        const int r = blk * kRowsPerInstr + lane / kChunksPerRow;
+        const int c = swizzle<D>(r, lane % kChunksPerRow);
+        const int row = min(row0 + r, seq_len - 1);
+        const uint16_t* src = slab + (int64_t)row * stride + c * 8;
+        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)src,
+                                         (__attribute__((address_space(3))) void*)(tile + blk * 1024), 16, 0, 0);
+    }
+}
 
-    // rows row0 .. row0+ROWS-1 of a [seq_len, D] slab with the given token stride (elements);
-    // rows at or beyond seq_len read as zero and touch no memory.
-    __device__ __forceinline__ void load(const uint16_t* slab, int64_t stride, int row0, int seq_len, int tid) {
-#pragma unroll
-        for (int i = 0; i < kPerThread; ++i) {
-            const int id = tid + i * kThreads;
-            const int r = id / kChunksPerRow, c = id % kChunksPerRow;
-            const int row = row0 + r;
-            u32x4 z = {0u, 0u, 0u, 0u};
-            if (row < seq_len) z = *reinterpret_cast<const u32x4*>(slab + (int64_t)row * stride + c * 8);
-            v[i] = z;
-        }
-    }
-    __device__ __forceinline__ void store(char* tile, int tid) const {
-#pragma unroll
-        for (int i = 0; i < kPerThread; ++i) {
-            const int id = tid + i * kThreads;
-            const int r = id / kChunksPerRow, c = id % kChunksPerRow;
-            *reinterpret_cast<u32x4*>(tile + tile_offset<D>(r, c * 8)) = v[i];
-        }
-    }
-};
+// all of this wave's outstanding global loads (direct-to-LDS copies included) have landed
+__device__ __forceinline__ void wait_tile_loads() { __builtin_amdgcn_s_waitcnt(0x0F70); }   // vmcnt(0)
 
 // A operand whose k runs along the tile's rows' columns: 8 consecutive elements of one row.
 //   rows: 32-row block `rb`; k-step kk covers columns 16*kk .. 16*kk+15

@@ -58,11 +58,13 @@ template <int D>
 __global__ __launch_bounds__(kThreads, 2) void bwd_dq_kernel(BwdParams p) {
     constexpr int BQ = kFwdQTile, BK = kFwdKTile;
     constexpr int KK = D / 16, DB = D / 32;
-    __shared__ __attribute__((aligned(16))) char lds[2 * 2 * BK * D * 2];   // {K, V} x 2 stages
+    constexpr int kTileBytes = BK * D * 2;
+    __shared__ __attribute__((aligned(1024))) char lds[2 * 2 * kTileBytes];   // {K, V} x 2 stages
 
     const hspmd_work_item item = p.items[blockIdx.x];
     if (item.tile < 0) return;
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int L = item.seq_len, h = item.head, hk = h / p.group;
     const int q_row0 = item.tile * BQ;
     const int wave_row0 = q_row0 + wave * 32;
@@ -74,6 +76,12 @@ __global__ __launch_bounds__(kThreads, 2) void bwd_dq_kernel(BwdParams p) {
     const uint16_t* dobase = p.d_o + ((int64_t)item.token_start * p.q_heads + h) * D;
     const uint16_t* kbase = p.k + (int64_t)item.token_start * p.kv_stride + (int64_t)hk * D;
     const uint16_t* vbase = p.v + (int64_t)item.token_start * p.kv_stride + (int64_t)hk * D;
+
+    const int kv_end = min(L, q_row0 + BQ);
+    const int n_tiles = (kv_end + BK - 1) / BK;
+
+    tile_load_async<D, BK>(lds, kbase, p.kv_stride, 0, L, wave, lane);
+    tile_load_async<D, BK>(lds + kTileBytes, vbase, p.kv_stride, 0, L, wave, lane);
 
     bf16x8 qf[KK], dof[KK];
 #pragma unroll
@@ -99,23 +107,15 @@ __global__ __launch_bounds__(kThreads, 2) void bwd_dq_kernel(BwdParams p) {
 #pragma unroll
         for (int i = 0; i < 16; ++i) acc[db][i] = 0.f;
 
-    const int kv_end = min(L, q_row0 + BQ);
-    const int n_tiles = (kv_end + BK - 1) / BK;
-
-    TileStage<D, BK> kst, vst;
-    kst.load(kbase, p.kv_stride, 0, L, tid);
-    vst.load(vbase, p.kv_stride, 0, L, tid);
-    kst.store(lds, tid);
-    vst.store(lds + BK * D * 2, tid);
-    __syncthreads();
-
     for (int kt = 0; kt < n_tiles; ++kt) {
-        const char* ktile = lds + (kt & 1) * (2 * BK * D * 2);
-        const char* vtile = ktile + BK * D * 2;
-        const bool more = kt + 1 < n_tiles;
-        if (more) {
-            kst.load(kbase, p.kv_stride, (kt + 1) * BK, L, tid);
-            vst.load(vbase, p.kv_stride, (kt + 1) * BK, L, tid);
+        wait_tile_loads();
+        __syncthreads();   // tile kt has landed; every wave is done with the other stage
+        const char* ktile = lds + (kt & 1) * (2 * kTileBytes);
+        const char* vtile = ktile + kTileBytes;
+        if (kt + 1 < n_tiles) {
+            char* next = lds + ((kt + 1) & 1) * (2 * kTileBytes);
+            tile_load_async<D, BK>(next, kbase, p.kv_stride, (kt + 1) * BK, L, wave, lane);
+            tile_load_async<D, BK>(next + kTileBytes, vbase, p.kv_stride, (kt + 1) * BK, L, wave, lane);
         }
         const int key0 = kt * BK;
 #pragma unroll
@@ -125,10 +125,20 @@ __global__ __launch_bounds__(kThreads, 2) void bwd_dq_kernel(BwdParams p) {
                 f32x16 s, dp;
 #pragma unroll
                 for (int i = 0; i < 16; ++i) { s[i] = 0.f; dp[i] = 0.f; }
+                {
+                    bf16x8 kf[KK];
 #pragma unroll
-                for (int kk = 0; kk < KK; ++kk) s = mfma(read_rowmajor_frag<D>(ktile, jb, kk, lane), qf[kk], s);
+                    for (int kk = 0; kk < KK; ++kk) kf[kk] = read_rowmajor_frag<D>(ktile, jb, kk, lane);
 #pragma unroll
-                for (int kk = 0; kk < KK; ++kk) dp = mfma(read_rowmajor_frag<D>(vtile, jb, kk, lane), dof[kk], dp);
+                    for (int kk = 0; kk < KK; ++kk) s = mfma(kf[kk], qf[kk], s);
+                }
+                {
+                    bf16x8 vf[KK];
+#pragma unroll
+                    for (int kk = 0; kk < KK; ++kk) vf[kk] = read_rowmajor_frag<D>(vtile, jb, kk, lane);
+#pragma unroll
+                    for (int kk = 0; kk < KK; ++kk) dp = mfma(vf[kk], dof[kk], dp);
+                }
                 const bool diag = kb + 31 > wave_row0;
 #pragma unroll
                 for (int i = 0; i < 16; ++i) {
@@ -139,18 +149,14 @@ __global__ __launch_bounds__(kThreads, 2) void bwd_dq_kernel(BwdParams p) {
 #pragma unroll
                 for (int tt = 0; tt < 2; ++tt) {
                     const bf16x8 dsf = frag_to_bf16(s, tt);
+                    bf16x8 ktf[DB];
 #pragma unroll
-                    for (int db = 0; db < DB; ++db)
-                        acc[db] = mfma(read_transposed_frag<D>(ktile, db, jb * 2 + tt, lane), dsf, acc[db]);
+                    for (int db = 0; db < DB; ++db) ktf[db] = read_transposed_frag<D>(ktile, db, jb * 2 + tt, lane);
+#pragma unroll
+                    for (int db = 0; db < DB; ++db) acc[db] = mfma(ktf[db], dsf, acc[db]);
                 }
             }
         }
-        if (more) {
-            char* next = lds + ((kt + 1) & 1) * (2 * BK * D * 2);
-            kst.store(next, tid);
-            vst.store(next + BK * D * 2, tid);
-        }
-        __syncthreads();
     }
 
     if (valid) {
@@ -171,12 +177,14 @@ __global__ __launch_bounds__(kThreads, 1) void bwd_dkv_kernel(BwdParams p) {
     constexpr int BKV = kDkvKTile, BQ = kDkvQTile;
     constexpr int KK = D / 16, DB = D / 32;
     constexpr int kTileBytes = BQ * D * 2;
-    constexpr int kStageBytes = 2 * kTileBytes + 2 * BQ * 4;   // Q, dO, lse2[BQ], dsum[BQ]
-    __shared__ __attribute__((aligned(16))) char lds[2 * kStageBytes];
+    constexpr int kStatBytes = 1024;                           // lse2[BQ], dsum[BQ] (fp32), padded
+    constexpr int kStageBytes = 2 * kTileBytes + kStatBytes;   // Q, dO, statistics
+    __shared__ __attribute__((aligned(1024))) char lds[2 * kStageBytes];
 
     const hspmd_work_item item = p.items[blockIdx.x];
     if (item.tile < 0) return;
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int L = item.seq_len, g = item.head;
     const int key0 = item.tile * BKV;
     const int wave_key0 = key0 + wave * 32;
@@ -186,6 +194,39 @@ __global__ __launch_bounds__(kThreads, 1) void bwd_dkv_kernel(BwdParams p) {
 
     const uint16_t* kbase = p.k + (int64_t)item.token_start * p.kv_stride + (int64_t)g * D;
     const uint16_t* vbase = p.v + (int64_t)item.token_start * p.kv_stride + (int64_t)g * D;
+
+    // steps: for each head of the group, q tiles first_qt .. n_qt-1 (rows at or below the diagonal)
+    const int first_qt = key0 / BQ;
+    const int n_qt = (L + BQ - 1) / BQ;
+    const int per_head = n_qt - first_qt;
+    const int n_steps = per_head * p.group;
+
+    float st_lse = 0.f, st_dsum = 0.f;   // threads 0..BQ-1 carry one row's statistics of the next step
+    auto load_step = [&](int step, char* stage) {
+        const int hq = g * p.group + step / per_head;
+        const int row0 = (first_qt + step % per_head) * BQ;
+        const uint16_t* qb = p.q + (int64_t)item.token_start * p.q_stride + (int64_t)hq * D;
+        const uint16_t* dob = p.d_o + ((int64_t)item.token_start * p.q_heads + hq) * D;
+        tile_load_async<D, BQ>(stage, qb, p.q_stride, row0, L, wave, lane);
+        tile_load_async<D, BQ>(stage + kTileBytes, dob, (int64_t)p.q_heads * D, row0, L, wave, lane);
+        if (tid < BQ) {
+            const int r = row0 + tid;
+            const int64_t stat = (int64_t)hq * p.total_tokens + item.token_start + r;
+            st_lse = r < L ? p.lse[stat] * kLog2e : INFINITY;   // rows past the end: P = exp2(-inf) = 0
+            st_dsum = r < L ? p.dsum[stat] : 0.f;
+        }
+    };
+    auto store_stats = [&](char* stage) {
+        if (tid < BQ) {
+            reinterpret_cast<float*>(stage + 2 * kTileBytes)[tid] = st_lse;
+            reinterpret_cast<float*>(stage + 2 * kTileBytes + BQ * 4)[tid] = st_dsum;
+        }
+    };
+
+    if (n_steps > 0) {
+        load_step(0, lds);
+        store_stats(lds);
+    }
 
     bf16x8 kf[KK], vf[KK];
 #pragma unroll
@@ -208,52 +249,17 @@ __global__ __launch_bounds__(kThreads, 1) void bwd_dkv_kernel(BwdParams p) {
 #pragma unroll
         for (int i = 0; i < 16; ++i) { dk[db][i] = 0.f; dv[db][i] = 0.f; }
 
-    // steps: for each head of the group, q tiles first_qt .. n_qt-1 (rows at or below the diagonal)
-    const int first_qt = key0 / BQ;
-    const int n_qt = (L + BQ - 1) / BQ;
-    const int per_head = n_qt - first_qt;
-    const int n_steps = per_head * p.group;
-
-    TileStage<D, BQ> qst, dost;
-    float st_lse = 0.f, st_dsum = 0.f;   // threads 0..BQ-1 stage one row's statistics each
-
-    auto load_step = [&](int step) {
-        const int hq = g * p.group + step / per_head;
-        const int row0 = (first_qt + step % per_head) * BQ;
-        const uint16_t* qb = p.q + (int64_t)item.token_start * p.q_stride + (int64_t)hq * D;
-        const uint16_t* dob = p.d_o + ((int64_t)item.token_start * p.q_heads + hq) * D;
-        qst.load(qb, p.q_stride, row0, L, tid);
-        dost.load(dob, (int64_t)p.q_heads * D, row0, L, tid);
-        if (tid < BQ) {
-            const int r = row0 + tid;
-            const int64_t stat = (int64_t)hq * p.total_tokens + item.token_start + r;
-            st_lse = r < L ? p.lse[stat] * kLog2e : INFINITY;   // rows past the end: P = exp2(-inf) = 0
-            st_dsum = r < L ? p.dsum[stat] : 0.f;
-        }
-    };
-    auto store_step = [&](char* stage) {
-        qst.store(stage, tid);
-        dost.store(stage + kTileBytes, tid);
-        if (tid < BQ) {
-            reinterpret_cast<float*>(stage + 2 * kTileBytes)[tid] = st_lse;
-            reinterpret_cast<float*>(stage + 2 * kTileBytes + BQ * 4)[tid] = st_dsum;
-        }
-    };
-
-    if (n_steps > 0) {
-        load_step(0);
-        store_step(lds);
-    }
-    __syncthreads();
-
     for (int step = 0; step < n_steps; ++step) {
+        wait_tile_loads();
+        __syncthreads();   // this step's tiles and statistics are in LDS; the other stage is free
         const char* stage = lds + (step & 1) * kStageBytes;
         const char* qtile = stage;
         const char* dotile = stage + kTileBytes;
         const float* lse_s = reinterpret_cast<const float*>(stage + 2 * kTileBytes);
         const float* dsum_s = lse_s + BQ;
         const bool more = step + 1 < n_steps;
-        if (more) load_step(step + 1);
+        char* next = lds + ((step + 1) & 1) * kStageBytes;
+        if (more) load_step(step + 1, next);
         const int row0 = (first_qt + step % per_head) * BQ;
 #pragma unroll
         for (int rb = 0; rb < 2; ++rb) {
@@ -262,10 +268,20 @@ __global__ __launch_bounds__(kThreads, 1) void bwd_dkv_kernel(BwdParams p) {
                 f32x16 s, dp;
 #pragma unroll
                 for (int i = 0; i < 16; ++i) { s[i] = 0.f; dp[i] = 0.f; }
+                {
+                    bf16x8 qf[KK];
 #pragma unroll
-                for (int kk = 0; kk < KK; ++kk) s = mfma(read_rowmajor_frag<D>(qtile, rb, kk, lane), kf[kk], s);
+                    for (int kk = 0; kk < KK; ++kk) qf[kk] = read_rowmajor_frag<D>(qtile, rb, kk, lane);
 #pragma unroll
-                for (int kk = 0; kk < KK; ++kk) dp = mfma(read_rowmajor_frag<D>(dotile, rb, kk, lane), vf[kk], dp);
+                    for (int kk = 0; kk < KK; ++kk) s = mfma(qf[kk], kf[kk], s);
+                }
+                {
+                    bf16x8 dof[KK];
+#pragma unroll
+                    for (int kk = 0; kk < KK; ++kk) dof[kk] = read_rowmajor_frag<D>(dotile, rb, kk, lane);
+#pragma unroll
+                    for (int kk = 0; kk < KK; ++kk) dp = mfma(dof[kk], vf[kk], dp);
+                }
                 const bool diag = qb0 < wave_key0 + 31;
 #pragma unroll
                 for (int i4 = 0; i4 < 4; ++i4) {
@@ -285,16 +301,19 @@ __global__ __launch_bounds__(kThreads, 1) void bwd_dkv_kernel(BwdParams p) {
                 for (int tt = 0; tt < 2; ++tt) {
                     const bf16x8 pf = frag_to_bf16(s, tt);
                     const bf16x8 dsf = frag_to_bf16(dp, tt);
+                    bf16x8 dotf[DB], qtf[DB];
 #pragma unroll
-                    for (int db = 0; db < DB; ++db) {
-                        dv[db] = mfma(read_transposed_frag<D>(dotile, db, rb * 2 + tt, lane), pf, dv[db]);
-                        dk[db] = mfma(read_transposed_frag<D>(qtile, db, rb * 2 + tt, lane), dsf, dk[db]);
-                    }
+                    for (int db = 0; db < DB; ++db) dotf[db] = read_transposed_frag<D>(dotile, db, rb * 2 + tt, lane);
+#pragma unroll
+                    for (int db = 0; db < DB; ++db) qtf[db] = read_transposed_frag<D>(qtile, db, rb * 2 + tt, lane);
+#pragma unroll
+                    for (int db = 0; db < DB; ++db) dv[db] = mfma(dotf[db], pf, dv[db]);
+#pragma unroll
+                    for (int db = 0; db < DB; ++db) dk[db] = mfma(qtf[db], dsf, dk[db]);
                 }
             }
         }
-        if (more) store_step(lds + ((step + 1) & 1) * kStageBytes);
-        __syncthreads();
+        if (more) store_stats(next);
     }
 
     if (valid) {

@@ -1,8 +1,8 @@
 // Forward kernel: one workgroup per (sequence, 128-row q tile, q head) work item.
 //
 // Each of the 4 waves owns 32 query rows.  For every 64-key tile of the causal prefix the
-// workgroup stages K and V in LDS (coalesced 16-byte loads, prefetched one tile ahead through
-// registers), each wave computes S^T = K Q^T on MFMA (keys along rows, its queries along
+// workgroup stages K and V in LDS (coalesced 16-byte global->LDS copies issued one tile ahead,
+// double buffered, one barrier per tile), each wave computes S^T = K Q^T on MFMA (keys along rows, its queries along
 // columns), runs the online-softmax recurrence with one lane per query, and feeds the bf16
 // P^T fragments straight back into MFMA as the B operand of O^T += V^T P^T, V^T being read
 // from the row-major V tile with the LDS transpose read.
@@ -17,11 +17,13 @@ __global__ __launch_bounds__(kThreads, 2) void fwd_kernel(FwdParams p) {
     constexpr int BQ = kFwdQTile, BK = kFwdKTile;
     constexpr int KK = D / 16;   // k-steps of S^T = K Q^T
     constexpr int DB = D / 32;   // 32-row blocks of O^T
-    __shared__ __attribute__((aligned(16))) char lds[2 * 2 * BK * D * 2];   // {K, V} x 2 stages
+    constexpr int kTileBytes = BK * D * 2;
+    __shared__ __attribute__((aligned(1024))) char lds[2 * 2 * kTileBytes];   // {K, V} x 2 stages
 
     const hspmd_work_item item = p.items[blockIdx.x];
     if (item.tile < 0) return;
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int L = item.seq_len, h = item.head, hk = h / p.group;
     const int q_row0 = item.tile * BQ;
     const int wave_row0 = q_row0 + wave * 32;
@@ -31,6 +33,12 @@ __global__ __launch_bounds__(kThreads, 2) void fwd_kernel(FwdParams p) {
     const uint16_t* qbase = p.q + (int64_t)item.token_start * p.q_stride + (int64_t)h * D;
     const uint16_t* kbase = p.k + (int64_t)item.token_start * p.kv_stride + (int64_t)hk * D;
     const uint16_t* vbase = p.v + (int64_t)item.token_start * p.kv_stride + (int64_t)hk * D;
+
+    const int kv_end = min(L, q_row0 + BQ);
+    const int n_tiles = (kv_end + BK - 1) / BK;
+
+    tile_load_async<D, BK>(lds, kbase, p.kv_stride, 0, L, wave, lane);
+    tile_load_async<D, BK>(lds + kTileBytes, vbase, p.kv_stride, 0, L, wave, lane);
 
     // this lane's query row as B operand fragments (zero for rows past the sequence end)
     bf16x8 qf[KK];
@@ -51,94 +59,88 @@ __global__ __launch_bounds__(kThreads, 2) void fwd_kernel(FwdParams p) {
     float l = 0.f;         // this lane's share of the running row sum
     const float c = p.scale_log2;
 
-    const int kv_end = min(L, q_row0 + BQ);
-    const int n_tiles = (kv_end + BK - 1) / BK;
-
-    TileStage<D, BK> kst, vst;
-    kst.load(kbase, p.kv_stride, 0, L, tid);
-    vst.load(vbase, p.kv_stride, 0, L, tid);
-    kst.store(lds, tid);
-    vst.store(lds + BK * D * 2, tid);
-    __syncthreads();
-
     for (int kt = 0; kt < n_tiles; ++kt) {
-        const char* ktile = lds + (kt & 1) * (2 * BK * D * 2);
-        const char* vtile = ktile + BK * D * 2;
-        const bool more = kt + 1 < n_tiles;
-        if (more) {
-            kst.load(kbase, p.kv_stride, (kt + 1) * BK, L, tid);
-            vst.load(vbase, p.kv_stride, (kt + 1) * BK, L, tid);
+        wait_tile_loads();
+        __syncthreads();   // tile kt has landed; every wave is done with the other stage
+        const char* ktile = lds + (kt & 1) * (2 * kTileBytes);
+        const char* vtile = ktile + kTileBytes;
+        if (kt + 1 < n_tiles) {
+            char* next = lds + ((kt + 1) & 1) * (2 * kTileBytes);
+            tile_load_async<D, BK>(next, kbase, p.kv_stride, (kt + 1) * BK, L, wave, lane);
+            tile_load_async<D, BK>(next + kTileBytes, vbase, p.kv_stride, (kt + 1) * BK, L, wave, lane);
         }
         const int key0 = kt * BK;
         // 32-key blocks whose first key is beyond this wave's last query are fully masked
         const int nblk = (key0 > wave_row0 + 31) ? 0 : ((key0 + 32 > wave_row0 + 31) ? 1 : 2);
-        if (nblk > 0) {
-            f32x16 s[2];
+        if (nblk == 0) continue;
+
+        f32x16 s[2];
 #pragma unroll
-            for (int jb = 0; jb < 2; ++jb) {
+        for (int jb = 0; jb < 2; ++jb) {
 #pragma unroll
-                for (int i = 0; i < 16; ++i) s[jb][i] = 0.f;
-                if (jb < nblk) {
+            for (int i = 0; i < 16; ++i) s[jb][i] = 0.f;
+            if (jb < nblk) {
+                bf16x8 kf[KK];
 #pragma unroll
-                    for (int kk = 0; kk < KK; ++kk) s[jb] = mfma(read_rowmajor_frag<D>(ktile, jb, kk, lane), qf[kk], s[jb]);
-                }
+                for (int kk = 0; kk < KK; ++kk) kf[kk] = read_rowmajor_frag<D>(ktile, jb, kk, lane);
+#pragma unroll
+                for (int kk = 0; kk < KK; ++kk) s[jb] = mfma(kf[kk], qf[kk], s[jb]);
             }
-            // causal mask, only where the block straddles the diagonal
+        }
+        // causal mask, only where the block straddles the diagonal
 #pragma unroll
-            for (int jb = 0; jb < 2; ++jb) {
-                const int kb = key0 + jb * 32;
-                if (jb >= nblk) {
+        for (int jb = 0; jb < 2; ++jb) {
+            const int kb = key0 + jb * 32;
+            if (jb >= nblk) {
 #pragma unroll
-                    for (int i = 0; i < 16; ++i) s[jb][i] = -INFINITY;
-                } else if (kb + 31 > wave_row0) {
+                for (int i = 0; i < 16; ++i) s[jb][i] = -INFINITY;
+            } else if (kb + 31 > wave_row0) {
 #pragma unroll
-                    for (int i = 0; i < 16; ++i)
-                        if (kb + acc_row(i, lane) > my_row) s[jb][i] = -INFINITY;
-                }
+                for (int i = 0; i < 16; ++i)
+                    if (kb + acc_row(i, lane) > my_row) s[jb][i] = -INFINITY;
             }
-            float tmax = s[0][0];
+        }
+        float tmax = s[0][0];
 #pragma unroll
-            for (int jb = 0; jb < 2; ++jb)
+        for (int jb = 0; jb < 2; ++jb)
 #pragma unroll
-                for (int i = 0; i < 16; ++i) tmax = fmaxf(tmax, s[jb][i]);
-            tmax = fmaxf(tmax, partner32(tmax));
-            const float m_new = fmaxf(m, tmax);
-            const float alpha = fast_exp2((m - m_new) * c);
-            const float mc = m_new * c;
-            m = m_new;
-            float psum = 0.f;
+            for (int i = 0; i < 16; ++i) tmax = fmaxf(tmax, s[jb][i]);
+        tmax = fmaxf(tmax, partner32(tmax));
+        const float m_new = fmaxf(m, tmax);
+        const float alpha = fast_exp2((m - m_new) * c);
+        const bool rescale = __any(m_new > m);      // wave-uniform: skip the accumulator rescale when no max moved
+        const float mc = m_new * c;
+        m = m_new;
+        float psum = 0.f;
 #pragma unroll
-            for (int jb = 0; jb < 2; ++jb)
+        for (int jb = 0; jb < 2; ++jb)
 #pragma unroll
-                for (int i = 0; i < 16; ++i) {
-                    const float e = fast_exp2(fmaf(s[jb][i], c, -mc));
-                    s[jb][i] = e;
-                    psum += e;
-                }
-            l = l * alpha + psum;
+            for (int i = 0; i < 16; ++i) {
+                const float e = fast_exp2(fmaf(s[jb][i], c, -mc));
+                s[jb][i] = e;
+                psum += e;
+            }
+        l = l * alpha + psum;
+        if (rescale) {
 #pragma unroll
             for (int db = 0; db < DB; ++db)
 #pragma unroll
                 for (int i = 0; i < 16; ++i) acc[db][i] *= alpha;
+        }
 #pragma unroll
-            for (int jb = 0; jb < 2; ++jb) {
-                if (jb < nblk) {
+        for (int jb = 0; jb < 2; ++jb) {
+            if (jb < nblk) {
 #pragma unroll
-                    for (int tt = 0; tt < 2; ++tt) {
-                        const bf16x8 pf = frag_to_bf16(s[jb], tt);
+                for (int tt = 0; tt < 2; ++tt) {
+                    const bf16x8 pf = frag_to_bf16(s[jb], tt);
+                    bf16x8 vf[DB];
 #pragma unroll
-                        for (int db = 0; db < DB; ++db)
-                            acc[db] = mfma(read_transposed_frag<D>(vtile, db, jb * 2 + tt, lane), pf, acc[db]);
-                    }
+                    for (int db = 0; db < DB; ++db) vf[db] = read_transposed_frag<D>(vtile, db, jb * 2 + tt, lane);
+#pragma unroll
+                    for (int db = 0; db < DB; ++db) acc[db] = mfma(vf[db], pf, acc[db]);
                 }
             }
         }
-        if (more) {
-            char* next = lds + ((kt + 1) & 1) * (2 * BK * D * 2);
-            kst.store(next, tid);
-            vst.store(next + BK * D * 2, tid);
-        }
-        __syncthreads();
     }
 
     const float l_row = l + partner32(l);
