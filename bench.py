@@ -120,7 +120,7 @@ def main() -> int:
     dq = torch.empty(T, hq, d, dtype=gd, device=dev)
     dk = torch.empty(T, hkv, d, dtype=gd, device=dev)
     dv = torch.empty_like(dk)
-    ws = torch.empty(hq * T * 4 + 16, dtype=torch.uint8, device=dev)
+    ws = torch.empty(2 * hq * T * 4 + 256, dtype=torch.uint8, device=dev)
     stream = torch.cuda.current_stream()
 
     def step():

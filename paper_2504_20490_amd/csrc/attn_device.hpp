@@ -140,6 +140,30 @@ __device__ __forceinline__ bf16x8 frag_to_bf16(const f32x16& c, int tt) {
 // row (MFMA M index within a 32-block) held in accumulator register i by this lane
 __device__ __forceinline__ int acc_row(int i, int lane) { return ((i >> 2) << 3) + ((lane >> 5) << 2) + (i & 3); }
 
+// writes 4 consecutive gradient elements of one row (bf16 or fp32)
+__device__ __forceinline__ void store_grad4(void* base, int64_t elem, bool f32, float a, float b, float c, float d) {
+    if (f32) {
+        *reinterpret_cast<f32x4*>(static_cast<float*>(base) + elem) = f32x4{a, b, c, d};
+    } else {
+        u32x2 w;
+        w[0] = pack_bf16(a, b);
+        w[1] = pack_bf16(c, d);
+        *reinterpret_cast<u32x2*>(static_cast<uint16_t*>(base) + elem) = w;
+    }
+}
+
+// Scheduling hint for one basic block: N times {1 MFMA, DS LDS reads, VA VALU instructions}, in that
+// order, as one pipeline with the given id (llvm.amdgcn.sched.group.barrier; arguments must be constants).
+template <int N, int DS, int VA, int ID>
+struct InterleaveHint {
+    static __device__ __forceinline__ void apply() {
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, ID);
+        if constexpr (DS > 0) __builtin_amdgcn_sched_group_barrier(0x100, DS, ID);
+        if constexpr (VA > 0) __builtin_amdgcn_sched_group_barrier(0x002, VA, ID);
+        if constexpr (N > 1) InterleaveHint<N - 1, DS, VA, ID>::apply();
+    }
+};
+
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
 }  // namespace hspmd

@@ -1,0 +1,327 @@
+// Backward dK/dV pass: one workgroup per (sequence, 128-key tile, kv head).
+//
+// Each of the 4 waves owns 32 keys (K and V rows stay in registers as MFMA B operands) and walks
+// over the query heads of the KV group and, per head, over the 32-row query blocks at or below the
+// diagonal.  Per block b:
+//     G1(b): S = Q_b K^T, dP = dO_b V^T                      (16 MFMA, operands read along tile rows)
+//     V(b) : P = exp2(S c - LSE log2e), dS = P (dP - D)      (VALU, one lane per key)
+//     G2(b): dV^T += dO_b^T P, dK^T += Q_b^T dS              (16 MFMA, operands by LDS transpose read)
+// The group loop runs inside the workgroup, so dK/dV need no atomics.
+//
+// The kernel holds two fp32 accumulators of 32 x D per wave, which leaves room for only one wave
+// per SIMD; nothing else can hide MFMA latency, so the loop is software-pipelined inside the wave.
+// Iteration i is one basic block in two phases:
+//     phase A: MFMA G2(i-1)  |  VALU V(i)            |  LDS reads: statistics of block i, Q/dO rows of block i+1
+//     phase B: MFMA G1(i+1)  |  pack P, dS to bf16   |  LDS reads: Q^T/dO^T of block i (for G2(i) next time)
+// so every MFMA operand is requested half an iteration (16 MFMAs) before its use and the exp/FMA work
+// of one block runs under the MFMAs of its neighbours.  Scheduling-group hints fix the interleaving.
+//
+// LDS: three stages of {Q tile, dO tile (64 rows each), LSE log2e [64], D [64]}.  While iterations
+// 2t and 2t+1 work on tile t and read ahead into tile t+1, tile t+2 is in flight (global -> LDS
+// copies) into the stage that tile t-1 occupied.  One barrier per tile.
+#include "attn_device.hpp"
+#include "kernels.hpp"
+#include "schedule.hpp"
+
+namespace hspmd {
+
+namespace {
+
+template <int D>
+struct DkvGeom {
+    static constexpr int KK = D / 16;                      // k-steps over head_dim; also frags per G2 operand
+    static constexpr int DB = D / 32;                      // 32-row blocks of dK^T / dV^T
+    static constexpr int kTileBytes = kDkvQTile * D * 2;   // one 64-row tile
+    static constexpr int kBlockBytes = 32 * D * 2;         // one 32-row block of it
+    static constexpr int kStatBytes = 1024;                // lse2[64] at +0, D[64] at +256
+    static constexpr int kStageBytes = 2 * kTileBytes + kStatBytes;
+    static constexpr int kStages = 3;
+};
+
+template <int D>
+struct DkvState {
+    using G = DkvGeom<D>;
+    bf16x8 kf[G::KK], vf[G::KK];           // this wave's 32 keys: K rows, V rows (B operands)
+    f32x16 dk[G::DB], dv[G::DB];           // dK^T, dV^T accumulators
+    f32x16 s_cur, dp_cur;                  // S, dP of block i
+    bf16x8 qf[G::KK], dof[G::KK];          // Q, dO rows of block i+1 (A operands of G1), live inside an iteration
+    bf16x8 qtf[G::KK], dotf[G::KK];        // Q^T, dO^T of block i-1 (A operands of G2), index tt*DB + db
+    bf16x8 pprev[2], dsprev[2];            // P, dS of block i-1 as bf16 B operands
+};
+
+// per-lane LDS byte addresses (stage base included) of the operand fragments
+template <int D>
+struct DkvAddr {
+    using G = DkvGeom<D>;
+    int rm[G::KK];         // row-major fragment kk of a 32-row block (Q tile; dO tile is + kTileBytes)
+    int tr[G::DB][2];      // transposed fragment: column block db, 8-row part
+    int st;                // statistics
+};
+
+__device__ __forceinline__ bf16x8 lds_read128(const char* lds, int addr) {
+    return *reinterpret_cast<const bf16x8*>(lds + addr);
+}
+
+template <int D>
+__device__ __forceinline__ bf16x8 lds_read_tr(const char* lds, int a0, int a1) {
+    const s16x4 lo = lds_transpose_read(lds + a0);
+    const s16x4 hi = lds_transpose_read(lds + a1);
+    union { struct { s16x4 a, b; } s; bf16x8 v; } u;
+    u.s.a = lo;
+    u.s.b = hi;
+    return u.v;
+}
+
+// One pipelined iteration on block i (RB = i & 1 is its position inside its 64-row tile).
+//   `cur`: addresses in the stage of block i's tile; `ahead`: addresses in the stage of block i+1's tile.
+// dkey = my_key - (first row of block i) - 4 * (lane / 32): element e of an accumulator fragment is a
+// masked (row < key) pair iff 8 * (e / 4) + e % 4 < dkey.
+template <int D, int RB, bool MASK>
+__device__ __forceinline__ void dkv_iteration(DkvState<D>& st, const char* lds, const DkvAddr<D>& ahead,
+                                              const DkvAddr<D>& cur, int dkey, float c) {
+    using G = DkvGeom<D>;
+    constexpr int KK = G::KK, DB = G::DB;
+    constexpr int NRB = RB ^ 1;   // block i+1 sits at the other position (of the next tile when RB == 1)
+
+    // ================= phase A =================
+    f32x4 lse4[4], ds4[4];
+#pragma unroll
+    for (int i4 = 0; i4 < 4; ++i4) {
+        lse4[i4] = *reinterpret_cast<const f32x4*>(lds + cur.st + RB * 128 + i4 * 32);
+        ds4[i4] = *reinterpret_cast<const f32x4*>(lds + cur.st + RB * 128 + i4 * 32 + 256);
+    }
+#pragma unroll
+    for (int kk = 0; kk < KK; ++kk) {
+        st.qf[kk] = lds_read128(lds, ahead.rm[kk] + NRB * G::kBlockBytes);
+        st.dof[kk] = lds_read128(lds, ahead.rm[kk] + NRB * G::kBlockBytes + G::kTileBytes);
+    }
+    // G2(i-1)
+#pragma unroll
+    for (int kk = 0; kk < KK; ++kk) {
+        const int tt = kk / DB, db = kk % DB;
+        st.dv[db] = mfma(st.dotf[kk], st.pprev[tt], st.dv[db]);
+        st.dk[db] = mfma(st.qtf[kk], st.dsprev[tt], st.dk[db]);
+    }
+    // V(i)
+    f32x16 pr, ds;
+#pragma unroll
+    for (int e = 0; e < 16; ++e) {
+        float pe = fast_exp2(fmaf(st.s_cur[e], c, -lse4[e >> 2][e & 3]));
+        if (MASK && (8 * (e >> 2) + (e & 3) < dkey)) pe = 0.f;
+        pr[e] = pe;
+        ds[e] = pe * (st.dp_cur[e] - ds4[e >> 2][e & 3]);
+    }
+    // per MFMA: 2 LDS reads (8 statistics + 2*KK fragments in all) and a share of V(i)'s VALU work
+    InterleaveHint<2 * KK, 2, (MASK ? 7 : 5), 0>::apply();
+    __builtin_amdgcn_sched_barrier(0);
+
+    // ================= phase B =================
+    bf16x8 nqtf[KK], ndotf[KK];
+#pragma unroll
+    for (int tt = 0; tt < 2; ++tt)
+#pragma unroll
+        for (int db = 0; db < DB; ++db) {
+            const int off = (RB * 2 + tt) * 16 * D * 2;   // 16 tile rows per k-step
+            nqtf[tt * DB + db] = lds_read_tr<D>(lds, cur.tr[db][0] + off, cur.tr[db][1] + off);
+            ndotf[tt * DB + db] = lds_read_tr<D>(lds, cur.tr[db][0] + off + G::kTileBytes, cur.tr[db][1] + off + G::kTileBytes);
+        }
+    // G1(i+1): two independent accumulation chains, interleaved
+    f32x16 s_next, dp_next;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) { s_next[i] = 0.f; dp_next[i] = 0.f; }
+#pragma unroll
+    for (int kk = 0; kk < KK; ++kk) {
+        s_next = mfma(st.qf[kk], st.kf[kk], s_next);
+        dp_next = mfma(st.dof[kk], st.vf[kk], dp_next);
+    }
+    st.pprev[0] = frag_to_bf16(pr, 0);
+    st.pprev[1] = frag_to_bf16(pr, 1);
+    st.dsprev[0] = frag_to_bf16(ds, 0);
+    st.dsprev[1] = frag_to_bf16(ds, 1);
+    st.s_cur = s_next;
+    st.dp_cur = dp_next;
+#pragma unroll
+    for (int kk = 0; kk < KK; ++kk) {
+        st.qtf[kk] = nqtf[kk];
+        st.dotf[kk] = ndotf[kk];
+    }
+    // per MFMA: 2 of the 4*KK transpose reads and one of the 16 packs
+    InterleaveHint<2 * KK, 2, 1, 1>::apply();
+    __builtin_amdgcn_sched_barrier(0);
+}
+
+}  // namespace
+
+template <int D>
+__global__ __launch_bounds__(kThreads, 1) void bwd_dkv_kernel(BwdParams p) {
+    using G = DkvGeom<D>;
+    constexpr int BKV = kDkvKTile, BQ = kDkvQTile;
+    constexpr int KK = G::KK, DB = G::DB;
+    __shared__ __attribute__((aligned(1024))) char lds[G::kStages * G::kStageBytes];
+
+    const hspmd_work_item item = p.items[blockIdx.x];
+    if (item.tile < 0) return;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int L = item.seq_len, g = item.head;
+    const int key0 = item.tile * BKV;
+    const int wave_key0 = key0 + wave * 32;
+    const int my_key = wave_key0 + (lane & 31);
+    const int hh = lane >> 5;
+    const bool valid = my_key < L;
+
+    const uint16_t* kbase = p.k + (int64_t)item.token_start * p.kv_stride + (int64_t)g * D;
+    const uint16_t* vbase = p.v + (int64_t)item.token_start * p.kv_stride + (int64_t)g * D;
+
+    // tiles: for each head of the group, q tiles first_qt .. n_qt-1 (rows at or below the diagonal)
+    const int first_qt = key0 / BQ;
+    const int n_qt = (L + BQ - 1) / BQ;
+    const int per_head = n_qt - first_qt;
+    const int n_tiles = per_head * p.group;
+
+    // global -> LDS copy of tile u (flattened over heads) into a stage, statistics included
+    auto load_tile = [&](int u, int stage_index) {
+        char* stage = lds + stage_index * G::kStageBytes;
+        const int hq = g * p.group + u / per_head;
+        const int row0 = (first_qt + u % per_head) * BQ;
+        const uint16_t* qb = p.q + (int64_t)item.token_start * p.q_stride + (int64_t)hq * D;
+        const uint16_t* dob = p.d_o + ((int64_t)item.token_start * p.q_heads + hq) * D;
+        tile_load_async<D, BQ>(stage, qb, p.q_stride, row0, L, wave, lane);
+        tile_load_async<D, BQ>(stage + G::kTileBytes, dob, (int64_t)p.q_heads * D, row0, L, wave, lane);
+        if (wave < 2) {
+            // wave 0: LSE log2e of the 64 rows; wave 1: D.  Rows past the end read +inf (P = 0) / a finite duplicate.
+            const int r = row0 + lane;
+            const int64_t stat = (int64_t)hq * p.total_tokens + item.token_start + min(r, L - 1);
+            const float* src = (wave == 0) ? ((r < L) ? p.lse2 + stat : p.inf_pad) : p.dsum + stat;
+            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)src,
+                                             (__attribute__((address_space(3))) void*)(stage + 2 * G::kTileBytes + wave * 256),
+                                             4, 0, 0);
+        }
+    };
+
+    load_tile(0, 0);
+    if (n_tiles > 1) load_tile(1, 1);
+
+    DkvState<D> st;
+#pragma unroll
+    for (int kk = 0; kk < KK; ++kk) {
+        union { u32x4 u; bf16x8 v; } a, b;
+        a.u = u32x4{0u, 0u, 0u, 0u};
+        b.u = u32x4{0u, 0u, 0u, 0u};
+        if (valid) {
+            a.u = *reinterpret_cast<const u32x4*>(kbase + (int64_t)my_key * p.kv_stride + kk * 16 + hh * 8);
+            b.u = *reinterpret_cast<const u32x4*>(vbase + (int64_t)my_key * p.kv_stride + kk * 16 + hh * 8);
+        }
+        st.kf[kk] = a.v;
+        st.vf[kk] = b.v;
+    }
+#pragma unroll
+    for (int db = 0; db < DB; ++db)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) { st.dk[db][i] = 0.f; st.dv[db][i] = 0.f; }
+    const float c = p.scale_log2;
+
+    // per-lane fragment offsets inside a stage
+    DkvAddr<D> off;
+#pragma unroll
+    for (int kk = 0; kk < KK; ++kk) off.rm[kk] = tile_offset<D>(lane & 31, kk * 16 + hh * 8);
+    {
+        const int c16 = lane & 15;
+        const int row = (hh << 2) + (c16 >> 2);
+#pragma unroll
+        for (int db = 0; db < DB; ++db) {
+            const int col = db * 32 + (((lane >> 4) & 1) << 4) + ((c16 & 3) << 2);
+            off.tr[db][0] = tile_offset<D>(row, col);
+            off.tr[db][1] = tile_offset<D>(row + 8, col);
+        }
+    }
+    off.st = 2 * G::kTileBytes + hh * 16;
+    auto at_stage = [&](int stage_index) {
+        DkvAddr<D> a;
+        const int base = stage_index * G::kStageBytes;
+#pragma unroll
+        for (int kk = 0; kk < KK; ++kk) a.rm[kk] = off.rm[kk] + base;
+#pragma unroll
+        for (int db = 0; db < DB; ++db) { a.tr[db][0] = off.tr[db][0] + base; a.tr[db][1] = off.tr[db][1] + base; }
+        a.st = off.st + base;
+        return a;
+    };
+
+    wait_tile_loads();
+    __syncthreads();   // tiles 0 and 1 are in LDS
+
+    // prologue: G1(0) computed directly; P = dS = 0 for the non-existent block -1
+    {
+        const DkvAddr<D> a0 = at_stage(0);
+#pragma unroll
+        for (int i = 0; i < 16; ++i) { st.s_cur[i] = 0.f; st.dp_cur[i] = 0.f; }
+#pragma unroll
+        for (int kk = 0; kk < KK; ++kk) {
+            st.s_cur = mfma(lds_read128(lds, a0.rm[kk]), st.kf[kk], st.s_cur);
+            st.dp_cur = mfma(lds_read128(lds, a0.rm[kk] + G::kTileBytes), st.vf[kk], st.dp_cur);
+        }
+#pragma unroll
+        for (int kk = 0; kk < KK; ++kk) {
+            st.qtf[kk] = lds_read128(lds, a0.rm[kk]);      // any finite operand: it meets P = dS = 0
+            st.dotf[kk] = st.qtf[kk];
+        }
+        union { u32x4 u; bf16x8 v; } z;
+        z.u = u32x4{0u, 0u, 0u, 0u};
+        st.pprev[0] = st.pprev[1] = st.dsprev[0] = st.dsprev[1] = z.v;
+    }
+
+    int qt = first_qt;   // q tile index of tile u inside its head
+    for (int u = 0; u < n_tiles; ++u) {
+        if (u > 0) {
+            wait_tile_loads();
+            __syncthreads();   // tile u+1 has landed; every wave is done with tile u-1
+        }
+        if (u + 2 < n_tiles) load_tile(u + 2, (u + 2) % G::kStages);
+        const DkvAddr<D> cur = at_stage(u % G::kStages);
+        // block 2u+2 lives in the next tile; the last tile has none: it re-reads itself (result unused)
+        const DkvAddr<D> next = at_stage((u + 1 < n_tiles ? u + 1 : u) % G::kStages);
+        const int row0 = qt * BQ;
+        const int dkey0 = my_key - row0 - 4 * hh;
+        // the causal mask is applied branch-free in every iteration: two code paths that each carry
+        // ~450 live registers cost far more in copies at their join than 32 compare/select pairs
+        dkv_iteration<D, 0, true>(st, lds, cur, cur, dkey0, c);
+        dkv_iteration<D, 1, true>(st, lds, next, cur, dkey0 - 32, c);
+        if (++qt == n_qt) qt = first_qt;
+    }
+
+    // epilogue: G2 of the last block
+#pragma unroll
+    for (int kk = 0; kk < KK; ++kk) {
+        const int tt = kk / DB, db = kk % DB;
+        st.dv[db] = mfma(st.dotf[kk], st.pprev[tt], st.dv[db]);
+        st.dk[db] = mfma(st.qtf[kk], st.dsprev[tt], st.dk[db]);
+    }
+
+    if (valid) {
+        const int64_t row_elem = ((int64_t)(item.token_start + my_key) * p.kv_heads + g) * D;
+        const bool f32 = p.grad_f32 != 0;
+#pragma unroll
+        for (int db = 0; db < DB; ++db)
+#pragma unroll
+            for (int i4 = 0; i4 < 4; ++i4) {
+                const int64_t e = row_elem + db * 32 + i4 * 8 + hh * 4;
+                store_grad4(p.dk, e, f32, st.dk[db][4 * i4 + 0] * p.scale, st.dk[db][4 * i4 + 1] * p.scale,
+                            st.dk[db][4 * i4 + 2] * p.scale, st.dk[db][4 * i4 + 3] * p.scale);
+                store_grad4(p.dv, e, f32, st.dv[db][4 * i4 + 0], st.dv[db][4 * i4 + 1], st.dv[db][4 * i4 + 2],
+                            st.dv[db][4 * i4 + 3]);
+            }
+    }
+}
+
+hipError_t launch_bwd_dkv(const BwdParams& p, int head_dim, int64_t num_items, hipStream_t stream) {
+    if (num_items == 0) return hipSuccess;
+    const dim3 grid((unsigned)num_items), block(kThreads);
+    if (head_dim == 128) {
+        hipLaunchKernelGGL(bwd_dkv_kernel<128>, grid, block, 0, stream, p);
+    } else {
+        hipLaunchKernelGGL(bwd_dkv_kernel<64>, grid, block, 0, stream, p);
+    }
+    return hipGetLastError();
+}
+
+}  // namespace hspmd

@@ -193,7 +193,8 @@ int64_t hspmd_attn_plan_num_items(const hspmd_attn_plan* plan, hspmd_list_kind k
 
 size_t hspmd_attn_bwd_workspace_bytes(const hspmd_attn_plan* plan) {
     if (!plan) return 0;
-    return (size_t)plan->q_heads * (size_t)plan->total_tokens * sizeof(float);
+    // D[Hq,T], LSE*log2(e) [Hq,T], and 16 floats of +inf
+    return (2 * (size_t)plan->q_heads * (size_t)plan->total_tokens + 16) * sizeof(float);
 }
 
 static hspmd_status check_strides(const hspmd_attn_plan* plan, int64_t q_token_stride, int64_t kv_token_stride) {
@@ -261,6 +262,8 @@ hspmd_status hspmd_attn_varlen_bwd(const hspmd_attn_plan* plan, const void* q, c
     p.d_o = static_cast<const uint16_t*>(d_o);
     p.lse = lse;
     p.dsum = static_cast<float*>(workspace);
+    p.lse2 = p.dsum + (size_t)plan->q_heads * (size_t)plan->total_tokens;
+    p.inf_pad = p.lse2 + (size_t)plan->q_heads * (size_t)plan->total_tokens;
     p.dq = dq;
     p.dk = dk;
     p.dv = dv;

@@ -27,7 +27,9 @@ struct BwdParams {
     const uint16_t* o;
     const uint16_t* d_o;
     const float* lse;
-    float* dsum;                   // D[Hq, T] = rowsum(dO * O), fp32 workspace
+    float* dsum;                   // workspace: D[Hq, T] = rowsum(dO * O)
+    float* lse2;                   // workspace: lse * log2(e), [Hq, T]
+    float* inf_pad;                // workspace: 16 floats holding +inf
     void* dq;
     void* dk;
     void* dv;
