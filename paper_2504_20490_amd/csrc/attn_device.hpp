@@ -54,33 +54,111 @@ __device__ __forceinline__ int tile_offset(int row, int col) {
     return row * (D * 2) + (swizzle<D>(row, col >> 3) << 4) + ((col & 7) << 1);
 }
 
-// Global -> LDS copy of a ROWS x D tile without a trip through registers (global_load_lds_dwordx4).
+// One wave-wide global -> LDS copy of SIZE bytes per lane (global_load_lds_dword / _dwordx4): lane i's
+// data lands at lds_dst + SIZE * i.  Written as inline assembly on purpose: when the compiler knows that
+// such copies are in flight it makes every later LDS transpose read wait for all of them (vmcnt(0)),
+// which serialises the prefetch.  Here the copies are ordered by hand instead: the issuing wave waits
+// with wait_tile_loads*() before the workgroup barrier that publishes the tile.  "memory" keeps the
+// compiler from moving LDS accesses across the issue point.  M0 (the LDS base of the copy) is written
+// inside the statement; nothing else in these kernels keeps a value in M0 (the compiler sets it up
+// immediately before each of its own uses), and it is a reserved register that cannot be named as a clobber.
+template <int SIZE>
+__device__ __forceinline__ void global_to_lds(const void* src, char* lds_dst) {
+    static_assert(SIZE == 4 || SIZE == 16, "dword or dwordx4");
+    const uint32_t m0 = __builtin_amdgcn_readfirstlane(
+        (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char*)lds_dst);
+    if constexpr (SIZE == 16) {
+        asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off"
+                     :: "s"(m0), "v"(src) : "memory");
+    } else {
+        asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dword %1, off"
+                     :: "s"(m0), "v"(src) : "memory");
+    }
+}
+
+// Same copy with the global address given as a wave-uniform base plus a per-lane unsigned byte offset
+// (the saddr form): the per-lane offsets of a tile are loop-invariant, so issuing a tile costs no VALU work.
+template <int SIZE>
+__device__ __forceinline__ void global_to_lds(const void* uniform_base, uint32_t lane_byte_offset, char* lds_dst) {
+    static_assert(SIZE == 4 || SIZE == 16, "dword or dwordx4");
+    const uint32_t m0 = __builtin_amdgcn_readfirstlane(
+        (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char*)lds_dst);
+    // readfirstlane returns a signed int: widen each half as unsigned, or a low half with bit 31 set
+    // would sign-extend over the high half and produce a wild address
+    const uint64_t b = (uint64_t)(uintptr_t)uniform_base;
+    const uint32_t lo = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)b);
+    const uint32_t hi = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)(b >> 32));
+    const uint64_t base = ((uint64_t)hi << 32) | (uint64_t)lo;
+    if constexpr (SIZE == 16) {
+        asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+                     :: "s"(m0), "v"(lane_byte_offset), "s"(base) : "memory");
+    } else {
+        asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dword %1, %2"
+                     :: "s"(m0), "v"(lane_byte_offset), "s"(base) : "memory");
+    }
+}
+
+// Global -> LDS copy of a ROWS x D tile without a trip through registers.
 // One wave instruction moves 64 x 16 B into 1024 consecutive LDS bytes (lane i lands at base + 16 i),
 // so the swizzle is applied on the global side: the lane that owns physical chunk p of row r
 // fetches logical chunk p ^ f(r).  Rows at or beyond seq_len are replaced by the last valid row:
 // they only ever meet a zero weight, and a finite duplicate keeps 0 * x = 0.
 // The copies are asynchronous: wait_tile_loads() + a workgroup barrier make them visible.
 template <int D, int ROWS>
-__device__ __forceinline__ void tile_load_async(char* tile, const uint16_t* slab, int64_t stride, int row0,
-                                                int seq_len, int wave, int lane) {
-    constexpr int kChunksPerRow = D / 8;
-    constexpr int kRowsPerInstr = 64 / kChunksPerRow;
-    constexpr int kInstr = ROWS / kRowsPerInstr;
+struct TileCopy {
+    static constexpr int kChunksPerRow = D / 8;
+    static constexpr int kRowsPerInstr = 64 / kChunksPerRow;
+    static constexpr int kInstr = ROWS / kRowsPerInstr;
+    static constexpr int kPerWave = kInstr / 4;
     static_assert(kInstr % 4 == 0, "tile must divide over 4 waves");
+    uint32_t off[kPerWave];   // byte offset of this lane's chunk from the tile's first row, per instruction
+    int chunk_bytes;          // swizzled column offset (bytes) of this lane's chunk: same for every instruction
+    int row_in_instr;
+
+    // stride: token stride of the tensor in elements (loop-invariant)
+    __device__ __forceinline__ void init(int64_t stride, int wave, int lane) {
+        row_in_instr = lane / kChunksPerRow;
 #pragma unroll
-    for (int i = 0; i < kInstr / 4; ++i) {
-        const int blk = i * 4 + wave;
-        const int r = blk * kRowsPerInstr + lane / kChunksPerRow;
-        const int c = swizzle<D>(r, lane % kChunksPerRow);
-        const int row = min(row0 + r, seq_len - 1);
-        const uint16_t* src = slab + (int64_t)row * stride + c * 8;
-        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)src,
-                                         (__attribute__((address_space(3))) void*)(tile + blk * 1024), 16, 0, 0);
+        for (int i = 0; i < kPerWave; ++i) {
+            const int r = (i * 4 + wave) * kRowsPerInstr + row_in_instr;
+            const int c = swizzle<D>(r, lane % kChunksPerRow);
+            off[i] = (uint32_t)(r * (int)stride + c * 8) * 2u;
+        }
     }
-}
+    // whole tile inside the sequence: rows row0 .. row0+ROWS-1 all exist.  slab points at row 0, column 0.
+    __device__ __forceinline__ void issue_full(char* tile, const uint16_t* slab, int64_t stride, int row0, int wave) const {
+        const uint16_t* base = slab + (int64_t)row0 * stride;
+#pragma unroll
+        for (int i = 0; i < kPerWave; ++i) global_to_lds<16>(base, off[i], tile + (i * 4 + wave) * 1024);
+    }
+    // tile that runs past the end of the sequence: per-lane row clamp
+    __device__ __forceinline__ void issue_clamped(char* tile, const uint16_t* slab, int64_t stride, int row0, int seq_len,
+                                                  int wave, int lane) const {
+#pragma unroll
+        for (int i = 0; i < kPerWave; ++i) {
+            const int blk = i * 4 + wave;
+            const int r = blk * kRowsPerInstr + row_in_instr;
+            const int c = swizzle<D>(r, lane % kChunksPerRow);
+            const int row = min(row0 + r, seq_len - 1);
+            global_to_lds<16>(slab + (int64_t)row * stride + c * 8, tile + blk * 1024);
+        }
+    }
+    __device__ __forceinline__ void issue(char* tile, const uint16_t* slab, int64_t stride, int row0, int seq_len,
+                                          int wave, int lane) const {
+        if (row0 + ROWS <= seq_len) issue_full(tile, slab, stride, row0, wave);
+        else issue_clamped(tile, slab, stride, row0, seq_len, wave, lane);
+    }
+};
 
 // all of this wave's outstanding global loads (direct-to-LDS copies included) have landed
 __device__ __forceinline__ void wait_tile_loads() { __builtin_amdgcn_s_waitcnt(0x0F70); }   // vmcnt(0)
+
+// all but the newest N (N < 16) of this wave's global loads have landed (loads complete in order)
+template <int N>
+__device__ __forceinline__ void wait_tile_loads_except() {
+    static_assert(N >= 0 && N < 16, "vmcnt field");
+    __builtin_amdgcn_s_waitcnt(0x0F70 | N);
+}
 
 // A operand whose k runs along the tile's rows' columns: 8 consecutive elements of one row.
 //   rows: 32-row block `rb`; k-step kk covers columns 16*kk .. 16*kk+15
@@ -94,8 +172,9 @@ __device__ __forceinline__ bf16x8 read_rowmajor_frag(const char* tile, int rb, i
 // consecutive 16-bit elements (row i, columns 4c .. 4c+3 of a 4 x 16 block); lane n of the group
 // receives column n of that block, i.e. elements (0,n), (1,n), (2,n), (3,n).
 __device__ __forceinline__ s16x4 lds_transpose_read(const char* p) {
-    return __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-        (__attribute__((address_space(3))) s16x4*)(uintptr_t)(p));
+    // a plain address-space cast (no trip through an integer) keeps the pointer's provenance, so the compiler
+    // can tell these reads from the in-flight global->LDS copies and does not wait for those first
+    return __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)(const_cast<char*>(p)));
 }
 
 // A operand whose k runs DOWN the tile's rows (the tile is used transposed):

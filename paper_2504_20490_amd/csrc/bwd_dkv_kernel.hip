@@ -16,9 +16,11 @@
 // so every MFMA operand is requested half an iteration (16 MFMAs) before its use and the exp/FMA work
 // of one block runs under the MFMAs of its neighbours.  Scheduling-group hints fix the interleaving.
 //
-// LDS: three stages of {Q tile, dO tile (64 rows each), LSE log2e [64], D [64]}.  While iterations
-// 2t and 2t+1 work on tile t and read ahead into tile t+1, tile t+2 is in flight (global -> LDS
-// copies) into the stage that tile t-1 occupied.  One barrier per tile.
+// LDS: four stages of {Q tile, dO tile (64 rows each), LSE log2e [64], D [64]}.  While iterations
+// 2t and 2t+1 work on tile t and read ahead into tile t+1, tiles t+2 and t+3 are in flight
+// (global -> LDS copies; t+3 goes into the stage that tile t-1 occupied).  One barrier per tile.
+#include <type_traits>
+
 #include "attn_device.hpp"
 #include "kernels.hpp"
 #include "schedule.hpp"
@@ -35,7 +37,7 @@ struct DkvGeom {
     static constexpr int kBlockBytes = 32 * D * 2;         // one 32-row block of it
     static constexpr int kStatBytes = 1024;                // lse2[64] at +0, D[64] at +256
     static constexpr int kStageBytes = 2 * kTileBytes + kStatBytes;
-    static constexpr int kStages = 3;
+    static constexpr int kStages = 4;
 };
 
 template <int D>
@@ -102,51 +104,47 @@ __device__ __forceinline__ void dkv_iteration(DkvState<D>& st, const char* lds, 
         st.dv[db] = mfma(st.dotf[kk], st.pprev[tt], st.dv[db]);
         st.dk[db] = mfma(st.qtf[kk], st.dsprev[tt], st.dk[db]);
     }
-    // V(i)
-    f32x16 pr, ds;
+    // V(i): P first (S is complete long before dP), then dS; packed to bf16 pair by pair
+    float pe[16];
 #pragma unroll
     for (int e = 0; e < 16; ++e) {
-        float pe = fast_exp2(fmaf(st.s_cur[e], c, -lse4[e >> 2][e & 3]));
-        if (MASK && (8 * (e >> 2) + (e & 3) < dkey)) pe = 0.f;
-        pr[e] = pe;
-        ds[e] = pe * (st.dp_cur[e] - ds4[e >> 2][e & 3]);
+        pe[e] = fast_exp2(fmaf(st.s_cur[e], c, -lse4[e >> 2][e & 3]));
+        if (MASK && (8 * (e >> 2) + (e & 3) < dkey)) pe[e] = 0.f;
+    }
+    u32x4 pw[2], dw[2];
+#pragma unroll
+    for (int e = 0; e < 16; e += 2) {
+        const float d0 = pe[e] * (st.dp_cur[e] - ds4[e >> 2][e & 3]);
+        const float d1 = pe[e + 1] * (st.dp_cur[e + 1] - ds4[(e + 1) >> 2][(e + 1) & 3]);
+        pw[e >> 3][(e >> 1) & 3] = pack_bf16(pe[e], pe[e + 1]);
+        dw[e >> 3][(e >> 1) & 3] = pack_bf16(d0, d1);
     }
     // per MFMA: 2 LDS reads (8 statistics + 2*KK fragments in all) and a share of V(i)'s VALU work
-    InterleaveHint<2 * KK, 2, (MASK ? 7 : 5), 0>::apply();
+    InterleaveHint<2 * KK, 2, (MASK ? 9 : 7), 0>::apply();
     __builtin_amdgcn_sched_barrier(0);
 
     // ================= phase B =================
-    bf16x8 nqtf[KK], ndotf[KK];
+    union { u32x4 u; bf16x8 v; } cv;
+    cv.u = pw[0]; st.pprev[0] = cv.v;
+    cv.u = pw[1]; st.pprev[1] = cv.v;
+    cv.u = dw[0]; st.dsprev[0] = cv.v;
+    cv.u = dw[1]; st.dsprev[1] = cv.v;
 #pragma unroll
     for (int tt = 0; tt < 2; ++tt)
 #pragma unroll
         for (int db = 0; db < DB; ++db) {
             const int off = (RB * 2 + tt) * 16 * D * 2;   // 16 tile rows per k-step
-            nqtf[tt * DB + db] = lds_read_tr<D>(lds, cur.tr[db][0] + off, cur.tr[db][1] + off);
-            ndotf[tt * DB + db] = lds_read_tr<D>(lds, cur.tr[db][0] + off + G::kTileBytes, cur.tr[db][1] + off + G::kTileBytes);
+            st.qtf[tt * DB + db] = lds_read_tr<D>(lds, cur.tr[db][0] + off, cur.tr[db][1] + off);
+            st.dotf[tt * DB + db] = lds_read_tr<D>(lds, cur.tr[db][0] + off + G::kTileBytes, cur.tr[db][1] + off + G::kTileBytes);
         }
-    // G1(i+1): two independent accumulation chains, interleaved
-    f32x16 s_next, dp_next;
+    // G1(i+1): the S chain first, so that the next iteration's exp work never waits for it
 #pragma unroll
-    for (int i = 0; i < 16; ++i) { s_next[i] = 0.f; dp_next[i] = 0.f; }
+    for (int i = 0; i < 16; ++i) { st.s_cur[i] = 0.f; st.dp_cur[i] = 0.f; }
 #pragma unroll
-    for (int kk = 0; kk < KK; ++kk) {
-        s_next = mfma(st.qf[kk], st.kf[kk], s_next);
-        dp_next = mfma(st.dof[kk], st.vf[kk], dp_next);
-    }
-    st.pprev[0] = frag_to_bf16(pr, 0);
-    st.pprev[1] = frag_to_bf16(pr, 1);
-    st.dsprev[0] = frag_to_bf16(ds, 0);
-    st.dsprev[1] = frag_to_bf16(ds, 1);
-    st.s_cur = s_next;
-    st.dp_cur = dp_next;
+    for (int kk = 0; kk < KK; ++kk) st.s_cur = mfma(st.qf[kk], st.kf[kk], st.s_cur);
 #pragma unroll
-    for (int kk = 0; kk < KK; ++kk) {
-        st.qtf[kk] = nqtf[kk];
-        st.dotf[kk] = ndotf[kk];
-    }
-    // per MFMA: 2 of the 4*KK transpose reads and one of the 16 packs
-    InterleaveHint<2 * KK, 2, 1, 1>::apply();
+    for (int kk = 0; kk < KK; ++kk) st.dp_cur = mfma(st.dof[kk], st.vf[kk], st.dp_cur);
+    InterleaveHint<2 * KK, 2, 0, 1>::apply();   // per MFMA: 2 of the 4*KK transpose reads
     __builtin_amdgcn_sched_barrier(0);
 }
 
@@ -173,6 +171,7 @@ __global__ __launch_bounds__(kThreads, 1) void bwd_dkv_kernel(BwdParams p) {
     const uint16_t* kbase = p.k + (int64_t)item.token_start * p.kv_stride + (int64_t)g * D;
     const uint16_t* vbase = p.v + (int64_t)item.token_start * p.kv_stride + (int64_t)g * D;
 
+    constexpr int kLoadsPerTile = 2 * (BQ * D * 2 / 1024) / 4 + 1;   // per wave: Q and dO chunks + one statistics copy
     // tiles: for each head of the group, q tiles first_qt .. n_qt-1 (rows at or below the diagonal)
     const int first_qt = key0 / BQ;
     const int n_qt = (L + BQ - 1) / BQ;
@@ -180,27 +179,38 @@ __global__ __launch_bounds__(kThreads, 1) void bwd_dkv_kernel(BwdParams p) {
     const int n_tiles = per_head * p.group;
 
     // global -> LDS copy of tile u (flattened over heads) into a stage, statistics included
+    TileCopy<D, BQ> qcopy, docopy;
+    qcopy.init(p.q_stride, wave, lane);
+    docopy.init((int64_t)p.q_heads * D, wave, lane);
     auto load_tile = [&](int u, int stage_index) {
         char* stage = lds + stage_index * G::kStageBytes;
         const int hq = g * p.group + u / per_head;
         const int row0 = (first_qt + u % per_head) * BQ;
         const uint16_t* qb = p.q + (int64_t)item.token_start * p.q_stride + (int64_t)hq * D;
         const uint16_t* dob = p.d_o + ((int64_t)item.token_start * p.q_heads + hq) * D;
-        tile_load_async<D, BQ>(stage, qb, p.q_stride, row0, L, wave, lane);
-        tile_load_async<D, BQ>(stage + G::kTileBytes, dob, (int64_t)p.q_heads * D, row0, L, wave, lane);
-        if (wave < 2) {
-            // wave 0: LSE log2e of the 64 rows; wave 1: D.  Rows past the end read +inf (P = 0) / a finite duplicate.
+        // even waves: LSE log2e of the 64 rows; odd waves: D (waves 2, 3 repeat the copies of waves 0, 1 so that
+        // every wave has the same number of loads in flight)
+        const int which = wave & 1;
+        char* stat_dst = stage + 2 * G::kTileBytes + which * 256;
+        const int64_t stat0 = (int64_t)hq * p.total_tokens + item.token_start + row0;
+        if (row0 + BQ <= L) {
+            qcopy.issue_full(stage, qb, p.q_stride, row0, wave);
+            docopy.issue_full(stage + G::kTileBytes, dob, (int64_t)p.q_heads * D, row0, wave);
+            global_to_lds<4>((which == 0 ? p.lse2 : p.dsum) + stat0, (uint32_t)lane * 4u, stat_dst);
+        } else {
+            // last tile of a head: rows past the end read a finite duplicate; their LSE reads +inf, so P = 0
+            qcopy.issue_clamped(stage, qb, p.q_stride, row0, L, wave, lane);
+            docopy.issue_clamped(stage + G::kTileBytes, dob, (int64_t)p.q_heads * D, row0, L, wave, lane);
             const int r = row0 + lane;
-            const int64_t stat = (int64_t)hq * p.total_tokens + item.token_start + min(r, L - 1);
-            const float* src = (wave == 0) ? ((r < L) ? p.lse2 + stat : p.inf_pad) : p.dsum + stat;
-            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)src,
-                                             (__attribute__((address_space(3))) void*)(stage + 2 * G::kTileBytes + wave * 256),
-                                             4, 0, 0);
+            const int64_t stat = stat0 + min(lane, L - 1 - row0);
+            const float* src = (which == 0) ? ((r < L) ? p.lse2 + stat : p.inf_pad) : p.dsum + stat;
+            global_to_lds<4>(src, stat_dst);
         }
     };
 
     load_tile(0, 0);
     if (n_tiles > 1) load_tile(1, 1);
+    if (n_tiles > 2) load_tile(2, 2);
 
     DkvState<D> st;
 #pragma unroll
@@ -248,7 +258,7 @@ __global__ __launch_bounds__(kThreads, 1) void bwd_dkv_kernel(BwdParams p) {
     };
 
     wait_tile_loads();
-    __syncthreads();   // tiles 0 and 1 are in LDS
+    __syncthreads();   // tiles 0, 1 and 2 are in LDS
 
     // prologue: G1(0) computed directly; P = dS = 0 for the non-existent block -1
     {
@@ -270,23 +280,32 @@ __global__ __launch_bounds__(kThreads, 1) void bwd_dkv_kernel(BwdParams p) {
         st.pprev[0] = st.pprev[1] = st.dsprev[0] = st.dsprev[1] = z.v;
     }
 
-    int qt = first_qt;   // q tile index of tile u inside its head
-    for (int u = 0; u < n_tiles; ++u) {
+    // One tile = two iterations.  Tiles 0 and 1 of every head hold the (row < key) pairs of some wave and
+    // take the masked code; all later tiles take the unmasked code.  Two loops instead of a branch inside
+    // one: the ~400 live registers then meet at a join once per head, not once per iteration.
+    int stage = 0;   // stage of tile u
+    auto tile_step = [&](int u, int qt, auto masked) {
+        constexpr bool kMask = decltype(masked)::value;
         if (u > 0) {
-            wait_tile_loads();
-            __syncthreads();   // tile u+1 has landed; every wave is done with tile u-1
+            // tile u+1 must have landed; the copies of tile u+2 (the newest kLoadsPerTile of this wave) may still fly
+            if (u + 2 < n_tiles) wait_tile_loads_except<kLoadsPerTile>(); else wait_tile_loads();
+            __syncthreads();   // ... for every wave; and every wave is done with tile u-1
         }
-        if (u + 2 < n_tiles) load_tile(u + 2, (u + 2) % G::kStages);
-        const DkvAddr<D> cur = at_stage(u % G::kStages);
+        const int stage1 = stage + 1 == G::kStages ? 0 : stage + 1;
+        const int stage3 = (stage + 3) % G::kStages;
+        if (u + 3 < n_tiles) load_tile(u + 3, stage3);
+        const DkvAddr<D> cur = at_stage(stage);
         // block 2u+2 lives in the next tile; the last tile has none: it re-reads itself (result unused)
-        const DkvAddr<D> next = at_stage((u + 1 < n_tiles ? u + 1 : u) % G::kStages);
-        const int row0 = qt * BQ;
-        const int dkey0 = my_key - row0 - 4 * hh;
-        // the causal mask is applied branch-free in every iteration: two code paths that each carry
-        // ~450 live registers cost far more in copies at their join than 32 compare/select pairs
-        dkv_iteration<D, 0, true>(st, lds, cur, cur, dkey0, c);
-        dkv_iteration<D, 1, true>(st, lds, next, cur, dkey0 - 32, c);
-        if (++qt == n_qt) qt = first_qt;
+        const DkvAddr<D> next = at_stage(u + 1 < n_tiles ? stage1 : stage);
+        const int dkey0 = my_key - qt * BQ - 4 * hh;
+        dkv_iteration<D, 0, kMask>(st, lds, cur, cur, dkey0, c);
+        dkv_iteration<D, 1, kMask>(st, lds, next, cur, dkey0 - 32, c);
+        stage = stage1;
+    };
+    const int n_masked = min(2, per_head);
+    for (int h = 0, u = 0; h < p.group; ++h) {
+        for (int j = 0; j < n_masked; ++j, ++u) tile_step(u, first_qt + j, std::true_type{});
+        for (int j = n_masked; j < per_head; ++j, ++u) tile_step(u, first_qt + j, std::false_type{});
     }
 
     // epilogue: G2 of the last block

@@ -67,8 +67,10 @@ __global__ __launch_bounds__(kThreads, 2) void bwd_dq_kernel(BwdParams p) {
     const int kv_end = min(L, q_row0 + BQ);
     const int n_tiles = (kv_end + BK - 1) / BK;
 
-    tile_load_async<D, BK>(lds, kbase, p.kv_stride, 0, L, wave, lane);
-    tile_load_async<D, BK>(lds + kTileBytes, vbase, p.kv_stride, 0, L, wave, lane);
+    TileCopy<D, BK> kvcopy;   // K and V share stride and geometry
+    kvcopy.init(p.kv_stride, wave, lane);
+    kvcopy.issue(lds, kbase, p.kv_stride, 0, L, wave, lane);
+    kvcopy.issue(lds + kTileBytes, vbase, p.kv_stride, 0, L, wave, lane);
 
     bf16x8 qf[KK], dof[KK];
 #pragma unroll
@@ -101,8 +103,8 @@ __global__ __launch_bounds__(kThreads, 2) void bwd_dq_kernel(BwdParams p) {
         const char* vtile = ktile + kTileBytes;
         if (kt + 1 < n_tiles) {
             char* next = lds + ((kt + 1) & 1) * (2 * kTileBytes);
-            tile_load_async<D, BK>(next, kbase, p.kv_stride, (kt + 1) * BK, L, wave, lane);
-            tile_load_async<D, BK>(next + kTileBytes, vbase, p.kv_stride, (kt + 1) * BK, L, wave, lane);
+            kvcopy.issue(next, kbase, p.kv_stride, (kt + 1) * BK, L, wave, lane);
+            kvcopy.issue(next + kTileBytes, vbase, p.kv_stride, (kt + 1) * BK, L, wave, lane);
         }
         const int key0 = kt * BK;
 #pragma unroll
