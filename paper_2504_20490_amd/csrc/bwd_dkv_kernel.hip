@@ -185,7 +185,7 @@ __global__ __launch_bounds__(kThreads, 1) void bwd_dkv_kernel(BwdParams p) {
     auto load_tile = [&](int u, int stage_index) {
         char* stage = lds + stage_index * G::kStageBytes;
         const int hq = g * p.group + u / per_head;
-        const int row0 = (first_qt + u % per_head) * BQ;
+        const int row0 = (n_qt - 1 - u % per_head) * BQ;   // q tiles are walked from the end of the sequence down
         const uint16_t* qb = p.q + (int64_t)item.token_start * p.q_stride + (int64_t)hq * D;
         const uint16_t* dob = p.d_o + ((int64_t)item.token_start * p.q_heads + hq) * D;
         // even waves: LSE log2e of the 64 rows; odd waves: D (waves 2, 3 repeat the copies of waves 0, 1 so that
@@ -280,8 +280,8 @@ __global__ __launch_bounds__(kThreads, 1) void bwd_dkv_kernel(BwdParams p) {
         st.pprev[0] = st.pprev[1] = st.dsprev[0] = st.dsprev[1] = z.v;
     }
 
-    // One tile = two iterations.  Tiles 0 and 1 of every head hold the (row < key) pairs of some wave and
-    // take the masked code; all later tiles take the unmasked code.  Two loops instead of a branch inside
+    // One tile = two iterations.  The two q tiles next to the diagonal hold the (row < key) pairs of some wave
+    // and take the masked code; all other tiles take the unmasked code.  Two loops instead of a branch inside
     // one: the ~400 live registers then meet at a join once per head, not once per iteration.
     int stage = 0;   // stage of tile u
     auto tile_step = [&](int u, int qt, auto masked) {
@@ -302,10 +302,14 @@ __global__ __launch_bounds__(kThreads, 1) void bwd_dkv_kernel(BwdParams p) {
         dkv_iteration<D, 1, kMask>(st, lds, next, cur, dkey0 - 32, c);
         stage = stage1;
     };
+    // Every head is walked from its LAST q tile down to the diagonal.  All key tiles of one (sequence, kv head)
+    // run on one XCD at about the same time; walking down from the common end keeps them on the same Q / dO
+    // tiles at the same time (one L2 fill serves them all), whereas walking up from each item's own diagonal
+    // would spread them over the whole sequence.
     const int n_masked = min(2, per_head);
     for (int h = 0, u = 0; h < p.group; ++h) {
-        for (int j = 0; j < n_masked; ++j, ++u) tile_step(u, first_qt + j, std::true_type{});
-        for (int j = n_masked; j < per_head; ++j, ++u) tile_step(u, first_qt + j, std::false_type{});
+        for (int j = per_head - 1; j >= n_masked; --j, ++u) tile_step(u, first_qt + j, std::false_type{});
+        for (int j = n_masked - 1; j >= 0; --j, ++u) tile_step(u, first_qt + j, std::true_type{});
     }
 
     // epilogue: G2 of the last block
