@@ -84,6 +84,9 @@ def main() -> int:
     ap.add_argument("--workload", default="C4", help="C1..C5 (default: the 32768-token asymmetric-head pack)")
     ap.add_argument("--grad-dtype", default="f32", choices=["f32", "bf16"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--order", default="xcd_cost", choices=["xcd_cost", "natural", "cost"],
+                    help="launch order of the work lists; the default is the library's, the others exist to "
+                         "measure what it buys")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="before the steps, run one plain device copy of 1 GiB (a kernel of known HBM traffic "
                          "that scales the FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run)")
@@ -122,10 +125,11 @@ def main() -> int:
     dv = torch.empty_like(dk)
     ws = torch.empty(2 * hq * T * 4 + 256, dtype=torch.uint8, device=dev)
     stream = torch.cuda.current_stream()
+    order = {"xcd_cost": A.ORDER_XCD_COST, "natural": A.ORDER_NATURAL, "cost": A.ORDER_COST}[args.order]
 
     def step():
         cu, _, _ = A.build_cu_seqlens(lengths)                 # packed offsets
-        plan = A.Plan(cu, hq, hkv, d, stream.cuda_stream)       # cost-sorted work lists
+        plan = A.Plan(cu, hq, hkv, d, stream.cuda_stream, order=order)   # cost-sorted work lists
         A.attn_varlen_fwd(plan, tq, tk, tv, o, lse, stream=stream)
         A.attn_varlen_bwd(plan, tq, tk, tv, o, lse, tdo, dq, dk, dv, ws, grad_dtype=grad, stream=stream)
         return plan
@@ -160,7 +164,7 @@ def main() -> int:
     t1 = time.perf_counter()
     for _ in range(5):
         cu, _, _ = A.build_cu_seqlens(lengths)
-        A.Plan(cu, hq, hkv, d, stream.cuda_stream).destroy()
+        A.Plan(cu, hq, hkv, d, stream.cuda_stream, order=order).destroy()
     plan_ms = (time.perf_counter() - t1) / 5 * 1e3
 
     ms_per_step = elapsed / args.steps * 1e3
@@ -190,7 +194,7 @@ def main() -> int:
         "config": {"workload": f"{cfg.name}: {cfg.note}", "total_tokens": T, "q_heads": hq, "kv_heads": hkv,
                    "head_dim": d, "num_seqs": len(lengths), "lengths": lengths,
                    "sum_L_Lplus1": 2 * w.causal_pairs(lengths), "fwd_useful_flops": fwd,
-                   "grad_dtype": args.grad_dtype,
+                   "grad_dtype": args.grad_dtype, "order": args.order,
                    "step": "build_cu_seqlens + work lists + fwd + bwd(D, dQ, dK/dV)"},
         "pct_of_bf16_mfma_peak": round(100.0 * tflops / PEAK_BF16_TFLOPS, 2),
         "kernel_ms": {name: round(ms, 4) for name, ms in kern.items()},

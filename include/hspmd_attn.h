@@ -70,6 +70,13 @@ typedef enum {
     HSPMD_LIST_DKV = 2    /* items (sequence, k tile, kv head): backward dK/dV pass    */
 } hspmd_list_kind;
 
+/* launch order of a work list */
+typedef enum {
+    HSPMD_ORDER_XCD_COST = 0,   /* default: chains per XCD queue, balanced by cost, expensive items first */
+    HSPMD_ORDER_NATURAL = 1,    /* sequence-major, tiles ascending, heads innermost: no cost model at all    */
+    HSPMD_ORDER_COST = 2        /* one global list, most expensive item first, no XCD placement             */
+} hspmd_order;
+
 /* One unit of work for one workgroup.  tile < 0 marks a padding slot that does nothing. */
 typedef struct {
     int32_t token_start;  /* first packed token of the sequence (cu_seqlens[seq])      */
@@ -121,6 +128,11 @@ hspmd_status hspmd_attn_schedule(hspmd_list_kind kind, const int32_t* cu_seqlens
                                  int32_t local_q_heads, int32_t local_kv_heads, int32_t num_queues,
                                  hspmd_work_item* items, int64_t capacity, int64_t* count);
 
+/* Same with an explicit launch order (the alternatives exist to measure what the default buys). */
+hspmd_status hspmd_attn_schedule_ordered(hspmd_list_kind kind, hspmd_order order, const int32_t* cu_seqlens,
+                                         int32_t num_seqs, int32_t local_q_heads, int32_t local_kv_heads,
+                                         int32_t num_queues, hspmd_work_item* items, int64_t capacity, int64_t* count);
+
 /*
  * Plan: the three device-resident work lists for one pack and one local head
  * configuration.  One plan serves every layer and both passes of a micro-batch.
@@ -134,6 +146,9 @@ typedef struct hspmd_attn_plan hspmd_attn_plan;
 hspmd_status hspmd_attn_plan_create(const int32_t* cu_seqlens_host, int32_t num_seqs, int32_t local_q_heads,
                                     int32_t local_kv_heads, int32_t head_dim, void* stream,
                                     hspmd_attn_plan** out);
+hspmd_status hspmd_attn_plan_create_ordered(const int32_t* cu_seqlens_host, int32_t num_seqs, int32_t local_q_heads,
+                                            int32_t local_kv_heads, int32_t head_dim, hspmd_order order,
+                                            void* stream, hspmd_attn_plan** out);
 hspmd_status hspmd_attn_plan_destroy(hspmd_attn_plan* plan);      /* NULL is accepted */
 int64_t hspmd_attn_plan_total_tokens(const hspmd_attn_plan* plan); /* -1 on NULL */
 int64_t hspmd_attn_plan_num_items(const hspmd_attn_plan* plan, hspmd_list_kind kind); /* slots incl. padding */

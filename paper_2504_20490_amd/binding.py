@@ -12,6 +12,7 @@ _LIB_PATH = os.path.join(HERE, "libhspmd_attn.so")
 
 LIST_FWD, LIST_DQ, LIST_DKV = 0, 1, 2
 GRAD_BF16, GRAD_F32 = 0, 1
+ORDER_XCD_COST, ORDER_NATURAL, ORDER_COST = 0, 1, 2
 
 _STATUS = {0: "OK", 1: "INVALID_ARG", 2: "UNSUPPORTED", 3: "WORKSPACE_TOO_SMALL", 4: "HIP"}
 
@@ -56,6 +57,13 @@ def load_library():
     lib.hspmd_attn_schedule.restype = ctypes.c_int
     lib.hspmd_attn_schedule.argtypes = [ctypes.c_int, i32p, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32,
                                         ctypes.c_int32, ctypes.POINTER(WorkItem), ctypes.c_int64, i64p]
+    lib.hspmd_attn_schedule_ordered.restype = ctypes.c_int
+    lib.hspmd_attn_schedule_ordered.argtypes = [ctypes.c_int, ctypes.c_int, i32p, ctypes.c_int32, ctypes.c_int32,
+                                                ctypes.c_int32, ctypes.c_int32, ctypes.POINTER(WorkItem),
+                                                ctypes.c_int64, i64p]
+    lib.hspmd_attn_plan_create_ordered.restype = ctypes.c_int
+    lib.hspmd_attn_plan_create_ordered.argtypes = [i32p, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32,
+                                                   ctypes.c_int, vp, ctypes.POINTER(vp)]
     lib.hspmd_attn_plan_create.restype = ctypes.c_int
     lib.hspmd_attn_plan_create.argtypes = [i32p, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32,
                                            vp, ctypes.POINTER(vp)]
@@ -114,30 +122,32 @@ def build_cu_seqlens(lengths: Sequence[int]) -> Tuple[np.ndarray, int, int]:
     return cu, int(mx.value), int(tot.value)
 
 
-def schedule(kind: int, cu_seqlens: Sequence[int], q_heads: int, kv_heads: int, num_queues: int = 8) -> np.ndarray:
+def schedule(kind: int, cu_seqlens: Sequence[int], q_heads: int, kv_heads: int, num_queues: int = 8,
+             order: int = ORDER_XCD_COST) -> np.ndarray:
     """Host-only: the launch-ordered work list as an int32 array [slots, 4]
     (token_start, seq_len, tile, head); padding slots have tile == -1."""
     lib = load_library()
     cu = _i32(cu_seqlens)
     n = ctypes.c_int64(0)
-    _check(lib.hspmd_attn_schedule(kind, _ptr32(cu), len(cu) - 1, q_heads, kv_heads, num_queues, None, 0,
-                                   ctypes.byref(n)))
+    _check(lib.hspmd_attn_schedule_ordered(kind, order, _ptr32(cu), len(cu) - 1, q_heads, kv_heads, num_queues, None, 0,
+                                           ctypes.byref(n)))
     out = np.zeros((n.value, 4), dtype=np.int32)
     if n.value:
-        _check(lib.hspmd_attn_schedule(kind, _ptr32(cu), len(cu) - 1, q_heads, kv_heads, num_queues,
-                                       out.ctypes.data_as(ctypes.POINTER(WorkItem)), n.value, ctypes.byref(n)))
+        _check(lib.hspmd_attn_schedule_ordered(kind, order, _ptr32(cu), len(cu) - 1, q_heads, kv_heads, num_queues,
+                                               out.ctypes.data_as(ctypes.POINTER(WorkItem)), n.value, ctypes.byref(n)))
     return out
 
 
 class Plan:
     """Device-resident work lists for one pack and one local head configuration."""
 
-    def __init__(self, cu_seqlens: Sequence[int], q_heads: int, kv_heads: int, head_dim: int, stream: int = 0):
+    def __init__(self, cu_seqlens: Sequence[int], q_heads: int, kv_heads: int, head_dim: int, stream: int = 0,
+                 order: int = ORDER_XCD_COST):
         lib = load_library()
         cu = _i32(cu_seqlens)
         handle = ctypes.c_void_p(None)
-        _check(lib.hspmd_attn_plan_create(_ptr32(cu), len(cu) - 1, q_heads, kv_heads, head_dim,
-                                          ctypes.c_void_p(stream), ctypes.byref(handle)))
+        _check(lib.hspmd_attn_plan_create_ordered(_ptr32(cu), len(cu) - 1, q_heads, kv_heads, head_dim, order,
+                                                  ctypes.c_void_p(stream), ctypes.byref(handle)))
         self._h = handle
         self.q_heads, self.kv_heads, self.head_dim = q_heads, kv_heads, head_dim
         self.total_tokens = int(lib.hspmd_attn_plan_total_tokens(handle))

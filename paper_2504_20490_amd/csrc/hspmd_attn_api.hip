@@ -73,7 +73,8 @@ struct hspmd_attn_plan {
     int32_t q_heads = 0, kv_heads = 0, head_dim = 0;
     int64_t total_tokens = 0;
     int64_t count[3] = {0, 0, 0};
-    hspmd_work_item* items[3] = {nullptr, nullptr, nullptr};   // device
+    hspmd_work_item* items[3] = {nullptr, nullptr, nullptr};   // device; three views into one allocation
+    void* device_block = nullptr;
 };
 
 extern "C" {
@@ -104,11 +105,13 @@ hspmd_status hspmd_build_cu_seqlens(const int32_t* lengths, int32_t num_seqs, in
     return HSPMD_OK;
 }
 
-hspmd_status hspmd_attn_schedule(hspmd_list_kind kind, const int32_t* cu_seqlens, int32_t num_seqs,
-                                 int32_t local_q_heads, int32_t local_kv_heads, int32_t num_queues,
-                                 hspmd_work_item* items, int64_t capacity, int64_t* count) {
+hspmd_status hspmd_attn_schedule_ordered(hspmd_list_kind kind, hspmd_order order, const int32_t* cu_seqlens,
+                                         int32_t num_seqs, int32_t local_q_heads, int32_t local_kv_heads,
+                                         int32_t num_queues, hspmd_work_item* items, int64_t capacity, int64_t* count) {
     if (kind != HSPMD_LIST_FWD && kind != HSPMD_LIST_DQ && kind != HSPMD_LIST_DKV)
         return fail(HSPMD_ERR_INVALID_ARG, "unknown list kind");
+    if (order != HSPMD_ORDER_XCD_COST && order != HSPMD_ORDER_NATURAL && order != HSPMD_ORDER_COST)
+        return fail(HSPMD_ERR_INVALID_ARG, "unknown order");
     if (!count) return fail(HSPMD_ERR_INVALID_ARG, "count is NULL");
     if (num_queues < 1) return fail(HSPMD_ERR_INVALID_ARG, "num_queues must be >= 1");
     if (capacity < 0 || (capacity > 0 && !items)) return fail(HSPMD_ERR_INVALID_ARG, "items is NULL");
@@ -116,7 +119,7 @@ hspmd_status hspmd_attn_schedule(hspmd_list_kind kind, const int32_t* cu_seqlens
     if (!why.empty()) return fail(HSPMD_ERR_INVALID_ARG, why);
     std::vector<hspmd_work_item> list;
     try {
-        list = hspmd::build_work_list(kind, cu_seqlens, num_seqs, local_q_heads, local_kv_heads, num_queues);
+        list = hspmd::build_work_list(kind, cu_seqlens, num_seqs, local_q_heads, local_kv_heads, num_queues, order);
     } catch (const std::bad_alloc&) {
         return fail(HSPMD_ERR_INVALID_ARG, "out of host memory while building the work list");
     }
@@ -127,14 +130,23 @@ hspmd_status hspmd_attn_schedule(hspmd_list_kind kind, const int32_t* cu_seqlens
     return HSPMD_OK;
 }
 
-hspmd_status hspmd_attn_plan_create(const int32_t* cu_seqlens_host, int32_t num_seqs, int32_t local_q_heads,
-                                    int32_t local_kv_heads, int32_t head_dim, void* stream,
-                                    hspmd_attn_plan** out) {
+hspmd_status hspmd_attn_schedule(hspmd_list_kind kind, const int32_t* cu_seqlens, int32_t num_seqs,
+                                 int32_t local_q_heads, int32_t local_kv_heads, int32_t num_queues,
+                                 hspmd_work_item* items, int64_t capacity, int64_t* count) {
+    return hspmd_attn_schedule_ordered(kind, HSPMD_ORDER_XCD_COST, cu_seqlens, num_seqs, local_q_heads, local_kv_heads,
+                                       num_queues, items, capacity, count);
+}
+
+hspmd_status hspmd_attn_plan_create_ordered(const int32_t* cu_seqlens_host, int32_t num_seqs, int32_t local_q_heads,
+                                            int32_t local_kv_heads, int32_t head_dim, hspmd_order order,
+                                            void* stream, hspmd_attn_plan** out) {
     if (!out) return fail(HSPMD_ERR_INVALID_ARG, "out is NULL");
     *out = nullptr;
     const std::string why = hspmd::check_pack(cu_seqlens_host, num_seqs, local_q_heads, local_kv_heads);
     if (!why.empty()) return fail(HSPMD_ERR_INVALID_ARG, why);
     if (head_dim != 64 && head_dim != 128) return fail(HSPMD_ERR_UNSUPPORTED, "head_dim must be 64 or 128");
+    if (order != HSPMD_ORDER_XCD_COST && order != HSPMD_ORDER_NATURAL && order != HSPMD_ORDER_COST)
+        return fail(HSPMD_ERR_INVALID_ARG, "unknown order");
     hspmd_attn_plan* plan = new (std::nothrow) hspmd_attn_plan();
     if (!plan) return fail(HSPMD_ERR_INVALID_ARG, "out of host memory");
     plan->num_seqs = num_seqs;
@@ -142,43 +154,55 @@ hspmd_status hspmd_attn_plan_create(const int32_t* cu_seqlens_host, int32_t num_
     plan->kv_heads = local_kv_heads;
     plan->head_dim = head_dim;
     plan->total_tokens = cu_seqlens_host[num_seqs];
-    hipStream_t s = static_cast<hipStream_t>(stream);
-    for (int kind = 0; kind < 3; ++kind) {
-        std::vector<hspmd_work_item> list;
-        try {
-            list = hspmd::build_work_list((hspmd_list_kind)kind, cu_seqlens_host, num_seqs, local_q_heads,
-                                          local_kv_heads, hspmd::kNumXcd);
-        } catch (const std::bad_alloc&) {
-            hspmd_attn_plan_destroy(plan);
-            return fail(HSPMD_ERR_INVALID_ARG, "out of host memory while building the work list");
+    // the three lists back to back in one host vector -> one allocation, one copy, one synchronisation
+    std::vector<hspmd_work_item> all;
+    size_t offset[3] = {0, 0, 0};
+    try {
+        for (int kind = 0; kind < 3; ++kind) {
+            const std::vector<hspmd_work_item> list = hspmd::build_work_list(
+                (hspmd_list_kind)kind, cu_seqlens_host, num_seqs, local_q_heads, local_kv_heads, hspmd::kNumXcd, order);
+            plan->count[kind] = (int64_t)list.size();
+            offset[kind] = all.size();
+            all.insert(all.end(), list.begin(), list.end());
         }
-        plan->count[kind] = (int64_t)list.size();
-        if (list.empty()) continue;
-        const size_t bytes = list.size() * sizeof(hspmd_work_item);
-        hipError_t e = hipMalloc(reinterpret_cast<void**>(&plan->items[kind]), bytes);
+    } catch (const std::bad_alloc&) {
+        delete plan;
+        return fail(HSPMD_ERR_INVALID_ARG, "out of host memory while building the work lists");
+    }
+    if (!all.empty()) {
+        hipStream_t s = static_cast<hipStream_t>(stream);
+        const size_t bytes = all.size() * sizeof(hspmd_work_item);
+        hipError_t e = hipMalloc(&plan->device_block, bytes);
+        if (e != hipSuccess) {
+            delete plan;
+            return fail_hip(e, "hipMalloc(work lists)");
+        }
+        e = hipMemcpyAsync(plan->device_block, all.data(), bytes, hipMemcpyHostToDevice, s);
+        if (e == hipSuccess) e = hipStreamSynchronize(s);   // `all` dies at the end of this scope
         if (e != hipSuccess) {
             hspmd_attn_plan_destroy(plan);
-            return fail_hip(e, "hipMalloc(work list)");
+            return fail_hip(e, "hipMemcpyAsync(work lists)");
         }
-        e = hipMemcpyAsync(plan->items[kind], list.data(), bytes, hipMemcpyHostToDevice, s);
-        if (e == hipSuccess) e = hipStreamSynchronize(s);   // `list` dies at the end of this iteration
-        if (e != hipSuccess) {
-            hspmd_attn_plan_destroy(plan);
-            return fail_hip(e, "hipMemcpyAsync(work list)");
-        }
+        for (int kind = 0; kind < 3; ++kind)
+            if (plan->count[kind] > 0) plan->items[kind] = static_cast<hspmd_work_item*>(plan->device_block) + offset[kind];
     }
     *out = plan;
     return HSPMD_OK;
 }
 
+hspmd_status hspmd_attn_plan_create(const int32_t* cu_seqlens_host, int32_t num_seqs, int32_t local_q_heads,
+                                    int32_t local_kv_heads, int32_t head_dim, void* stream,
+                                    hspmd_attn_plan** out) {
+    return hspmd_attn_plan_create_ordered(cu_seqlens_host, num_seqs, local_q_heads, local_kv_heads, head_dim,
+                                          HSPMD_ORDER_XCD_COST, stream, out);
+}
+
 hspmd_status hspmd_attn_plan_destroy(hspmd_attn_plan* plan) {
     if (!plan) return HSPMD_OK;
     hspmd_status rc = HSPMD_OK;
-    for (int kind = 0; kind < 3; ++kind) {
-        if (plan->items[kind]) {
-            const hipError_t e = hipFree(plan->items[kind]);
-            if (e != hipSuccess) rc = fail_hip(e, "hipFree(work list)");
-        }
+    if (plan->device_block) {
+        const hipError_t e = hipFree(plan->device_block);
+        if (e != hipSuccess) rc = fail_hip(e, "hipFree(work lists)");
     }
     delete plan;
     return rc;

@@ -58,8 +58,30 @@ struct Segment {
 };
 }  // namespace
 
+// The two orders without placement: used only to measure what the default order buys.
+static std::vector<hspmd_work_item> build_plain_list(hspmd_list_kind kind, const int32_t* cu, int32_t num_seqs,
+                                                     int32_t hq, int32_t hkv, hspmd_order order) {
+    const int32_t group = hq / hkv;
+    const int tile_rows = (kind == HSPMD_LIST_DKV) ? kDkvKTile : kFwdQTile;
+    const int32_t heads = (kind == HSPMD_LIST_DKV) ? hkv : hq;
+    std::vector<hspmd_work_item> out;
+    for (int32_t s = 0; s < num_seqs; ++s) {
+        const int32_t len = cu[s + 1] - cu[s];
+        if (len <= 0) continue;
+        const int32_t n_tiles = (int32_t)ceil_div(len, tile_rows);
+        for (int32_t t = 0; t < n_tiles; ++t)
+            for (int32_t h = 0; h < heads; ++h) out.push_back({cu[s], len, t, h});
+    }
+    if (order == HSPMD_ORDER_COST)
+        std::stable_sort(out.begin(), out.end(), [&](const hspmd_work_item& a, const hspmd_work_item& b) {
+            return item_cost(kind, a.seq_len, a.tile, group) > item_cost(kind, b.seq_len, b.tile, group);
+        });
+    return out;
+}
+
 std::vector<hspmd_work_item> build_work_list(hspmd_list_kind kind, const int32_t* cu, int32_t num_seqs,
-                                             int32_t hq, int32_t hkv, int32_t num_queues) {
+                                             int32_t hq, int32_t hkv, int32_t num_queues, hspmd_order order) {
+    if (order != HSPMD_ORDER_XCD_COST) return build_plain_list(kind, cu, num_seqs, hq, hkv, order);
     const int32_t group = hq / hkv;
     const int tile_rows = (kind == HSPMD_LIST_DKV) ? kDkvKTile : kFwdQTile;
 

@@ -23,6 +23,7 @@ int64_t item_cost(hspmd_list_kind kind, int32_t seq_len, int32_t tile, int32_t g
 
 // Builds the launch-ordered list (see hspmd_attn_schedule in the public header).
 std::vector<hspmd_work_item> build_work_list(hspmd_list_kind kind, const int32_t* cu, int32_t num_seqs,
-                                             int32_t hq, int32_t hkv, int32_t num_queues);
+                                             int32_t hq, int32_t hkv, int32_t num_queues,
+                                             hspmd_order order = HSPMD_ORDER_XCD_COST);
 
 }  // namespace hspmd

@@ -94,6 +94,27 @@ def test_work_list_invariants(name, kind):
             assert np.all(tiles[pad[0]:] < 0)
 
 
+@pytest.mark.parametrize("order", [A.ORDER_NATURAL, A.ORDER_COST])
+@pytest.mark.parametrize("kind", [A.LIST_FWD, A.LIST_DKV])
+def test_alternative_orders_hold_every_item_once(order, kind):
+    cfg = w.config_by_name("C3")
+    lengths = w.lengths_for(cfg)
+    cu, _, _ = A.build_cu_seqlens(lengths)
+    default = A.schedule(kind, cu, cfg.q_heads, cfg.kv_heads, 8)
+    other = A.schedule(kind, cu, cfg.q_heads, cfg.kv_heads, 8, order=order)
+    assert np.all(other[:, 2] >= 0)                     # no padding without queues
+    as_set = lambda a: sorted(tuple(int(x) for x in r) for r in a if r[2] >= 0)
+    assert as_set(other) == as_set(default)
+    G = cfg.q_heads // cfg.kv_heads
+    costs = [_cost(kind, int(r[1]), int(r[2]), G) for r in other]
+    if order == A.ORDER_COST:
+        assert costs == sorted(costs, reverse=True)
+    else:
+        assert [int(r[0]) for r in other] == sorted(int(r[0]) for r in other)   # sequence-major
+    with pytest.raises(A.HspmdError):
+        A.schedule(kind, cu, cfg.q_heads, cfg.kv_heads, 8, order=7)
+
+
 def test_work_list_gqa_heads_of_one_tile_are_adjacent():
     cu, _, _ = A.build_cu_seqlens([1000, 3000])
     items = A.schedule(A.LIST_FWD, cu, 8, 2, 8)
