@@ -83,9 +83,26 @@ def errors(got: np.ndarray, ref: np.ndarray):
         float(np.linalg.norm(diff) / max(np.linalg.norm(ref), 1e-300)) if diff.size else 0.0
 
 
+CONTEXT = {"case": ""}   # set by a test; written into the optional report
+
+
+def _report(name, ma, rf, ref):
+    """With HSPMD_PARITY_REPORT=<path> every comparison appends one JSON line (the measured errors that the
+    results table quotes)."""
+    import json
+    import os
+    path = os.environ.get("HSPMD_PARITY_REPORT")
+    if not path:
+        return
+    with open(path, "a") as f:
+        f.write(json.dumps({"case": CONTEXT["case"], "tensor": name, "max_abs": ma, "rel_fro": rf,
+                            "max_ref": float(np.max(np.abs(ref))) if ref.size else 0.0, "elements": int(ref.size)}) + "\n")
+
+
 def assert_close(name, got, ref, max_abs=MAX_ABS, rel_fro=REL_FRO):
     assert not np.isnan(got).any(), f"{name}: NaN in GPU output (unwritten or invalid elements)"
     ma, rf = errors(got, ref)
+    _report(name, ma, rf, ref)
     assert ma <= max_abs and rf <= rel_fro, f"{name}: max_abs {ma:.3e} (<= {max_abs}), rel_fro {rf:.3e} (<= {rel_fro})"
     return ma, rf
 

@@ -11,6 +11,7 @@ import pytest
 
 import hspmd_workloads as w
 import oracle
+import gpu_util
 from gpu_util import GpuRun, LSE_ABS, assert_close, default_scale, f64
 
 pytestmark = pytest.mark.gpu
@@ -27,6 +28,7 @@ def _pick_medium(lengths, lo=400, hi=2300):
 def test_full_size_config(name):
     import torch
     cfg = w.config_by_name(name)
+    gpu_util.CONTEXT["case"] = cfg.name
     lengths, q, k, v, do = w.make_inputs(cfg)
     hq, hkv, d = cfg.q_heads, cfg.kv_heads, cfg.head_dim
     G = hq // hkv

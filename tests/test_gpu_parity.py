@@ -6,6 +6,7 @@ import pytest
 
 import hspmd_workloads as w
 import oracle
+import gpu_util
 from gpu_util import (GpuRun, LSE_ABS, assert_close, default_scale, f64, make_case, to_dev)
 
 pytestmark = pytest.mark.gpu
@@ -14,6 +15,7 @@ RAGGED = [1, 2, 31, 32, 33, 63, 64, 65, 127, 128, 129, 200, 257, 0, 300]
 
 
 def _full_check(lengths, hq, hkv, d, seed, value_scale=1.0, grad_dtype=None, scale=0.0):
+    gpu_util.CONTEXT["case"] = f"small pack {len(lengths)} seqs Hq{hq} Hkv{hkv} d{d} seed{seed}"
     q, k, v, do = make_case(lengths, hq, hkv, d, seed, value_scale)
     run = GpuRun(lengths, q, k, v, do, grad_dtype=grad_dtype, scale=scale).run()
     s = scale if scale > 0 else default_scale(d)
@@ -29,6 +31,7 @@ def _full_check(lengths, hq, hkv, d, seed, value_scale=1.0, grad_dtype=None, sca
 
 def test_c1_tiny_pack():
     cfg = w.config_by_name("C1")
+    gpu_util.CONTEXT["case"] = cfg.name
     lengths, q, k, v, do = w.make_inputs(cfg)
     assert lengths == [17, 64, 111]
     run = GpuRun(lengths, q, k, v, do).run()
