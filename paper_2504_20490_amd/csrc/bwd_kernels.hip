@@ -8,6 +8,8 @@
 //   dK/dV pass: bwd_dkv_kernel.hip
 // In every product the operand that changes per step comes from a row-major LDS tile, read
 // either along its rows or with the transpose read; the wave's own rows stay in registers.
+#include <type_traits>
+
 #include "attn_device.hpp"
 #include "kernels.hpp"
 #include "schedule.hpp"
@@ -96,7 +98,10 @@ __global__ __launch_bounds__(kThreads, 2) void bwd_dq_kernel(BwdParams p) {
 #pragma unroll
         for (int i = 0; i < 16; ++i) acc[db][i] = 0.f;
 
-    for (int kt = 0; kt < n_tiles; ++kt) {
+    // One key tile.  MASK = false: every key of the tile precedes every row of this q tile (no compare, no
+    // skipped block); MASK = true: the tile touches the diagonal.
+    auto step = [&](int kt, auto masked) {
+        constexpr bool kMask = decltype(masked)::value;
         wait_tile_loads();
         __syncthreads();   // tile kt has landed; every wave is done with the other stage
         const char* ktile = lds + (kt & 1) * (2 * kTileBytes);
@@ -110,7 +115,7 @@ __global__ __launch_bounds__(kThreads, 2) void bwd_dq_kernel(BwdParams p) {
 #pragma unroll
         for (int jb = 0; jb < 2; ++jb) {
             const int kb = key0 + jb * 32;
-            if (kb <= wave_row0 + 31) {           // otherwise every key of the block is masked for this wave
+            if (!kMask || kb <= wave_row0 + 31) {           // otherwise every key of the block is masked for this wave
                 f32x16 s, dp;
 #pragma unroll
                 for (int i = 0; i < 16; ++i) { s[i] = 0.f; dp[i] = 0.f; }
@@ -128,11 +133,10 @@ __global__ __launch_bounds__(kThreads, 2) void bwd_dq_kernel(BwdParams p) {
 #pragma unroll
                     for (int kk = 0; kk < KK; ++kk) dp = mfma(vf[kk], dof[kk], dp);
                 }
-                const bool diag = kb + 31 > wave_row0;
 #pragma unroll
                 for (int i = 0; i < 16; ++i) {
                     float pr = fast_exp2(fmaf(s[i], c, -lse2));
-                    if (diag && kb + acc_row(i, lane) > my_row) pr = 0.f;
+                    if (kMask && kb + acc_row(i, lane) > my_row) pr = 0.f;
                     s[i] = pr * (dp[i] - dsum);   // dS^T
                 }
 #pragma unroll
@@ -146,7 +150,12 @@ __global__ __launch_bounds__(kThreads, 2) void bwd_dq_kernel(BwdParams p) {
                 }
             }
         }
-    }
+    };
+    // two loops instead of a test per tile: the tiles wholly below the diagonal, then the (at most two) on it
+    const int n_interior = min(n_tiles, 2 * item.tile);
+    int kt = 0;
+    for (; kt < n_interior; ++kt) step(kt, std::false_type{});
+    for (; kt < n_tiles; ++kt) step(kt, std::true_type{});
 
     if (valid) {
         const int64_t row_elem = ((int64_t)(item.token_start + my_row) * p.q_heads + h) * D;
