@@ -125,6 +125,12 @@ struct TileCopy {
             off[i] = (uint32_t)(r * (int)stride + c * 8) * 2u;
         }
     }
+    // instruction I (of kPerWave) of a whole-tile copy; first_row points at the tile's first row, column 0
+    template <int I>
+    __device__ __forceinline__ void issue_full_one(char* tile, const uint16_t* first_row, int wave) const {
+        static_assert(I >= 0 && I < kPerWave, "instruction index");
+        global_to_lds<16>(first_row, off[I], tile + (I * 4 + wave) * 1024);
+    }
     // whole tile inside the sequence: rows row0 .. row0+ROWS-1 all exist.  slab points at row 0, column 0.
     __device__ __forceinline__ void issue_full(char* tile, const uint16_t* slab, int64_t stride, int row0, int wave) const {
         const uint16_t* base = slab + (int64_t)row0 * stride;

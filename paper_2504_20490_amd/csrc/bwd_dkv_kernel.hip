@@ -49,6 +49,7 @@ struct DkvState {
     bf16x8 qf[G::KK], dof[G::KK];          // Q, dO rows of block i+1 (A operands of G1), live inside an iteration
     bf16x8 qtf[G::KK], dotf[G::KK];        // Q^T, dO^T of block i-1 (A operands of G2), index tt*DB + db
     bf16x8 pprev[2], dsprev[2];            // P, dS of block i-1 as bf16 B operands
+    f32x4 lse4[4], ds4[4];                 // LSE log2e and D of block i's rows (rows 8 j + 4 (lane / 32) .. + 3 in [j])
 };
 
 // per-lane LDS byte addresses (stage base included) of the operand fragments
@@ -58,6 +59,34 @@ struct DkvAddr {
     int rm[G::KK];         // row-major fragment kk of a 32-row block (Q tile; dO tile is + kTileBytes)
     int tr[G::DB][2];      // transposed fragment: column block db, 8-row part
     int st;                // statistics
+};
+
+// The global -> LDS copies of one whole 64-row tile (Q chunks, dO chunks, one statistics row), cut into
+// this wave's single instructions so that an iteration can issue them one at a time between its MFMAs:
+// issued back to back after the barrier, the copies of all four waves queue up in front of the CU's one
+// address unit and every wave sits in its issue slot for hundreds of cycles with nothing else to run.
+template <int D>
+struct DkvTileLoad {
+    using Copy = TileCopy<D, kDkvQTile>;
+    static constexpr int kPieces = 2 * Copy::kPerWave + 1;
+    const Copy* qcopy;
+    const Copy* docopy;
+    const uint16_t* q_row;      // first row of the tile, this head, column 0
+    const uint16_t* do_row;
+    const float* stat;          // LSE log2e (even waves) or D (odd waves) of the tile's first row
+    char* stage;
+    char* stat_dst;
+    int wave, lane;
+    template <int N>
+    __device__ __forceinline__ void piece() const {
+        if constexpr (N < Copy::kPerWave) {
+            qcopy->template issue_full_one<N>(stage, q_row, wave);
+        } else if constexpr (N < 2 * Copy::kPerWave) {
+            docopy->template issue_full_one<N - Copy::kPerWave>(stage + DkvGeom<D>::kTileBytes, do_row, wave);
+        } else if constexpr (N == 2 * Copy::kPerWave) {
+            global_to_lds<4>(stat, (uint32_t)lane * 4u, stat_dst);
+        }
+    }
 };
 
 __device__ __forceinline__ bf16x8 lds_read128(const char* lds, int addr) {
@@ -78,24 +107,26 @@ __device__ __forceinline__ bf16x8 lds_read_tr(const char* lds, int a0, int a1) {
 //   `cur`: addresses in the stage of block i's tile; `ahead`: addresses in the stage of block i+1's tile.
 // dkey = my_key - (first row of block i) - 4 * (lane / 32): element e of an accumulator fragment is a
 // masked (row < key) pair iff 8 * (e / 4) + e % 4 < dkey.
-template <int D, int RB, bool MASK>
+// SPREAD: the iteration also issues its share of the copies of a later tile (`load`), one instruction at a
+// time at fixed places among its LDS reads (the copies are ordered against LDS accesses, the reads are tied
+// to the MFMAs by the scheduling hints): pieces 0-3 in the first iteration of a tile, 4-8 in the second.
+template <int D, int RB, bool MASK, bool SPREAD>
 __device__ __forceinline__ void dkv_iteration(DkvState<D>& st, const char* lds, const DkvAddr<D>& ahead,
-                                              const DkvAddr<D>& cur, int dkey, float c) {
+                                              const DkvAddr<D>& cur, int dkey, float c, const DkvTileLoad<D>& load) {
     using G = DkvGeom<D>;
     constexpr int KK = G::KK, DB = G::DB;
     constexpr int NRB = RB ^ 1;   // block i+1 sits at the other position (of the next tile when RB == 1)
+    constexpr int P0 = RB == 0 ? 0 : 4;   // first piece of this iteration
 
     // ================= phase A =================
-    f32x4 lse4[4], ds4[4];
-#pragma unroll
-    for (int i4 = 0; i4 < 4; ++i4) {
-        lse4[i4] = *reinterpret_cast<const f32x4*>(lds + cur.st + RB * 128 + i4 * 32);
-        ds4[i4] = *reinterpret_cast<const f32x4*>(lds + cur.st + RB * 128 + i4 * 32 + 256);
-    }
 #pragma unroll
     for (int kk = 0; kk < KK; ++kk) {
         st.qf[kk] = lds_read128(lds, ahead.rm[kk] + NRB * G::kBlockBytes);
         st.dof[kk] = lds_read128(lds, ahead.rm[kk] + NRB * G::kBlockBytes + G::kTileBytes);
+        if constexpr (SPREAD) {
+            if (kk == KK / 4 - 1) load.template piece<P0>();
+            if (kk == 3 * KK / 4 - 1) load.template piece<P0 + 1>();
+        }
     }
     // G2(i-1)
 #pragma unroll
@@ -108,18 +139,18 @@ __device__ __forceinline__ void dkv_iteration(DkvState<D>& st, const char* lds, 
     float pe[16];
 #pragma unroll
     for (int e = 0; e < 16; ++e) {
-        pe[e] = fast_exp2(fmaf(st.s_cur[e], c, -lse4[e >> 2][e & 3]));
+        pe[e] = fast_exp2(fmaf(st.s_cur[e], c, -st.lse4[e >> 2][e & 3]));
         if (MASK && (8 * (e >> 2) + (e & 3) < dkey)) pe[e] = 0.f;
     }
     u32x4 pw[2], dw[2];
 #pragma unroll
     for (int e = 0; e < 16; e += 2) {
-        const float d0 = pe[e] * (st.dp_cur[e] - ds4[e >> 2][e & 3]);
-        const float d1 = pe[e + 1] * (st.dp_cur[e + 1] - ds4[(e + 1) >> 2][(e + 1) & 3]);
+        const float d0 = pe[e] * (st.dp_cur[e] - st.ds4[e >> 2][e & 3]);
+        const float d1 = pe[e + 1] * (st.dp_cur[e + 1] - st.ds4[(e + 1) >> 2][(e + 1) & 3]);
         pw[e >> 3][(e >> 1) & 3] = pack_bf16(pe[e], pe[e + 1]);
         dw[e >> 3][(e >> 1) & 3] = pack_bf16(d0, d1);
     }
-    // per MFMA: 2 LDS reads (8 statistics + 2*KK fragments in all) and a share of V(i)'s VALU work
+    // per MFMA: 2 LDS reads (2*KK fragments in all) and a share of V(i)'s VALU work
     InterleaveHint<2 * KK, 2, (MASK ? 9 : 7), 0>::apply();
     __builtin_amdgcn_sched_barrier(0);
 
@@ -129,6 +160,13 @@ __device__ __forceinline__ void dkv_iteration(DkvState<D>& st, const char* lds, 
     cv.u = pw[1]; st.pprev[1] = cv.v;
     cv.u = dw[0]; st.dsprev[0] = cv.v;
     cv.u = dw[1]; st.dsprev[1] = cv.v;
+    // statistics of block i+1, first in the phase: they are the oldest LDS reads in flight when the next
+    // iteration's exp work starts, so it never waits for them
+#pragma unroll
+    for (int i4 = 0; i4 < 4; ++i4) {
+        st.lse4[i4] = *reinterpret_cast<const f32x4*>(lds + ahead.st + NRB * 128 + i4 * 32);
+        st.ds4[i4] = *reinterpret_cast<const f32x4*>(lds + ahead.st + NRB * 128 + i4 * 32 + 256);
+    }
 #pragma unroll
     for (int tt = 0; tt < 2; ++tt)
 #pragma unroll
@@ -136,6 +174,11 @@ __device__ __forceinline__ void dkv_iteration(DkvState<D>& st, const char* lds, 
             const int off = (RB * 2 + tt) * 16 * D * 2;   // 16 tile rows per k-step
             st.qtf[tt * DB + db] = lds_read_tr<D>(lds, cur.tr[db][0] + off, cur.tr[db][1] + off);
             st.dotf[tt * DB + db] = lds_read_tr<D>(lds, cur.tr[db][0] + off + G::kTileBytes, cur.tr[db][1] + off + G::kTileBytes);
+            if constexpr (SPREAD) {
+                if (tt == 0 && db == DB - 1) load.template piece<P0 + 2>();
+                if (tt == 1 && db == DB / 2 - 1) load.template piece<P0 + 3>();
+                if (RB == 1 && tt == 1 && db == DB - 1) load.template piece<P0 + 4>();
+            }
         }
     // G1(i+1): the S chain first, so that the next iteration's exp work never waits for it
 #pragma unroll
@@ -144,7 +187,8 @@ __device__ __forceinline__ void dkv_iteration(DkvState<D>& st, const char* lds, 
     for (int kk = 0; kk < KK; ++kk) st.s_cur = mfma(st.qf[kk], st.kf[kk], st.s_cur);
 #pragma unroll
     for (int kk = 0; kk < KK; ++kk) st.dp_cur = mfma(st.dof[kk], st.vf[kk], st.dp_cur);
-    InterleaveHint<2 * KK, 2, 0, 1>::apply();   // per MFMA: 2 of the 4*KK transpose reads
+    __builtin_amdgcn_sched_group_barrier(0x100, 8, 1);   // the 8 statistics reads
+    InterleaveHint<2 * KK, 2, 0, 1>::apply();            // then per MFMA: 2 of the 4*KK transpose reads
     __builtin_amdgcn_sched_barrier(0);
 }
 
@@ -275,6 +319,11 @@ __global__ __launch_bounds__(kThreads, 1) void bwd_dkv_kernel(BwdParams p) {
             st.qtf[kk] = lds_read128(lds, a0.rm[kk]);      // any finite operand: it meets P = dS = 0
             st.dotf[kk] = st.qtf[kk];
         }
+#pragma unroll
+        for (int i4 = 0; i4 < 4; ++i4) {
+            st.lse4[i4] = *reinterpret_cast<const f32x4*>(lds + a0.st + i4 * 32);
+            st.ds4[i4] = *reinterpret_cast<const f32x4*>(lds + a0.st + i4 * 32 + 256);
+        }
         union { u32x4 u; bf16x8 v; } z;
         z.u = u32x4{0u, 0u, 0u, 0u};
         st.pprev[0] = st.pprev[1] = st.dsprev[0] = st.dsprev[1] = z.v;
@@ -284,6 +333,7 @@ __global__ __launch_bounds__(kThreads, 1) void bwd_dkv_kernel(BwdParams p) {
     // and take the masked code; all other tiles take the unmasked code.  Two loops instead of a branch inside
     // one: the ~400 live registers then meet at a join once per head, not once per iteration.
     int stage = 0;   // stage of tile u
+    DkvTileLoad<D> no_load{};
     auto tile_step = [&](int u, int qt, auto masked) {
         constexpr bool kMask = decltype(masked)::value;
         if (u > 0) {
@@ -298,8 +348,36 @@ __global__ __launch_bounds__(kThreads, 1) void bwd_dkv_kernel(BwdParams p) {
         // block 2u+2 lives in the next tile; the last tile has none: it re-reads itself (result unused)
         const DkvAddr<D> next = at_stage(u + 1 < n_tiles ? stage1 : stage);
         const int dkey0 = my_key - qt * BQ - 4 * hh;
-        dkv_iteration<D, 0, kMask>(st, lds, cur, cur, dkey0, c);
-        dkv_iteration<D, 1, kMask>(st, lds, next, cur, dkey0 - 32, c);
+        dkv_iteration<D, 0, kMask, false>(st, lds, cur, cur, dkey0, c, no_load);
+        dkv_iteration<D, 1, kMask, false>(st, lds, next, cur, dkey0 - 32, c, no_load);
+        stage = stage1;
+    };
+    // The same for an unmasked tile that is at least three tiles above the head's last one: the tile loaded
+    // meanwhile (u + 3) belongs to the same head and is a whole tile, so its copies need no case distinction
+    // and are issued from inside the two iterations.
+    auto tile_step_spread = [&](int u, int qt, int hq) {
+        if (u > 0) {
+            wait_tile_loads_except<kLoadsPerTile>();   // u + 2 < n_tiles here
+            __syncthreads();
+        }
+        const int stage1 = stage + 1 == G::kStages ? 0 : stage + 1;
+        const int stage3 = (stage + 3) % G::kStages;
+        const int row0 = (qt - 3) * BQ;
+        DkvTileLoad<D> load;
+        load.qcopy = &qcopy;
+        load.docopy = &docopy;
+        load.q_row = p.q + (int64_t)(item.token_start + row0) * p.q_stride + (int64_t)hq * D;
+        load.do_row = p.d_o + ((int64_t)(item.token_start + row0) * p.q_heads + hq) * D;
+        load.stat = ((wave & 1) == 0 ? p.lse2 : p.dsum) + (int64_t)hq * p.total_tokens + item.token_start + row0;
+        load.stage = lds + stage3 * G::kStageBytes;
+        load.stat_dst = load.stage + 2 * G::kTileBytes + (wave & 1) * 256;
+        load.wave = wave;
+        load.lane = lane;
+        const DkvAddr<D> cur = at_stage(stage);
+        const DkvAddr<D> next = at_stage(stage1);
+        const int dkey0 = my_key - qt * BQ - 4 * hh;
+        dkv_iteration<D, 0, false, true>(st, lds, cur, cur, dkey0, c, load);
+        dkv_iteration<D, 1, false, true>(st, lds, next, cur, dkey0 - 32, c, load);
         stage = stage1;
     };
     // Every head is walked from its LAST q tile down to the diagonal.  All key tiles of one (sequence, kv head)
@@ -308,8 +386,10 @@ __global__ __launch_bounds__(kThreads, 1) void bwd_dkv_kernel(BwdParams p) {
     // would spread them over the whole sequence.
     const int n_masked = min(2, per_head);
     for (int h = 0, u = 0; h < p.group; ++h) {
-        for (int j = per_head - 1; j >= n_masked; --j, ++u) tile_step(u, first_qt + j, std::false_type{});
-        for (int j = n_masked - 1; j >= 0; --j, ++u) tile_step(u, first_qt + j, std::true_type{});
+        int j = per_head - 1;
+        for (; j >= 3; --j, ++u) tile_step_spread(u, first_qt + j, g * p.group + h);
+        for (; j >= n_masked; --j, ++u) tile_step(u, first_qt + j, std::false_type{});
+        for (; j >= 0; --j, ++u) tile_step(u, first_qt + j, std::true_type{});
     }
 
     // epilogue: G2 of the last block
