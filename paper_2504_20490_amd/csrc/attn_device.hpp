@@ -131,6 +131,10 @@ struct TileCopy {
         static_assert(I >= 0 && I < kPerWave, "instruction index");
         global_to_lds<16>(first_row, off[I], tile + (I * 4 + wave) * 1024);
     }
+    // the same with the index as a (compile-time constant after unrolling) argument
+    __device__ __forceinline__ void issue_full_one_at(int i, char* tile, const uint16_t* first_row, int wave) const {
+        global_to_lds<16>(first_row, off[i], tile + (i * 4 + wave) * 1024);
+    }
     // whole tile inside the sequence: rows row0 .. row0+ROWS-1 all exist.  slab points at row 0, column 0.
     __device__ __forceinline__ void issue_full(char* tile, const uint16_t* slab, int64_t stride, int row0, int wave) const {
         const uint16_t* base = slab + (int64_t)row0 * stride;
@@ -239,13 +243,17 @@ __device__ __forceinline__ void store_grad4(void* base, int64_t elem, bool f32, 
 
 // Scheduling hint for one basic block: N times {1 MFMA, DS LDS reads, VA VALU instructions}, in that
 // order, as one pipeline with the given id (llvm.amdgcn.sched.group.barrier; arguments must be constants).
-template <int N, int DS, int VA, int ID>
+// VMASK selects what counts as a VALU instruction: 0x002 plain VALU, 0x402 plain VALU and transcendentals
+// (v_exp_f32 belongs to a class of its own and is left out of a 0x002 group).
+template <int N, int DS, int VA, int ID, int VMASK = 0x002>
 struct InterleaveHint {
     static __device__ __forceinline__ void apply() {
-        __builtin_amdgcn_sched_group_barrier(0x008, 1, ID);
-        if constexpr (DS > 0) __builtin_amdgcn_sched_group_barrier(0x100, DS, ID);
-        if constexpr (VA > 0) __builtin_amdgcn_sched_group_barrier(0x002, VA, ID);
-        if constexpr (N > 1) InterleaveHint<N - 1, DS, VA, ID>::apply();
+        if constexpr (N > 0) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, ID);
+            if constexpr (DS > 0) __builtin_amdgcn_sched_group_barrier(0x100, DS, ID);
+            if constexpr (VA > 0) __builtin_amdgcn_sched_group_barrier(VMASK, VA, ID);
+            InterleaveHint<N - 1, DS, VA, ID, VMASK>::apply();
+        }
     }
 };
 

@@ -37,6 +37,28 @@ struct FwdState {
     int tr[G::DB][2];      // per-lane LDS offsets of the V^T fragments (transpose read), k-step 0 of a tile
 };
 
+// this wave's single copy instructions of one whole K tile and one whole V tile
+template <int D>
+struct FwdTileLoad {
+    using Copy = TileCopy<D, kFwdKTile>;
+    const Copy* copy;
+    const uint16_t* k_row;   // first row of the K tile, this kv head, column 0
+    const uint16_t* v_row;
+    char* k_dst;
+    char* v_dst;
+    int wave;
+    __device__ __forceinline__ void k_piece(int i) const {
+#pragma unroll
+        for (int n = 0; n < Copy::kPerWave; ++n)
+            if (n == i) copy->issue_full_one_at(n, k_dst, k_row, wave);
+    }
+    __device__ __forceinline__ void v_piece(int i) const {
+#pragma unroll
+        for (int n = 0; n < Copy::kPerWave; ++n)
+            if (n == i) copy->issue_full_one_at(n, v_dst, v_row, wave);
+    }
+};
+
 __device__ __forceinline__ float pair_max(float x) {
     // v_permlane32_swap: first result = the value held by lane l % 32, second = the value of lane l % 32 + 32
     const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
@@ -44,30 +66,24 @@ __device__ __forceinline__ float pair_max(float x) {
 }
 
 // One iteration on key tile kt, whose scores are already in st.s:
-//   phase A: MFMA S^T(kt+1) = K(kt+1) Q^T   |  VALU: softmax step of tile kt (max, exp2, row sum, bf16 pack)
+//   first  : VALU only: running max of tile kt; accumulator rescale if some lane's max moved
+//   phase A: MFMA S^T(kt+1) = K(kt+1) Q^T   |  VALU: exp2, row sum, bf16 pack of tile kt
 //   phase B: MFMA O^T += V(kt)^T P^T(kt)
 // kbuf: K tile kt+1; vbuf: V tile kt.  MASK: tile kt touches the diagonal (keys beyond a lane's own row get
 // weight 0); LAST: there is no tile kt+1.
-template <int D, bool MASK, bool LAST>
+// SPREAD: the iteration also issues this wave's share of the copies of K(kt+2) and V(kt+1), both whole
+// tiles, one instruction at a time at fixed places among its LDS reads (copies are ordered against LDS
+// accesses and the reads are tied to the MFMAs by the scheduling hints).  Issued back to back after the
+// barrier, the copies of all waves queue up in front of the CU's one address unit.
+template <int D, bool MASK, bool LAST, bool SPREAD>
 __device__ __forceinline__ void fwd_iteration(FwdState<D>& st, const char* kbuf, const char* vbuf, float c,
-                                              int dkey /* my_row - key0 - 4 * (lane / 32) */) {
+                                              int dkey /* my_row - key0 - 4 * (lane / 32) */,
+                                              const FwdTileLoad<D>& load) {
     using G = FwdGeom<D>;
     constexpr int KK = G::KK, DB = G::DB;
+    constexpr int NP = FwdTileLoad<D>::Copy::kPerWave;   // copy instructions per wave and tile
 
-    // ---------------- phase A
-    f32x16 sn[2];
-    if constexpr (!LAST) {
-#pragma unroll
-        for (int jb = 0; jb < 2; ++jb) {
-#pragma unroll
-            for (int i = 0; i < 16; ++i) sn[jb][i] = 0.f;
-#pragma unroll
-            for (int kk = 0; kk < KK; ++kk) {
-                const bf16x8 kf = *reinterpret_cast<const bf16x8*>(kbuf + st.rm[kk] + jb * 32 * D * 2);
-                sn[jb] = mfma(kf, st.qf[kk], sn[jb]);
-            }
-        }
-    }
+    // ---------------- running max of tile kt and the (rare) accumulator rescale: a short VALU-only stretch
     if constexpr (MASK) {
         // element i of block jb is key 32 jb + 8 (i / 4) + i % 4 (+ 4 (lane / 32), folded into dkey)
 #pragma unroll
@@ -84,52 +100,88 @@ __device__ __forceinline__ void fwd_iteration(FwdState<D>& st, const char* kbuf,
     tmax = pair_max(tmax);
     const float m_new = fmaxf(st.m, tmax);
     const float alpha = fast_exp2((st.m - m_new) * c);
-    const bool rescale = __any(m_new > st.m);      // wave-uniform: skip the accumulator rescale when no max moved
     const float mc = m_new * c;
-    st.m = m_new;
-    float psum = 0.f;
-    bf16x8 pf[4];
-#pragma unroll
-    for (int jb = 0; jb < 2; ++jb) {
-        float e[16];
-#pragma unroll
-        for (int i = 0; i < 16; ++i) {
-            e[i] = fast_exp2(fmaf(st.s[jb][i], c, -mc));
-            psum += e[i];
-        }
-#pragma unroll
-        for (int tt = 0; tt < 2; ++tt) {
-            union { u32x4 u; bf16x8 v; } r;
-#pragma unroll
-            for (int w = 0; w < 4; ++w) r.u[w] = pack_bf16(e[8 * tt + 2 * w], e[8 * tt + 2 * w + 1]);
-            pf[jb * 2 + tt] = r.v;
-        }
-    }
-    st.l = st.l * alpha + psum;
-    if constexpr (!LAST) {
-        // per MFMA: one K fragment read and a share of the softmax VALU work
-        InterleaveHint<2 * KK, 1, (MASK ? 13 : 9), 0>::apply();
-    }
-    __builtin_amdgcn_sched_barrier(0);
-
-    // ---------------- phase B
-    if (rescale) {
+    if (__any(m_new > st.m)) {      // wave-uniform: skip the accumulator rescale when no lane's max moved
 #pragma unroll
         for (int db = 0; db < DB; ++db)
 #pragma unroll
             for (int i = 0; i < 16; ++i) st.acc[db][i] *= alpha;
     }
+    st.m = m_new;
+    __builtin_amdgcn_sched_barrier(0);
+
+    // ---------------- phase A: S^T(kt+1) on the MFMA, exp2 / row sum / bf16 pack of tile kt on the VALU.
+    // Written out step by step with a scheduling barrier after each: step n issues the K fragment read of
+    // MFMA n + kAheadK, MFMA n, and the softmax work on two scores.
+    f32x16 sn[2];
+    float psum = 0.f;
+    union { u32x4 u; bf16x8 v; } pw[4];
+    auto softmax_pair = [&](int n) {   // scores 2n, 2n+1 of the tile's 32 per lane -> one packed bf16 pair
+        const int jb = n >> 3, i = (n & 7) * 2;
+        const float e0 = fast_exp2(fmaf(st.s[jb][i], c, -mc));
+        const float e1 = fast_exp2(fmaf(st.s[jb][i + 1], c, -mc));
+        psum += e0 + e1;
+        pw[jb * 2 + (i >> 3)].u[(i >> 1) & 3] = pack_bf16(e0, e1);
+    };
+    if constexpr (!LAST) {
+        constexpr int kAheadK = 4;
+        constexpr int NM = 2 * KK;               // MFMAs of the phase
+        constexpr int every = NM / NP;           // one copy instruction per `every` MFMAs
+        auto k_frag = [&](int n) {
+            return *reinterpret_cast<const bf16x8*>(kbuf + st.rm[n % KK] + (n / KK) * 32 * D * 2);
+        };
+        bf16x8 kq[kAheadK + 1];
 #pragma unroll
-    for (int t = 0; t < 4; ++t) {
+        for (int n = 0; n < kAheadK; ++n) kq[n] = k_frag(n);
 #pragma unroll
-        for (int db = 0; db < DB; ++db) {
+        for (int i = 0; i < 16; ++i) { sn[0][i] = 0.f; sn[1][i] = 0.f; }
+#pragma unroll
+        for (int n = 0; n < NM; ++n) {
+            if (n + kAheadK < NM) kq[(n + kAheadK) % (kAheadK + 1)] = k_frag(n + kAheadK);
+            sn[n / KK] = mfma(kq[n % (kAheadK + 1)], st.qf[n % KK], sn[n / KK]);
+            // 16 score pairs over the NM MFMAs
+            if constexpr (NM == 16) {
+                softmax_pair(n);
+            } else {
+                softmax_pair(2 * n);
+                softmax_pair(2 * n + 1);
+            }
+            if constexpr (SPREAD) {
+                if (n % every == every - 1) load.k_piece(n / every);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    } else {
+#pragma unroll
+        for (int n = 0; n < 16; ++n) softmax_pair(n);
+    }
+    st.l = st.l * alpha + psum;
+    __builtin_amdgcn_sched_barrier(0);
+
+    // ---------------- phase B: O^T += V(kt)^T P^T(kt), transpose reads kAheadV MFMAs ahead
+    {
+        constexpr int kAheadV = 3;
+        constexpr int NM = 4 * DB;
+        constexpr int every = NM / NP;
+        auto v_frag = [&](int n) {
+            const int t = n / DB, db = n % DB;
             const int off = t * 16 * D * 2;
-            const s16x4 lo = lds_transpose_read(vbuf + st.tr[db][0] + off);
-            const s16x4 hi = lds_transpose_read(vbuf + st.tr[db][1] + off);
             union { struct { s16x4 a, b; } s; bf16x8 v; } u;
-            u.s.a = lo;
-            u.s.b = hi;
-            st.acc[db] = mfma(u.v, pf[t], st.acc[db]);
+            u.s.a = lds_transpose_read(vbuf + st.tr[db][0] + off);
+            u.s.b = lds_transpose_read(vbuf + st.tr[db][1] + off);
+            return u.v;
+        };
+        bf16x8 vq[kAheadV + 1];
+#pragma unroll
+        for (int n = 0; n < kAheadV; ++n) vq[n] = v_frag(n);
+#pragma unroll
+        for (int n = 0; n < NM; ++n) {
+            if (n + kAheadV < NM) vq[(n + kAheadV) % (kAheadV + 1)] = v_frag(n + kAheadV);
+            st.acc[n % DB] = mfma(vq[n % (kAheadV + 1)], pw[n / DB].v, st.acc[n % DB]);
+            if constexpr (SPREAD) {
+                if (n % every == every - 1) load.v_piece(n / every);
+            }
+            __builtin_amdgcn_sched_barrier(0);
         }
     }
     if constexpr (!LAST) {
@@ -218,6 +270,7 @@ __global__ __launch_bounds__(kThreads, 2) void fwd_kernel(FwdParams p) {
 
     // iteration kt: K(kt+1) in kbuf[(kt+1) & 1], V(kt) in vbuf[kt & 1]; issues K(kt+2) -> kbuf[kt & 1] and
     // V(kt+1) -> vbuf[(kt+1) & 1], both free since the barrier at the top
+    FwdTileLoad<D> no_load{};
     auto step = [&](int kt, auto masked, auto last) {
         if (kt > 0) {
             wait_tile_loads();
@@ -225,13 +278,33 @@ __global__ __launch_bounds__(kThreads, 2) void fwd_kernel(FwdParams p) {
         }
         if (kt + 2 < n_tiles) kvcopy.issue(kbuf0 + (kt & 1) * kTileBytes, kbase, p.kv_stride, (kt + 2) * BK, L, wave, lane);
         if (kt + 1 < n_tiles) kvcopy.issue(vbuf0 + ((kt + 1) & 1) * kTileBytes, vbase, p.kv_stride, (kt + 1) * BK, L, wave, lane);
-        fwd_iteration<D, decltype(masked)::value, decltype(last)::value>(
-            st, kbuf0 + ((kt + 1) & 1) * kTileBytes, vbuf0 + (kt & 1) * kTileBytes, c, my_row - kt * BK - 4 * hh);
+        fwd_iteration<D, decltype(masked)::value, decltype(last)::value, false>(
+            st, kbuf0 + ((kt + 1) & 1) * kTileBytes, vbuf0 + (kt & 1) * kTileBytes, c, my_row - kt * BK - 4 * hh, no_load);
     };
-    // three loops instead of branches inside one: unmasked tiles, masked tiles, and the final tile (which has no
-    // successor to compute scores for); the large register state then meets at a join once per loop, not per tile
+    // the same for an unmasked tile whose successors kt+1 and kt+2 are whole tiles: their copies need no case
+    // distinction and are issued from inside the iteration
+    auto step_spread = [&](int kt) {
+        if (kt > 0) {
+            wait_tile_loads();
+            __syncthreads();
+        }
+        FwdTileLoad<D> load;
+        load.copy = &kvcopy;
+        load.k_row = kbase + (int64_t)(kt + 2) * BK * p.kv_stride;
+        load.v_row = vbase + (int64_t)(kt + 1) * BK * p.kv_stride;
+        load.k_dst = kbuf0 + (kt & 1) * kTileBytes;
+        load.v_dst = vbuf0 + ((kt + 1) & 1) * kTileBytes;
+        load.wave = wave;
+        fwd_iteration<D, false, false, true>(st, kbuf0 + ((kt + 1) & 1) * kTileBytes, vbuf0 + (kt & 1) * kTileBytes, c,
+                                             my_row - kt * BK - 4 * hh, load);
+    };
+    // separate loops instead of branches inside one: unmasked tiles (with and without whole successors), masked
+    // tiles, and the final tile (which has no successor to compute scores for); the large register state then
+    // meets at a join once per loop, not per tile
     const int n_plain = min(n_interior, n_tiles - 1);
+    const int n_spread = max(0, min(n_plain, L / BK - 2));   // tile kt+2 exists and is whole
     int kt = 0;
+    for (; kt < n_spread; ++kt) step_spread(kt);
     for (; kt < n_plain; ++kt) step(kt, std::false_type{}, std::false_type{});
     for (; kt < n_tiles - 1; ++kt) step(kt, std::true_type{}, std::false_type{});
     step(kt, std::true_type{}, std::true_type{});   // the final tile always touches the diagonal
