@@ -98,8 +98,81 @@ __global__ __launch_bounds__(kThreads, 2) void bwd_dq_kernel(BwdParams p) {
 #pragma unroll
         for (int i = 0; i < 16; ++i) acc[db][i] = 0.f;
 
-    // One key tile.  MASK = false: every key of the tile precedes every row of this q tile (no compare, no
-    // skipped block); MASK = true: the tile touches the diagonal.
+    // per-lane LDS offsets of the operand fragments inside a tile
+    int rm[KK], tr[DB][2];
+#pragma unroll
+    for (int kk = 0; kk < KK; ++kk) rm[kk] = tile_offset<D>(lane & 31, kk * 16 + hh * 8);
+    {
+        const int c16 = lane & 15;
+        const int row = (hh << 2) + (c16 >> 2);
+#pragma unroll
+        for (int db = 0; db < DB; ++db) {
+            const int col = db * 32 + (((lane >> 4) & 1) << 4) + ((c16 & 3) << 2);
+            tr[db][0] = tile_offset<D>(row, col);
+            tr[db][1] = tile_offset<D>(row + 8, col);
+        }
+    }
+
+    // One 32-key block, written step by step with a scheduling barrier after each step so that operand
+    // fragments are requested kAhead MFMAs before their use:
+    //   2 KK steps: S^T = K Q^T then dP^T = V dO^T   (fragments along tile rows)
+    //   VALU      : dS^T = exp2(S^T c - LSE log2e) (dP^T - D), with the first K^T fragments already requested
+    //   2 DB steps: dQ^T += K^T dS^T                 (fragments by transpose read)
+    // MASK: the block touches the diagonal.  SPREAD: step n of the first phase also issues copy instruction
+    // n / (2 KK / kPerWave) of a whole tile (K in block 0, V in block 1), see `piece`.
+    auto block = [&](const char* ktile, const char* vtile, int jb, int kb, auto masked, auto spread, auto&& piece) {
+        constexpr bool kMask = decltype(masked)::value;
+        constexpr bool kSpread = decltype(spread)::value;
+        constexpr int kAhead = 4, kAheadT = 3;
+        constexpr int N1 = 2 * KK, N2 = 2 * DB;
+        constexpr int every = N1 / TileCopy<D, BK>::kPerWave;
+        auto frag1 = [&](int n) {
+            return *reinterpret_cast<const bf16x8*>((n < KK ? ktile : vtile) + rm[n % KK] + jb * 32 * D * 2);
+        };
+        auto frag2 = [&](int n) {
+            const int off = (jb * 2 + n / DB) * 16 * D * 2;
+            union { struct { s16x4 a, b; } s; bf16x8 v; } u;
+            u.s.a = lds_transpose_read(ktile + tr[n % DB][0] + off);
+            u.s.b = lds_transpose_read(ktile + tr[n % DB][1] + off);
+            return u.v;
+        };
+        f32x16 sacc, dp;
+#pragma unroll
+        for (int i = 0; i < 16; ++i) { sacc[i] = 0.f; dp[i] = 0.f; }
+        bf16x8 q1[kAhead + 1];
+#pragma unroll
+        for (int n = 0; n < kAhead; ++n) q1[n] = frag1(n);
+#pragma unroll
+        for (int n = 0; n < N1; ++n) {
+            if (n + kAhead < N1) q1[(n + kAhead) % (kAhead + 1)] = frag1(n + kAhead);
+            if (n < KK) sacc = mfma(q1[n % (kAhead + 1)], qf[n], sacc);
+            else dp = mfma(q1[n % (kAhead + 1)], dof[n - KK], dp);
+            if constexpr (kSpread) {
+                if (n % every == every - 1) piece(jb, n / every);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        bf16x8 q2[kAheadT + 1];
+#pragma unroll
+        for (int n = 0; n < kAheadT; ++n) q2[n] = frag2(n);
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+            float pr = fast_exp2(fmaf(sacc[i], c, -lse2));
+            if (kMask && kb + acc_row(i, lane) > my_row) pr = 0.f;
+            sacc[i] = pr * (dp[i] - dsum);   // dS^T
+        }
+        const bf16x8 dsf[2] = {frag_to_bf16(sacc, 0), frag_to_bf16(sacc, 1)};
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int n = 0; n < N2; ++n) {
+            if (n + kAheadT < N2) q2[(n + kAheadT) % (kAheadT + 1)] = frag2(n + kAheadT);
+            acc[n % DB] = mfma(q2[n % (kAheadT + 1)], dsf[n / DB], acc[n % DB]);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    };
+
+    // One key tile of the general kind: copies of the next tile issued at the top, blocks that lie wholly
+    // above the diagonal for this wave skipped.
     auto step = [&](int kt, auto masked) {
         constexpr bool kMask = decltype(masked)::value;
         wait_tile_loads();
@@ -111,49 +184,36 @@ __global__ __launch_bounds__(kThreads, 2) void bwd_dq_kernel(BwdParams p) {
             kvcopy.issue(next, kbase, p.kv_stride, (kt + 1) * BK, L, wave, lane);
             kvcopy.issue(next + kTileBytes, vbase, p.kv_stride, (kt + 1) * BK, L, wave, lane);
         }
-        const int key0 = kt * BK;
+        auto none = [](int, int) {};
 #pragma unroll
         for (int jb = 0; jb < 2; ++jb) {
-            const int kb = key0 + jb * 32;
-            if (!kMask || kb <= wave_row0 + 31) {           // otherwise every key of the block is masked for this wave
-                f32x16 s, dp;
-#pragma unroll
-                for (int i = 0; i < 16; ++i) { s[i] = 0.f; dp[i] = 0.f; }
-                {
-                    bf16x8 kf[KK];
-#pragma unroll
-                    for (int kk = 0; kk < KK; ++kk) kf[kk] = read_rowmajor_frag<D>(ktile, jb, kk, lane);
-#pragma unroll
-                    for (int kk = 0; kk < KK; ++kk) s = mfma(kf[kk], qf[kk], s);
-                }
-                {
-                    bf16x8 vf[KK];
-#pragma unroll
-                    for (int kk = 0; kk < KK; ++kk) vf[kk] = read_rowmajor_frag<D>(vtile, jb, kk, lane);
-#pragma unroll
-                    for (int kk = 0; kk < KK; ++kk) dp = mfma(vf[kk], dof[kk], dp);
-                }
-#pragma unroll
-                for (int i = 0; i < 16; ++i) {
-                    float pr = fast_exp2(fmaf(s[i], c, -lse2));
-                    if (kMask && kb + acc_row(i, lane) > my_row) pr = 0.f;
-                    s[i] = pr * (dp[i] - dsum);   // dS^T
-                }
-#pragma unroll
-                for (int tt = 0; tt < 2; ++tt) {
-                    const bf16x8 dsf = frag_to_bf16(s, tt);
-                    bf16x8 ktf[DB];
-#pragma unroll
-                    for (int db = 0; db < DB; ++db) ktf[db] = read_transposed_frag<D>(ktile, db, jb * 2 + tt, lane);
-#pragma unroll
-                    for (int db = 0; db < DB; ++db) acc[db] = mfma(ktf[db], dsf, acc[db]);
-                }
-            }
+            const int kb = kt * BK + jb * 32;
+            if (!kMask || kb <= wave_row0 + 31) block(ktile, vtile, jb, kb, masked, std::false_type{}, none);
         }
     };
-    // two loops instead of a test per tile: the tiles wholly below the diagonal, then the (at most two) on it
+    // An unmasked tile whose successor is a whole tile: the successor's copies are issued from inside the blocks,
+    // one instruction at a time (all waves' copies issued together queue up in front of the CU's address unit).
+    auto step_spread = [&](int kt) {
+        wait_tile_loads();
+        __syncthreads();
+        const char* ktile = lds + (kt & 1) * (2 * kTileBytes);
+        const char* vtile = ktile + kTileBytes;
+        char* next = lds + ((kt + 1) & 1) * (2 * kTileBytes);
+        const uint16_t* k_row = kbase + (int64_t)(kt + 1) * BK * p.kv_stride;
+        const uint16_t* v_row = vbase + (int64_t)(kt + 1) * BK * p.kv_stride;
+        auto piece = [&](int jb, int i) {
+            if (jb == 0) kvcopy.issue_full_one_at(i, next, k_row, wave);
+            else kvcopy.issue_full_one_at(i, next + kTileBytes, v_row, wave);
+        };
+        block(ktile, vtile, 0, kt * BK, std::false_type{}, std::true_type{}, piece);
+        block(ktile, vtile, 1, kt * BK + 32, std::false_type{}, std::true_type{}, piece);
+    };
+    // separate loops instead of tests per tile: tiles wholly below the diagonal (with and without a whole
+    // successor), then the (at most two) tiles on the diagonal
     const int n_interior = min(n_tiles, 2 * item.tile);
+    const int n_spread = max(0, min(min(n_interior, n_tiles - 1), L / BK - 1));
     int kt = 0;
+    for (; kt < n_spread; ++kt) step_spread(kt);
     for (; kt < n_interior; ++kt) step(kt, std::false_type{});
     for (; kt < n_tiles; ++kt) step(kt, std::true_type{});
 
