@@ -167,6 +167,11 @@ def main() -> int:
         A.Plan(cu, hq, hkv, d, stream.cuda_stream, order=order).destroy()
     plan_ms = (time.perf_counter() - t1) / 5 * 1e3
 
+    # measured matrix-core rate of this device (register-only MFMA loop): a second denominator beside the nominal peak
+    probe = torch.empty(A.probe_scratch_bytes(), dtype=torch.uint8, device=dev)
+    mfma_measured = A.probe_mfma_tflops(probe, stream=stream)
+    del probe
+
     ms_per_step = elapsed / args.steps * 1e3
     fwd = w.fwd_flops(lengths, hq, d)
     useful = 3.5 * fwd
@@ -203,6 +208,8 @@ def main() -> int:
                      "unit": "TFLOP/s", "frac": round(achieved / PEAK_BF16_TFLOPS, 4),
                      "traffic": read_traffic(dominant, cfg.name.split("_")[0]),
                      "flops_per_launch": GEMMS[dominant] * pair_flops,
+                     "measured_mfma_peak": round(mfma_measured, 1),
+                     "frac_of_measured_peak": round(achieved / mfma_measured, 4) if mfma_measured > 0 else None,
                      "note": f"{GEMMS[dominant]} GEMMs over the visible pairs; avg of {prof[dominant][1]} launches "
                              "timed with HIP events on the launch stream"},
     }

@@ -204,6 +204,20 @@ hspmd_status hspmd_profile_enable(int32_t on);
 hspmd_status hspmd_profile_read(double* ms, int64_t* launches);
 const char* hspmd_kernel_name(int32_t kernel);   /* symbol-like name, NULL if out of range */
 
+/*
+ * Measured matrix-core rate of the device the library runs on: a second denominator beside the
+ * nominal bf16 peak (measurement only; not part of the paper's method).  Launches, on `stream`, a
+ * kernel in which every wave of every compute unit issues `mfma_per_wave` back-to-back
+ * v_mfma_f32_32x32x16_bf16 on register operands (four independent accumulators, no memory traffic),
+ * times it with a pair of HIP events and returns the dense bf16 rate in TFLOP/s.  One untimed
+ * launch precedes the timed one.  Synchronises the stream; scratch_out is caller-owned device
+ * memory of at least hspmd_probe_scratch_bytes() bytes that receives a checksum (so that the
+ * compiler keeps the products).  mfma_per_wave is rounded up to a multiple of 16; <= 0 is INVALID_ARG.
+ */
+size_t       hspmd_probe_scratch_bytes(void);
+hspmd_status hspmd_probe_mfma_tflops(int64_t mfma_per_wave, void* scratch_out, size_t scratch_bytes,
+                                     void* stream, double* tflops);
+
 #ifdef __cplusplus
 }
 #endif

@@ -83,6 +83,11 @@ def load_library():
                                           ctypes.c_float, vp, vp, vp, ctypes.c_int, vp, ctypes.c_size_t, vp]
     lib.hspmd_profile_enable.restype = ctypes.c_int
     lib.hspmd_profile_enable.argtypes = [ctypes.c_int32]
+    lib.hspmd_probe_scratch_bytes.restype = ctypes.c_size_t
+    lib.hspmd_probe_scratch_bytes.argtypes = []
+    lib.hspmd_probe_mfma_tflops.restype = ctypes.c_int
+    lib.hspmd_probe_mfma_tflops.argtypes = [ctypes.c_int64, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p,
+                                            ctypes.POINTER(ctypes.c_double)]
     lib.hspmd_profile_read.restype = ctypes.c_int
     lib.hspmd_profile_read.argtypes = [ctypes.POINTER(ctypes.c_double), i64p]
     lib.hspmd_kernel_name.restype = ctypes.c_char_p
@@ -225,3 +230,17 @@ def profile_read():
     n = (ctypes.c_int64 * NUM_KERNELS)()
     _check(lib.hspmd_profile_read(ms, n))
     return {lib.hspmd_kernel_name(i).decode(): (float(ms[i]), int(n[i])) for i in range(NUM_KERNELS)}
+
+
+def probe_scratch_bytes() -> int:
+    return int(load_library().hspmd_probe_scratch_bytes())
+
+
+def probe_mfma_tflops(scratch, mfma_per_wave: int = 1 << 18, stream=None) -> float:
+    """Measured dense bf16 MFMA rate (TFLOP/s) of the current device; scratch is a device tensor of at least
+    probe_scratch_bytes() bytes.  Synchronises the stream."""
+    out = ctypes.c_double(0.0)
+    _check(load_library().hspmd_probe_mfma_tflops(int(mfma_per_wave), _dev_ptr(scratch),
+                                                  scratch.numel() * scratch.element_size(), _stream_handle(stream),
+                                                  ctypes.byref(out)))
+    return float(out.value)

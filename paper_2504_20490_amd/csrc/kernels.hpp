@@ -47,4 +47,11 @@ hipError_t launch_bwd_dsum(const BwdParams& p, int head_dim, hipStream_t stream)
 hipError_t launch_bwd_dq(const BwdParams& p, int head_dim, int64_t num_items, hipStream_t stream);
 hipError_t launch_bwd_dkv(const BwdParams& p, int head_dim, int64_t num_items, hipStream_t stream);
 
+// matrix-core rate probe: `grid` workgroups of kProbeThreads threads, each wave issues 16 * rounds MFMAs and
+// every thread writes one float to out[grid * kProbeThreads]
+constexpr int kProbeMaxGrid = 4096;
+constexpr int kProbeThreads = 256;
+int probe_grid(int compute_units);
+hipError_t launch_mfma_probe(float* out, int64_t rounds, int grid, hipStream_t stream);
+
 }  // namespace hspmd

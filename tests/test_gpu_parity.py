@@ -147,3 +147,17 @@ def test_argument_validation_on_device_calls():
                           grad_dtype=5)
     assert e.value.status == 2
     run.run()   # still usable after rejected calls
+
+
+@pytest.mark.gpu
+def test_mfma_rate_probe_is_plausible():
+    """The measurement hook returns a rate between a third of and slightly above the nominal 2.5 PFLOP/s."""
+    import torch
+    import paper_2504_20490_amd as A
+    scratch = torch.empty(A.probe_scratch_bytes(), dtype=torch.uint8, device="cuda")
+    rate = A.probe_mfma_tflops(scratch, mfma_per_wave=1 << 16)
+    assert 800.0 < rate < 2700.0, rate
+    with pytest.raises(A.HspmdError):
+        A.probe_mfma_tflops(scratch[:16])
+    with pytest.raises(A.HspmdError):
+        A.probe_mfma_tflops(scratch, mfma_per_wave=0)
