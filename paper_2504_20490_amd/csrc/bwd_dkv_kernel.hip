@@ -3,20 +3,22 @@
 // Each of the 4 waves owns 32 keys (K and V rows stay in registers as MFMA B operands) and walks
 // over the query heads of the KV group and, per head, over the 32-row query blocks at or below the
 // diagonal.  Per block b:
-//     G1(b): S = Q_b K^T, dP = dO_b V^T                      (16 MFMA, operands read along tile rows)
-//     V(b) : P = exp2(S c - LSE log2e), dS = P (dP - D)      (VALU, one lane per key)
-//     G2(b): dV^T += dO_b^T P, dK^T += Q_b^T dS              (16 MFMA, operands by LDS transpose read)
+//     G1(b): S' = Q_b K^T - LSE/scale, dP' = dO_b V^T - D    (16 MFMA, operands read along tile rows; the
+//            statistics are the initial accumulator values)
+//     V(b) : P = exp2(S' c), dS = P dP'                       (VALU, one lane per key)
+//     G2(b): dV^T += dO_b^T P, dK^T += Q_b^T dS               (16 MFMA, operands by LDS transpose read)
 // The group loop runs inside the workgroup, so dK/dV need no atomics.
 //
 // The kernel holds two fp32 accumulators of 32 x D per wave, which leaves room for only one wave
-// per SIMD; nothing else can hide MFMA latency, so the loop is software-pipelined inside the wave.
-// Iteration i is one basic block in two phases:
-//     phase A: MFMA G2(i-1)  |  VALU V(i)            |  LDS reads: statistics of block i, Q/dO rows of block i+1
-//     phase B: MFMA G1(i+1)  |  pack P, dS to bf16   |  LDS reads: Q^T/dO^T of block i (for G2(i) next time)
-// so every MFMA operand is requested half an iteration (16 MFMAs) before its use and the exp/FMA work
-// of one block runs under the MFMAs of its neighbours.  Scheduling-group hints fix the interleaving.
+// per SIMD; one wave is one in-order instruction stream, so the loop is software-pipelined inside the
+// wave and the instruction count per MFMA is kept low.  Iteration i is one basic block in two phases:
+//     phase A: MFMA G2(i-1)  |  first half of V(i)   |  LDS reads: Q/dO rows and statistics of block i+1
+//     phase B: MFMA G1(i+1)  |  second half of V(i)  |  LDS reads: Q^T/dO^T of block i (for G2(i) next time)
+// so every MFMA operand is requested half an iteration (16 MFMAs) before its use and the exp/multiply work
+// of one block is spread under the MFMAs of its neighbours.  S'/dP' are double buffered (block i is still
+// being consumed while G1(i+1) accumulates).  Scheduling-group hints fix the interleaving.
 //
-// LDS: four stages of {Q tile, dO tile (64 rows each), LSE log2e [64], D [64]}.  While iterations
+// LDS: four stages of {Q tile, dO tile (64 rows each), -LSE/scale [64], -D [64]}.  While iterations
 // 2t and 2t+1 work on tile t and read ahead into tile t+1, tiles t+2 and t+3 are in flight
 // (global -> LDS copies; t+3 goes into the stage that tile t-1 occupied).  One barrier per tile.
 #include <type_traits>
@@ -35,7 +37,7 @@ struct DkvGeom {
     static constexpr int DB = D / 32;                      // 32-row blocks of dK^T / dV^T
     static constexpr int kTileBytes = kDkvQTile * D * 2;   // one 64-row tile
     static constexpr int kBlockBytes = 32 * D * 2;         // one 32-row block of it
-    static constexpr int kStatBytes = 1024;                // lse2[64] at +0, D[64] at +256
+    static constexpr int kStatBytes = 1024;                // -LSE/scale [64] at +0, -D [64] at +256
     static constexpr int kStageBytes = 2 * kTileBytes + kStatBytes;
     static constexpr int kStages = 4;
 };
@@ -45,11 +47,10 @@ struct DkvState {
     using G = DkvGeom<D>;
     bf16x8 kf[G::KK], vf[G::KK];           // this wave's 32 keys: K rows, V rows (B operands)
     f32x16 dk[G::DB], dv[G::DB];           // dK^T, dV^T accumulators
-    f32x16 s_cur, dp_cur;                  // S, dP of block i
+    f32x16 s[2], dp[2];                    // S - LSE/scale and dP - D: [i & 1] of block i, [~i & 1] of block i+1
     bf16x8 qf[G::KK], dof[G::KK];          // Q, dO rows of block i+1 (A operands of G1), live inside an iteration
     bf16x8 qtf[G::KK], dotf[G::KK];        // Q^T, dO^T of block i-1 (A operands of G2), index tt*DB + db
     bf16x8 pprev[2], dsprev[2];            // P, dS of block i-1 as bf16 B operands
-    f32x4 lse4[4], ds4[4];                 // LSE log2e and D of block i's rows (rows 8 j + 4 (lane / 32) .. + 3 in [j])
 };
 
 // per-lane LDS byte addresses (stage base included) of the operand fragments
@@ -73,7 +74,7 @@ struct DkvTileLoad {
     const Copy* docopy;
     const uint16_t* q_row;      // first row of the tile, this head, column 0
     const uint16_t* do_row;
-    const float* stat;          // LSE log2e (even waves) or D (odd waves) of the tile's first row
+    const float* stat;          // -LSE/scale (even waves) or -D (odd waves) of the tile's first row
     char* stage;
     char* stat_dst;
     int wave, lane;
@@ -118,7 +119,28 @@ __device__ __forceinline__ void dkv_iteration(DkvState<D>& st, const char* lds, 
     constexpr int NRB = RB ^ 1;   // block i+1 sits at the other position (of the next tile when RB == 1)
     constexpr int P0 = RB == 0 ? 0 : 4;   // first piece of this iteration
 
+    // element e of an accumulator fragment -> packed bf16 pair index; one half = 8 elements = one B operand
+    auto softmax_half = [&](int half, u32x4& pw, u32x4& dw) {
+#pragma unroll
+        for (int e = 8 * half; e < 8 * half + 8; e += 2) {
+            float p0 = fast_exp2(st.s[RB][e] * c);
+            float p1 = fast_exp2(st.s[RB][e + 1] * c);
+            if (MASK && (8 * (e >> 2) + (e & 3) < dkey)) p0 = 0.f;
+            if (MASK && (8 * ((e + 1) >> 2) + ((e + 1) & 3) < dkey)) p1 = 0.f;
+            pw[(e >> 1) & 3] = pack_bf16(p0, p1);
+            dw[(e >> 1) & 3] = pack_bf16(p0 * st.dp[RB][e], p1 * st.dp[RB][e + 1]);
+        }
+    };
+
     // ================= phase A =================
+    // statistics of block i+1 straight into its accumulators: rows 8 j + 4 (lane / 32) .. + 3 in registers 4 j .. 4 j + 3
+#pragma unroll
+    for (int i4 = 0; i4 < 4; ++i4) {
+        const f32x4 a = *reinterpret_cast<const f32x4*>(lds + ahead.st + NRB * 128 + i4 * 32);
+        const f32x4 b = *reinterpret_cast<const f32x4*>(lds + ahead.st + NRB * 128 + i4 * 32 + 256);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) { st.s[NRB][4 * i4 + j] = a[j]; st.dp[NRB][4 * i4 + j] = b[j]; }
+    }
 #pragma unroll
     for (int kk = 0; kk < KK; ++kk) {
         st.qf[kk] = lds_read128(lds, ahead.rm[kk] + NRB * G::kBlockBytes);
@@ -135,38 +157,16 @@ __device__ __forceinline__ void dkv_iteration(DkvState<D>& st, const char* lds, 
         st.dv[db] = mfma(st.dotf[kk], st.pprev[tt], st.dv[db]);
         st.dk[db] = mfma(st.qtf[kk], st.dsprev[tt], st.dk[db]);
     }
-    // V(i): P first (S is complete long before dP), then dS; packed to bf16 pair by pair
-    float pe[16];
-#pragma unroll
-    for (int e = 0; e < 16; ++e) {
-        pe[e] = fast_exp2(fmaf(st.s_cur[e], c, -st.lse4[e >> 2][e & 3]));
-        if (MASK && (8 * (e >> 2) + (e & 3) < dkey)) pe[e] = 0.f;
-    }
-    u32x4 pw[2], dw[2];
-#pragma unroll
-    for (int e = 0; e < 16; e += 2) {
-        const float d0 = pe[e] * (st.dp_cur[e] - st.ds4[e >> 2][e & 3]);
-        const float d1 = pe[e + 1] * (st.dp_cur[e + 1] - st.ds4[(e + 1) >> 2][(e + 1) & 3]);
-        pw[e >> 3][(e >> 1) & 3] = pack_bf16(pe[e], pe[e + 1]);
-        dw[e >> 3][(e >> 1) & 3] = pack_bf16(d0, d1);
-    }
-    // per MFMA: 2 LDS reads (2*KK fragments in all) and a share of V(i)'s VALU work
-    InterleaveHint<2 * KK, 2, (MASK ? 9 : 7), 0>::apply();
+    u32x4 pw0, dw0;
+    softmax_half(0, pw0, dw0);
+    // per MFMA: LDS reads (8 statistics + 2*KK fragments in all) and a share of the VALU work
+    InterleaveHint<2 * KK, 2, (MASK ? 4 : 3), 0, 0x402>::apply();
     __builtin_amdgcn_sched_barrier(0);
 
     // ================= phase B =================
     union { u32x4 u; bf16x8 v; } cv;
-    cv.u = pw[0]; st.pprev[0] = cv.v;
-    cv.u = pw[1]; st.pprev[1] = cv.v;
-    cv.u = dw[0]; st.dsprev[0] = cv.v;
-    cv.u = dw[1]; st.dsprev[1] = cv.v;
-    // statistics of block i+1, first in the phase: they are the oldest LDS reads in flight when the next
-    // iteration's exp work starts, so it never waits for them
-#pragma unroll
-    for (int i4 = 0; i4 < 4; ++i4) {
-        st.lse4[i4] = *reinterpret_cast<const f32x4*>(lds + ahead.st + NRB * 128 + i4 * 32);
-        st.ds4[i4] = *reinterpret_cast<const f32x4*>(lds + ahead.st + NRB * 128 + i4 * 32 + 256);
-    }
+    cv.u = pw0; st.pprev[0] = cv.v;
+    cv.u = dw0; st.dsprev[0] = cv.v;
 #pragma unroll
     for (int tt = 0; tt < 2; ++tt)
 #pragma unroll
@@ -180,15 +180,16 @@ __device__ __forceinline__ void dkv_iteration(DkvState<D>& st, const char* lds, 
                 if (RB == 1 && tt == 1 && db == DB - 1) load.template piece<P0 + 4>();
             }
         }
-    // G1(i+1): the S chain first, so that the next iteration's exp work never waits for it
+    // G1(i+1) on top of the statistics
 #pragma unroll
-    for (int i = 0; i < 16; ++i) { st.s_cur[i] = 0.f; st.dp_cur[i] = 0.f; }
+    for (int kk = 0; kk < KK; ++kk) st.s[NRB] = mfma(st.qf[kk], st.kf[kk], st.s[NRB]);
 #pragma unroll
-    for (int kk = 0; kk < KK; ++kk) st.s_cur = mfma(st.qf[kk], st.kf[kk], st.s_cur);
-#pragma unroll
-    for (int kk = 0; kk < KK; ++kk) st.dp_cur = mfma(st.dof[kk], st.vf[kk], st.dp_cur);
-    __builtin_amdgcn_sched_group_barrier(0x100, 8, 1);   // the 8 statistics reads
-    InterleaveHint<2 * KK, 2, 0, 1>::apply();            // then per MFMA: 2 of the 4*KK transpose reads
+    for (int kk = 0; kk < KK; ++kk) st.dp[NRB] = mfma(st.dof[kk], st.vf[kk], st.dp[NRB]);
+    u32x4 pw1, dw1;
+    softmax_half(1, pw1, dw1);
+    cv.u = pw1; st.pprev[1] = cv.v;
+    cv.u = dw1; st.dsprev[1] = cv.v;
+    InterleaveHint<2 * KK, 2, (MASK ? 4 : 3), 1, 0x402>::apply();   // per MFMA: 2 of the 4*KK transpose reads, VALU share
     __builtin_amdgcn_sched_barrier(0);
 }
 
@@ -232,7 +233,7 @@ __global__ __launch_bounds__(kThreads, 1) void bwd_dkv_kernel(BwdParams p) {
         const int row0 = (n_qt - 1 - u % per_head) * BQ;   // q tiles are walked from the end of the sequence down
         const uint16_t* qb = p.q + (int64_t)item.token_start * p.q_stride + (int64_t)hq * D;
         const uint16_t* dob = p.d_o + ((int64_t)item.token_start * p.q_heads + hq) * D;
-        // even waves: LSE log2e of the 64 rows; odd waves: D (waves 2, 3 repeat the copies of waves 0, 1 so that
+        // even waves: -LSE/scale of the 64 rows; odd waves: -D (waves 2, 3 repeat the copies of waves 0, 1 so that
         // every wave has the same number of loads in flight)
         const int which = wave & 1;
         char* stat_dst = stage + 2 * G::kTileBytes + which * 256;
@@ -240,14 +241,14 @@ __global__ __launch_bounds__(kThreads, 1) void bwd_dkv_kernel(BwdParams p) {
         if (row0 + BQ <= L) {
             qcopy.issue_full(stage, qb, p.q_stride, row0, wave);
             docopy.issue_full(stage + G::kTileBytes, dob, (int64_t)p.q_heads * D, row0, wave);
-            global_to_lds<4>((which == 0 ? p.lse2 : p.dsum) + stat0, (uint32_t)lane * 4u, stat_dst);
+            global_to_lds<4>((which == 0 ? p.nlse : p.negd) + stat0, (uint32_t)lane * 4u, stat_dst);
         } else {
-            // last tile of a head: rows past the end read a finite duplicate; their LSE reads +inf, so P = 0
+            // last tile of a head: rows past the end read a finite duplicate; their -LSE/scale reads -inf, so P = 0
             qcopy.issue_clamped(stage, qb, p.q_stride, row0, L, wave, lane);
             docopy.issue_clamped(stage + G::kTileBytes, dob, (int64_t)p.q_heads * D, row0, L, wave, lane);
             const int r = row0 + lane;
             const int64_t stat = stat0 + min(lane, L - 1 - row0);
-            const float* src = (which == 0) ? ((r < L) ? p.lse2 + stat : p.inf_pad) : p.dsum + stat;
+            const float* src = (which == 0) ? ((r < L) ? p.nlse + stat : p.ninf_pad) : p.negd + stat;
             global_to_lds<4>(src, stat_dst);
         }
     };
@@ -304,25 +305,25 @@ __global__ __launch_bounds__(kThreads, 1) void bwd_dkv_kernel(BwdParams p) {
     wait_tile_loads();
     __syncthreads();   // tiles 0, 1 and 2 are in LDS
 
-    // prologue: G1(0) computed directly; P = dS = 0 for the non-existent block -1
+    // prologue: G1(0) computed directly on top of block 0's statistics; P = dS = 0 for the non-existent block -1
     {
         const DkvAddr<D> a0 = at_stage(0);
 #pragma unroll
-        for (int i = 0; i < 16; ++i) { st.s_cur[i] = 0.f; st.dp_cur[i] = 0.f; }
+        for (int i4 = 0; i4 < 4; ++i4) {
+            const f32x4 a = *reinterpret_cast<const f32x4*>(lds + a0.st + i4 * 32);
+            const f32x4 b = *reinterpret_cast<const f32x4*>(lds + a0.st + i4 * 32 + 256);
+#pragma unroll
+            for (int j = 0; j < 4; ++j) { st.s[0][4 * i4 + j] = a[j]; st.dp[0][4 * i4 + j] = b[j]; }
+        }
 #pragma unroll
         for (int kk = 0; kk < KK; ++kk) {
-            st.s_cur = mfma(lds_read128(lds, a0.rm[kk]), st.kf[kk], st.s_cur);
-            st.dp_cur = mfma(lds_read128(lds, a0.rm[kk] + G::kTileBytes), st.vf[kk], st.dp_cur);
+            st.s[0] = mfma(lds_read128(lds, a0.rm[kk]), st.kf[kk], st.s[0]);
+            st.dp[0] = mfma(lds_read128(lds, a0.rm[kk] + G::kTileBytes), st.vf[kk], st.dp[0]);
         }
 #pragma unroll
         for (int kk = 0; kk < KK; ++kk) {
             st.qtf[kk] = lds_read128(lds, a0.rm[kk]);      // any finite operand: it meets P = dS = 0
             st.dotf[kk] = st.qtf[kk];
-        }
-#pragma unroll
-        for (int i4 = 0; i4 < 4; ++i4) {
-            st.lse4[i4] = *reinterpret_cast<const f32x4*>(lds + a0.st + i4 * 32);
-            st.ds4[i4] = *reinterpret_cast<const f32x4*>(lds + a0.st + i4 * 32 + 256);
         }
         union { u32x4 u; bf16x8 v; } z;
         z.u = u32x4{0u, 0u, 0u, 0u};
@@ -368,7 +369,7 @@ __global__ __launch_bounds__(kThreads, 1) void bwd_dkv_kernel(BwdParams p) {
         load.docopy = &docopy;
         load.q_row = p.q + (int64_t)(item.token_start + row0) * p.q_stride + (int64_t)hq * D;
         load.do_row = p.d_o + ((int64_t)(item.token_start + row0) * p.q_heads + hq) * D;
-        load.stat = ((wave & 1) == 0 ? p.lse2 : p.dsum) + (int64_t)hq * p.total_tokens + item.token_start + row0;
+        load.stat = ((wave & 1) == 0 ? p.nlse : p.negd) + (int64_t)hq * p.total_tokens + item.token_start + row0;
         load.stage = lds + stage3 * G::kStageBytes;
         load.stat_dst = load.stage + 2 * G::kTileBytes + (wave & 1) * 256;
         load.wave = wave;

@@ -1,7 +1,10 @@
 // Backward kernels.  Both passes recompute P = exp(S - LSE) from the forward's logsumexp.
 //
-//   D pass    : D[h, t] = sum_c dO[t,h,c] * O[t,h,c]; also LSE * log2(e) and a +inf constant that
-//               the dK/dV pass copies into LDS for rows past a sequence's end      (HBM stream)
+//   D pass    : -D[h, t] = -sum_c dO[t,h,c] * O[t,h,c]; also -LSE / scale (the logsumexp in units of raw
+//               scores) and a -inf constant that the dK/dV pass copies into LDS for rows past a
+//               sequence's end.  Both statistics are stored negated because the dK/dV pass feeds
+//               them to the MFMA as the initial accumulator: S - LSE/scale and dP - D come out of
+//               the matrix core                                                     (HBM stream)
 //   dQ pass   : one workgroup per (sequence, 128-row q tile, q head); loops over 64-key tiles of
 //               the causal prefix; per wave (32 queries along MFMA columns):
 //                 S^T = K Q^T, dP^T = V dO^T, dS^T = P^T (dP^T - D), dQ^T += K^T dS^T
@@ -36,10 +39,10 @@ __global__ __launch_bounds__(kThreads) void bwd_dsum_kernel(BwdParams p) {
     for (int off = LANES / 2; off > 0; off >>= 1) s += __shfl_xor(s, off, 64);
     if (row < n_rows && c == 0) {
         const int64_t t = row / p.q_heads, h = row % p.q_heads;
-        p.dsum[h * p.total_tokens + t] = s;
-        p.lse2[h * p.total_tokens + t] = p.lse[h * p.total_tokens + t] * kLog2e;
+        p.negd[h * p.total_tokens + t] = -s;
+        p.nlse[h * p.total_tokens + t] = -p.lse[h * p.total_tokens + t] / p.scale;
     }
-    if (blockIdx.x == 0 && threadIdx.x < 16) p.inf_pad[threadIdx.x] = INFINITY;
+    if (blockIdx.x == 0 && threadIdx.x < 16) p.ninf_pad[threadIdx.x] = -INFINITY;
 }
 
 // --------------------------------------------------------------------------------- dQ pass
@@ -88,9 +91,9 @@ __global__ __launch_bounds__(kThreads, 2) void bwd_dq_kernel(BwdParams p) {
         dof[kk] = b.v;
     }
     const int64_t stat = (int64_t)h * p.total_tokens + item.token_start + my_row;
-    const float lse2 = valid ? p.lse2[stat] : INFINITY;   // rows past the end get P = 0
-    const float dsum = valid ? p.dsum[stat] : 0.f;
     const float c = p.scale_log2;
+    const float nlse2 = valid ? p.nlse[stat] * c : -INFINITY;   // -LSE log2(e); rows past the end get P = 0
+    const float negd = valid ? p.negd[stat] : 0.f;
 
     f32x16 acc[DB];
 #pragma unroll
@@ -157,9 +160,9 @@ __global__ __launch_bounds__(kThreads, 2) void bwd_dq_kernel(BwdParams p) {
         for (int n = 0; n < kAheadT; ++n) q2[n] = frag2(n);
 #pragma unroll
         for (int i = 0; i < 16; ++i) {
-            float pr = fast_exp2(fmaf(sacc[i], c, -lse2));
+            float pr = fast_exp2(fmaf(sacc[i], c, nlse2));
             if (kMask && kb + acc_row(i, lane) > my_row) pr = 0.f;
-            sacc[i] = pr * (dp[i] - dsum);   // dS^T
+            sacc[i] = pr * (dp[i] + negd);   // dS^T
         }
         const bf16x8 dsf[2] = {frag_to_bf16(sacc, 0), frag_to_bf16(sacc, 1)};
         __builtin_amdgcn_sched_barrier(0);

@@ -285,9 +285,9 @@ hspmd_status hspmd_attn_varlen_bwd(const hspmd_attn_plan* plan, const void* q, c
     p.o = static_cast<const uint16_t*>(o);
     p.d_o = static_cast<const uint16_t*>(d_o);
     p.lse = lse;
-    p.dsum = static_cast<float*>(workspace);
-    p.lse2 = p.dsum + (size_t)plan->q_heads * (size_t)plan->total_tokens;
-    p.inf_pad = p.lse2 + (size_t)plan->q_heads * (size_t)plan->total_tokens;
+    p.negd = static_cast<float*>(workspace);
+    p.nlse = p.negd + (size_t)plan->q_heads * (size_t)plan->total_tokens;
+    p.ninf_pad = p.nlse + (size_t)plan->q_heads * (size_t)plan->total_tokens;
     p.dq = dq;
     p.dk = dk;
     p.dv = dv;

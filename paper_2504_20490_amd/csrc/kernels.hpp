@@ -27,9 +27,9 @@ struct BwdParams {
     const uint16_t* o;
     const uint16_t* d_o;
     const float* lse;
-    float* dsum;                   // workspace: D[Hq, T] = rowsum(dO * O)
-    float* lse2;                   // workspace: lse * log2(e), [Hq, T]
-    float* inf_pad;                // workspace: 16 floats holding +inf
+    float* negd;                   // workspace: -D[Hq, T], D = rowsum(dO * O)
+    float* nlse;                   // workspace: -lse / scale [Hq, T] (the logsumexp in units of raw scores)
+    float* ninf_pad;               // workspace: 16 floats holding -inf
     void* dq;
     void* dk;
     void* dv;
