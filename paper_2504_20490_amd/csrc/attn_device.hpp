@@ -62,11 +62,16 @@ __device__ __forceinline__ int tile_offset(int row, int col) {
 // compiler from moving LDS accesses across the issue point.  M0 (the LDS base of the copy) is written
 // inside the statement; nothing else in these kernels keeps a value in M0 (the compiler sets it up
 // immediately before each of its own uses), and it is a reserved register that cannot be named as a clobber.
+// LDS destinations are passed as 32-bit LDS byte addresses (lds_address of the kernel's shared array plus
+// an offset): a generic pointer would be converted, null check included, at every copy.
+__device__ __forceinline__ uint32_t lds_address(const void* shared_ptr) {
+    return (uint32_t)(uintptr_t)(__attribute__((address_space(3))) const char*)shared_ptr;
+}
+
 template <int SIZE>
-__device__ __forceinline__ void global_to_lds(const void* src, char* lds_dst) {
+__device__ __forceinline__ void global_to_lds(const void* src, uint32_t lds_dst) {
     static_assert(SIZE == 4 || SIZE == 16, "dword or dwordx4");
-    const uint32_t m0 = __builtin_amdgcn_readfirstlane(
-        (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char*)lds_dst);
+    const uint32_t m0 = __builtin_amdgcn_readfirstlane(lds_dst);
     if constexpr (SIZE == 16) {
         asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off"
                      :: "s"(m0), "v"(src) : "memory");
@@ -79,10 +84,9 @@ __device__ __forceinline__ void global_to_lds(const void* src, char* lds_dst) {
 // Same copy with the global address given as a wave-uniform base plus a per-lane unsigned byte offset
 // (the saddr form): the per-lane offsets of a tile are loop-invariant, so issuing a tile costs no VALU work.
 template <int SIZE>
-__device__ __forceinline__ void global_to_lds(const void* uniform_base, uint32_t lane_byte_offset, char* lds_dst) {
+__device__ __forceinline__ void global_to_lds(const void* uniform_base, uint32_t lane_byte_offset, uint32_t lds_dst) {
     static_assert(SIZE == 4 || SIZE == 16, "dword or dwordx4");
-    const uint32_t m0 = __builtin_amdgcn_readfirstlane(
-        (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char*)lds_dst);
+    const uint32_t m0 = __builtin_amdgcn_readfirstlane(lds_dst);
     // readfirstlane returns a signed int: widen each half as unsigned, or a low half with bit 31 set
     // would sign-extend over the high half and produce a wild address
     const uint64_t b = (uint64_t)(uintptr_t)uniform_base;
@@ -127,22 +131,22 @@ struct TileCopy {
     }
     // instruction I (of kPerWave) of a whole-tile copy; first_row points at the tile's first row, column 0
     template <int I>
-    __device__ __forceinline__ void issue_full_one(char* tile, const uint16_t* first_row, int wave) const {
+    __device__ __forceinline__ void issue_full_one(uint32_t tile, const uint16_t* first_row, int wave) const {
         static_assert(I >= 0 && I < kPerWave, "instruction index");
         global_to_lds<16>(first_row, off[I], tile + (I * 4 + wave) * 1024);
     }
     // the same with the index as a (compile-time constant after unrolling) argument
-    __device__ __forceinline__ void issue_full_one_at(int i, char* tile, const uint16_t* first_row, int wave) const {
+    __device__ __forceinline__ void issue_full_one_at(int i, uint32_t tile, const uint16_t* first_row, int wave) const {
         global_to_lds<16>(first_row, off[i], tile + (i * 4 + wave) * 1024);
     }
     // whole tile inside the sequence: rows row0 .. row0+ROWS-1 all exist.  slab points at row 0, column 0.
-    __device__ __forceinline__ void issue_full(char* tile, const uint16_t* slab, int64_t stride, int row0, int wave) const {
+    __device__ __forceinline__ void issue_full(uint32_t tile, const uint16_t* slab, int64_t stride, int row0, int wave) const {
         const uint16_t* base = slab + (int64_t)row0 * stride;
 #pragma unroll
         for (int i = 0; i < kPerWave; ++i) global_to_lds<16>(base, off[i], tile + (i * 4 + wave) * 1024);
     }
     // tile that runs past the end of the sequence: per-lane row clamp
-    __device__ __forceinline__ void issue_clamped(char* tile, const uint16_t* slab, int64_t stride, int row0, int seq_len,
+    __device__ __forceinline__ void issue_clamped(uint32_t tile, const uint16_t* slab, int64_t stride, int row0, int seq_len,
                                                   int wave, int lane) const {
 #pragma unroll
         for (int i = 0; i < kPerWave; ++i) {
@@ -153,7 +157,7 @@ struct TileCopy {
             global_to_lds<16>(slab + (int64_t)row * stride + c * 8, tile + blk * 1024);
         }
     }
-    __device__ __forceinline__ void issue(char* tile, const uint16_t* slab, int64_t stride, int row0, int seq_len,
+    __device__ __forceinline__ void issue(uint32_t tile, const uint16_t* slab, int64_t stride, int row0, int seq_len,
                                           int wave, int lane) const {
         if (row0 + ROWS <= seq_len) issue_full(tile, slab, stride, row0, wave);
         else issue_clamped(tile, slab, stride, row0, seq_len, wave, lane);

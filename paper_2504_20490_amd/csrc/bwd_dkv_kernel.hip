@@ -75,8 +75,8 @@ struct DkvTileLoad {
     const uint16_t* q_row;      // first row of the tile, this head, column 0
     const uint16_t* do_row;
     const float* stat;          // -LSE/scale (even waves) or -D (odd waves) of the tile's first row
-    char* stage;
-    char* stat_dst;
+    uint32_t stage;             // LDS byte addresses
+    uint32_t stat_dst;
     int wave, lane;
     template <int N>
     __device__ __forceinline__ void piece() const {
@@ -224,11 +224,12 @@ __global__ __launch_bounds__(kThreads, 1) void bwd_dkv_kernel(BwdParams p) {
     const int n_tiles = per_head * p.group;
 
     // global -> LDS copy of tile u (flattened over heads) into a stage, statistics included
+    const uint32_t lds0 = lds_address(lds);   // copy destinations are LDS byte addresses
     TileCopy<D, BQ> qcopy, docopy;
     qcopy.init(p.q_stride, wave, lane);
     docopy.init((int64_t)p.q_heads * D, wave, lane);
     auto load_tile = [&](int u, int stage_index) {
-        char* stage = lds + stage_index * G::kStageBytes;
+        const uint32_t stage = lds0 + stage_index * G::kStageBytes;
         const int hq = g * p.group + u / per_head;
         const int row0 = (n_qt - 1 - u % per_head) * BQ;   // q tiles are walked from the end of the sequence down
         const uint16_t* qb = p.q + (int64_t)item.token_start * p.q_stride + (int64_t)hq * D;
@@ -236,7 +237,7 @@ __global__ __launch_bounds__(kThreads, 1) void bwd_dkv_kernel(BwdParams p) {
         // even waves: -LSE/scale of the 64 rows; odd waves: -D (waves 2, 3 repeat the copies of waves 0, 1 so that
         // every wave has the same number of loads in flight)
         const int which = wave & 1;
-        char* stat_dst = stage + 2 * G::kTileBytes + which * 256;
+        const uint32_t stat_dst = stage + 2 * G::kTileBytes + which * 256;
         const int64_t stat0 = (int64_t)hq * p.total_tokens + item.token_start + row0;
         if (row0 + BQ <= L) {
             qcopy.issue_full(stage, qb, p.q_stride, row0, wave);
@@ -356,29 +357,24 @@ __global__ __launch_bounds__(kThreads, 1) void bwd_dkv_kernel(BwdParams p) {
     // The same for an unmasked tile that is at least three tiles above the head's last one: the tile loaded
     // meanwhile (u + 3) belongs to the same head and is a whole tile, so its copies need no case distinction
     // and are issued from inside the two iterations.
-    auto tile_step_spread = [&](int u, int qt, int hq) {
+    // `load` arrives pointing at the first rows of tile qt - 3 of the head and leaves pointing one tile lower.
+    auto tile_step_spread = [&](int u, int qt, DkvTileLoad<D>& load) {
         if (u > 0) {
             wait_tile_loads_except<kLoadsPerTile>();   // u + 2 < n_tiles here
             __syncthreads();
         }
         const int stage1 = stage + 1 == G::kStages ? 0 : stage + 1;
-        const int stage3 = (stage + 3) % G::kStages;
-        const int row0 = (qt - 3) * BQ;
-        DkvTileLoad<D> load;
-        load.qcopy = &qcopy;
-        load.docopy = &docopy;
-        load.q_row = p.q + (int64_t)(item.token_start + row0) * p.q_stride + (int64_t)hq * D;
-        load.do_row = p.d_o + ((int64_t)(item.token_start + row0) * p.q_heads + hq) * D;
-        load.stat = ((wave & 1) == 0 ? p.nlse : p.negd) + (int64_t)hq * p.total_tokens + item.token_start + row0;
-        load.stage = lds + stage3 * G::kStageBytes;
+        const int stage3 = stage == 0 ? G::kStages - 1 : stage - 1;   // (stage + 3) % kStages
+        load.stage = lds0 + stage3 * G::kStageBytes;
         load.stat_dst = load.stage + 2 * G::kTileBytes + (wave & 1) * 256;
-        load.wave = wave;
-        load.lane = lane;
         const DkvAddr<D> cur = at_stage(stage);
         const DkvAddr<D> next = at_stage(stage1);
         const int dkey0 = my_key - qt * BQ - 4 * hh;
         dkv_iteration<D, 0, false, true>(st, lds, cur, cur, dkey0, c, load);
         dkv_iteration<D, 1, false, true>(st, lds, next, cur, dkey0 - 32, c, load);
+        load.q_row -= (int64_t)BQ * p.q_stride;
+        load.do_row -= (int64_t)BQ * p.q_heads * D;
+        load.stat -= BQ;
         stage = stage1;
     };
     // Every head is walked from its LAST q tile down to the diagonal.  All key tiles of one (sequence, kv head)
@@ -388,7 +384,19 @@ __global__ __launch_bounds__(kThreads, 1) void bwd_dkv_kernel(BwdParams p) {
     const int n_masked = min(2, per_head);
     for (int h = 0, u = 0; h < p.group; ++h) {
         int j = per_head - 1;
-        for (; j >= 3; --j, ++u) tile_step_spread(u, first_qt + j, g * p.group + h);
+        if (j >= 3) {
+            const int hq = g * p.group + h;
+            const int64_t row = item.token_start + (int64_t)(first_qt + j - 3) * BQ;   // first row of the tile loaded first
+            DkvTileLoad<D> load;
+            load.qcopy = &qcopy;
+            load.docopy = &docopy;
+            load.q_row = p.q + row * p.q_stride + (int64_t)hq * D;
+            load.do_row = p.d_o + (row * p.q_heads + hq) * D;
+            load.stat = ((wave & 1) == 0 ? p.nlse : p.negd) + (int64_t)hq * p.total_tokens + row;
+            load.wave = wave;
+            load.lane = lane;
+            for (; j >= 3; --j, ++u) tile_step_spread(u, first_qt + j, load);
+        }
         for (; j >= n_masked; --j, ++u) tile_step(u, first_qt + j, std::false_type{});
         for (; j >= 0; --j, ++u) tile_step(u, first_qt + j, std::true_type{});
     }

@@ -74,8 +74,9 @@ __global__ __launch_bounds__(kThreads, 2) void bwd_dq_kernel(BwdParams p) {
 
     TileCopy<D, BK> kvcopy;   // K and V share stride and geometry
     kvcopy.init(p.kv_stride, wave, lane);
-    kvcopy.issue(lds, kbase, p.kv_stride, 0, L, wave, lane);
-    kvcopy.issue(lds + kTileBytes, vbase, p.kv_stride, 0, L, wave, lane);
+    const uint32_t lds0 = lds_address(lds);   // copy destinations are LDS byte addresses
+    kvcopy.issue(lds0, kbase, p.kv_stride, 0, L, wave, lane);
+    kvcopy.issue(lds0 + kTileBytes, vbase, p.kv_stride, 0, L, wave, lane);
 
     bf16x8 qf[KK], dof[KK];
 #pragma unroll
@@ -183,7 +184,7 @@ __global__ __launch_bounds__(kThreads, 2) void bwd_dq_kernel(BwdParams p) {
         const char* ktile = lds + (kt & 1) * (2 * kTileBytes);
         const char* vtile = ktile + kTileBytes;
         if (kt + 1 < n_tiles) {
-            char* next = lds + ((kt + 1) & 1) * (2 * kTileBytes);
+            const uint32_t next = lds0 + ((kt + 1) & 1) * (2 * kTileBytes);
             kvcopy.issue(next, kbase, p.kv_stride, (kt + 1) * BK, L, wave, lane);
             kvcopy.issue(next + kTileBytes, vbase, p.kv_stride, (kt + 1) * BK, L, wave, lane);
         }
@@ -201,7 +202,7 @@ __global__ __launch_bounds__(kThreads, 2) void bwd_dq_kernel(BwdParams p) {
         __syncthreads();
         const char* ktile = lds + (kt & 1) * (2 * kTileBytes);
         const char* vtile = ktile + kTileBytes;
-        char* next = lds + ((kt + 1) & 1) * (2 * kTileBytes);
+        const uint32_t next = lds0 + ((kt + 1) & 1) * (2 * kTileBytes);
         const uint16_t* k_row = kbase + (int64_t)(kt + 1) * BK * p.kv_stride;
         const uint16_t* v_row = vbase + (int64_t)(kt + 1) * BK * p.kv_stride;
         auto piece = [&](int jb, int i) {

@@ -44,8 +44,8 @@ struct FwdTileLoad {
     const Copy* copy;
     const uint16_t* k_row;   // first row of the K tile, this kv head, column 0
     const uint16_t* v_row;
-    char* k_dst;
-    char* v_dst;
+    uint32_t k_dst;          // LDS byte addresses
+    uint32_t v_dst;
     int wave;
     __device__ __forceinline__ void k_piece(int i) const {
 #pragma unroll
@@ -202,6 +202,7 @@ __global__ __launch_bounds__(kThreads, 2) void fwd_kernel(FwdParams p) {
     __shared__ __attribute__((aligned(1024))) char lds[4 * kTileBytes];
     char* const kbuf0 = lds;
     char* const vbuf0 = lds + 2 * kTileBytes;
+    const uint32_t kdst0 = lds_address(lds), vdst0 = kdst0 + 2 * kTileBytes;   // the same buffers as copy destinations
 
     const hspmd_work_item item = p.items[blockIdx.x];
     if (item.tile < 0) return;
@@ -224,9 +225,9 @@ __global__ __launch_bounds__(kThreads, 2) void fwd_kernel(FwdParams p) {
     TileCopy<D, BK> kvcopy;   // K and V share stride and geometry
     kvcopy.init(p.kv_stride, wave, lane);
     // K(0), V(0), K(1)
-    kvcopy.issue(kbuf0, kbase, p.kv_stride, 0, L, wave, lane);
-    kvcopy.issue(vbuf0, vbase, p.kv_stride, 0, L, wave, lane);
-    if (n_tiles > 1) kvcopy.issue(kbuf0 + kTileBytes, kbase, p.kv_stride, BK, L, wave, lane);
+    kvcopy.issue(kdst0, kbase, p.kv_stride, 0, L, wave, lane);
+    kvcopy.issue(vdst0, vbase, p.kv_stride, 0, L, wave, lane);
+    if (n_tiles > 1) kvcopy.issue(kdst0 + kTileBytes, kbase, p.kv_stride, BK, L, wave, lane);
 
     FwdState<D> st;
 #pragma unroll
@@ -276,8 +277,8 @@ __global__ __launch_bounds__(kThreads, 2) void fwd_kernel(FwdParams p) {
             wait_tile_loads();
             __syncthreads();   // K(kt+1) and V(kt) have landed; every wave is done with iteration kt-1
         }
-        if (kt + 2 < n_tiles) kvcopy.issue(kbuf0 + (kt & 1) * kTileBytes, kbase, p.kv_stride, (kt + 2) * BK, L, wave, lane);
-        if (kt + 1 < n_tiles) kvcopy.issue(vbuf0 + ((kt + 1) & 1) * kTileBytes, vbase, p.kv_stride, (kt + 1) * BK, L, wave, lane);
+        if (kt + 2 < n_tiles) kvcopy.issue(kdst0 + (kt & 1) * kTileBytes, kbase, p.kv_stride, (kt + 2) * BK, L, wave, lane);
+        if (kt + 1 < n_tiles) kvcopy.issue(vdst0 + ((kt + 1) & 1) * kTileBytes, vbase, p.kv_stride, (kt + 1) * BK, L, wave, lane);
         fwd_iteration<D, decltype(masked)::value, decltype(last)::value, false>(
             st, kbuf0 + ((kt + 1) & 1) * kTileBytes, vbuf0 + (kt & 1) * kTileBytes, c, my_row - kt * BK - 4 * hh, no_load);
     };
@@ -292,8 +293,8 @@ __global__ __launch_bounds__(kThreads, 2) void fwd_kernel(FwdParams p) {
         load.copy = &kvcopy;
         load.k_row = kbase + (int64_t)(kt + 2) * BK * p.kv_stride;
         load.v_row = vbase + (int64_t)(kt + 1) * BK * p.kv_stride;
-        load.k_dst = kbuf0 + (kt & 1) * kTileBytes;
-        load.v_dst = vbuf0 + ((kt + 1) & 1) * kTileBytes;
+        load.k_dst = kdst0 + (kt & 1) * kTileBytes;
+        load.v_dst = vdst0 + ((kt + 1) & 1) * kTileBytes;
         load.wave = wave;
         fwd_iteration<D, false, false, true>(st, kbuf0 + ((kt + 1) & 1) * kTileBytes, vbuf0 + (kt & 1) * kTileBytes, c,
                                              my_row - kt * BK - 4 * hh, load);
