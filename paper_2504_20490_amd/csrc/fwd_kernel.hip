@@ -126,7 +126,7 @@ __device__ __forceinline__ void fwd_iteration(FwdState<D>& st, const char* kbuf,
     if constexpr (!LAST) {
         constexpr int kAheadK = 4;
         constexpr int NM = 2 * KK;               // MFMAs of the phase
-        constexpr int every = NM / NP;           // one copy instruction per `every` MFMAs
+        static_assert(2 * NP <= NM, "one copy instruction per MFMA step");
         auto k_frag = [&](int n) {
             return *reinterpret_cast<const bf16x8*>(kbuf + st.rm[n % KK] + (n / KK) * 32 * D * 2);
         };
@@ -147,7 +147,9 @@ __device__ __forceinline__ void fwd_iteration(FwdState<D>& st, const char* kbuf,
                 softmax_pair(2 * n + 1);
             }
             if constexpr (SPREAD) {
-                if (n % every == every - 1) load.k_piece(n / every);
+                // all copies early in the iteration: both tiles are needed right after the next barrier
+                if (n < NP) load.k_piece(n);
+                else if (n < 2 * NP) load.v_piece(n - NP);
             }
             __builtin_amdgcn_sched_barrier(0);
         }
@@ -162,7 +164,6 @@ __device__ __forceinline__ void fwd_iteration(FwdState<D>& st, const char* kbuf,
     {
         constexpr int kAheadV = 3;
         constexpr int NM = 4 * DB;
-        constexpr int every = NM / NP;
         auto v_frag = [&](int n) {
             const int t = n / DB, db = n % DB;
             const int off = t * 16 * D * 2;
@@ -178,9 +179,6 @@ __device__ __forceinline__ void fwd_iteration(FwdState<D>& st, const char* kbuf,
         for (int n = 0; n < NM; ++n) {
             if (n + kAheadV < NM) vq[(n + kAheadV) % (kAheadV + 1)] = v_frag(n + kAheadV);
             st.acc[n % DB] = mfma(vq[n % (kAheadV + 1)], pw[n / DB].v, st.acc[n % DB]);
-            if constexpr (SPREAD) {
-                if (n % every == every - 1) load.v_piece(n / every);
-            }
             __builtin_amdgcn_sched_barrier(0);
         }
     }
