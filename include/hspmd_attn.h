@@ -85,6 +85,22 @@ typedef struct {
     int32_t head;         /* local q head (FWD, DQ) or local kv head (DKV)               */
 } hspmd_work_item;
 
+/*
+ * One unit of work of the block variant (one step of context-parallel attention, see
+ * hspmd_attn_block_plan_create): the sequence's query chunk and key/value chunk are separate
+ * token ranges and the causal mask is shifted by the difference of their positions.
+ */
+typedef struct {
+    int32_t q_start;   /* first token of the sequence's query chunk in the packed q / o / d_o / dq tensors  */
+    int32_t q_len;     /* rows in that chunk                                                               */
+    int32_t k_start;   /* first token of the sequence's key/value chunk in the packed k / v / dk / dv tensors */
+    int32_t k_len;     /* keys in that chunk                                                               */
+    int32_t offset;    /* q_pos - k_pos: key j of the chunk is visible to row r of the chunk iff j <= r + offset */
+    int32_t tile;      /* q tile index (FWD, DQ) or k tile index (DKV) within the chunk; < 0: padding slot  */
+    int32_t head;      /* local q head (FWD, DQ) or local kv head (DKV)                                     */
+    int32_t reserved;  /* 0 */
+} hspmd_block_item;
+
 /* Never NULL.  Thread-local. */
 const char* hspmd_last_error(void);
 
@@ -187,6 +203,78 @@ hspmd_status hspmd_attn_varlen_bwd(const hspmd_attn_plan* plan, const void* q, c
                                    int64_t q_token_stride, int64_t kv_token_stride, float softmax_scale,
                                    void* dq, void* dk, void* dv, hspmd_grad_dtype grad_dtype,
                                    void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * ---- Block variant: one step of context-parallel attention on one device ----
+ * The paper shards long sequences over devices (context parallelism) with ring-based send-receive
+ * inside attention, wrapped in its fused ParallelAttn operator (Section 2.1, data sharding; system
+ * overview, footnote on ParallelAttn).  What one device computes per ring step is attention of its
+ * own chunk of query rows against one chunk of keys/values (its own or a received one); the steps'
+ * partial results are merged.  Positions are positions inside the whole sequence:
+ *   sequence i: rows at q_pos[i] + r (r < q_len[i]), keys at k_pos[i] + j (j < k_len[i]);
+ *   key j is visible to row r iff k_pos[i] + j <= q_pos[i] + r.
+ * Chunks may be empty, lie wholly in the past (every key visible) or wholly in the future (nothing
+ * visible: O = 0, LSE = -inf, zero gradients).  The sends and receives themselves are not part of
+ * this library.
+ *
+ * hspmd_attn_block_schedule / hspmd_attn_block_plan_create mirror hspmd_attn_schedule /
+ * hspmd_attn_plan_create:
+ *   cu_q, cu_k     host, [num_seqs + 1]: packed offsets of the query chunks / key chunks
+ *   q_pos, k_pos   host, [num_seqs], >= 0: position of each chunk's first row / key in its sequence
+ * A plan made here works only with the hspmd_attn_block_* calls (and the other plans only with
+ * hspmd_attn_varlen_*); hspmd_attn_plan_total_tokens counts its query tokens,
+ * hspmd_attn_plan_total_kv_tokens its key tokens, and hspmd_attn_bwd_workspace_bytes applies as is.
+ */
+hspmd_status hspmd_attn_block_schedule(hspmd_list_kind kind, const int32_t* cu_q, const int32_t* cu_k,
+                                       const int32_t* q_pos, const int32_t* k_pos, int32_t num_seqs,
+                                       int32_t local_q_heads, int32_t local_kv_heads, int32_t num_queues,
+                                       hspmd_block_item* items, int64_t capacity, int64_t* count);
+hspmd_status hspmd_attn_block_plan_create(const int32_t* cu_q_host, const int32_t* cu_k_host, const int32_t* q_pos_host,
+                                          const int32_t* k_pos_host, int32_t num_seqs, int32_t local_q_heads,
+                                          int32_t local_kv_heads, int32_t head_dim, void* stream, hspmd_attn_plan** out);
+int64_t hspmd_attn_plan_total_kv_tokens(const hspmd_attn_plan* plan);   /* -1 on NULL */
+
+/*
+ * Forward of one block.  q bf16 [Tq, Hq, d], k / v bf16 [Tk, Hkv, d] (strides as in hspmd_attn_varlen_fwd).
+ *   o_partial    fp32 [Tq, Hq, d], contiguous, written: softmax over the block's visible keys only
+ *   lse_partial  fp32 [Hq, Tq], written: logsumexp over the block's visible keys, -inf where none is visible
+ * Partial results stay in fp32 until the last merge.
+ */
+hspmd_status hspmd_attn_block_fwd(const hspmd_attn_plan* plan, const void* q, const void* k, const void* v,
+                                  int64_t q_token_stride, int64_t kv_token_stride, float softmax_scale,
+                                  float* o_partial, float* lse_partial, void* stream);
+
+/*
+ * Merge of two partial results of the same rows over disjoint key sets:
+ *   LSE = ln(exp(LSE_a) + exp(LSE_b)),  O = exp(LSE_a - LSE) O_a + exp(LSE_b - LSE) O_b;
+ * a partial result with LSE = -inf is the neutral element.  All tensors device memory, O fp32
+ * [total_tokens, local_q_heads, head_dim], LSE fp32 [local_q_heads, total_tokens].  o_out / lse_out may be
+ * the same buffers as o_a / lse_a (in-place accumulation), not o_b / lse_b.  o_out_bf16 (may be NULL)
+ * also receives the merged O rounded to bf16: pass it on the last merge to get the tensor the backward
+ * and the next layer consume.
+ */
+hspmd_status hspmd_attn_merge(int64_t total_tokens, int32_t local_q_heads, int32_t head_dim, const float* o_a,
+                              const float* lse_a, const float* o_b, const float* lse_b, float* o_out, float* lse_out,
+                              void* o_out_bf16, void* stream);
+
+/*
+ * Backward of one block.  o (bf16) and lse are the MERGED results of the whole rows (all blocks), d_o
+ * the gradient of that output; P is recomputed as exp(S - lse), so every block can be processed
+ * independently of the others.
+ *   dq   fp32 [Tq, Hq, d]: this block's share of dQ; dq_accumulate != 0 adds it to the buffer's
+ *        contents (the caller zeroes or overwrites on the first block), 0 overwrites
+ *   dk, dv  fp32 [Tk, Hkv, d], overwritten: gradients of this block's keys / values from this block's
+ *        rows (in a ring they travel on with the chunk and are summed by the caller)
+ *   reuse_statistics != 0: the D pass is skipped and `workspace` must still hold what an earlier
+ *        call with the same o, lse, d_o, scale and a plan of the same query chunks left there
+ *        (o and lse may then be NULL)
+ * Gradients are fp32 only: partial sums are not rounded to bf16.
+ */
+hspmd_status hspmd_attn_block_bwd(const hspmd_attn_plan* plan, const void* q, const void* k, const void* v,
+                                  const void* o, const float* lse, const void* d_o,
+                                  int64_t q_token_stride, int64_t kv_token_stride, float softmax_scale,
+                                  float* dq, int32_t dq_accumulate, float* dk, float* dv, int32_t reuse_statistics,
+                                  void* workspace, size_t workspace_bytes, void* stream);
 
 /*
  * Per-kernel timing for measurement (the evidence the kernels are tuned against; not part of

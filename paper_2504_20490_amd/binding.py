@@ -28,6 +28,12 @@ class WorkItem(ctypes.Structure):
                 ("tile", ctypes.c_int32), ("head", ctypes.c_int32)]
 
 
+class BlockItem(ctypes.Structure):
+    _fields_ = [("q_start", ctypes.c_int32), ("q_len", ctypes.c_int32), ("k_start", ctypes.c_int32),
+                ("k_len", ctypes.c_int32), ("offset", ctypes.c_int32), ("tile", ctypes.c_int32),
+                ("head", ctypes.c_int32), ("reserved", ctypes.c_int32)]
+
+
 _lib = None
 
 
@@ -83,6 +89,22 @@ def load_library():
                                           ctypes.c_float, vp, vp, vp, ctypes.c_int, vp, ctypes.c_size_t, vp]
     lib.hspmd_profile_enable.restype = ctypes.c_int
     lib.hspmd_profile_enable.argtypes = [ctypes.c_int32]
+    lib.hspmd_attn_block_schedule.restype = ctypes.c_int
+    lib.hspmd_attn_block_schedule.argtypes = [ctypes.c_int, i32p, i32p, i32p, i32p, ctypes.c_int32, ctypes.c_int32,
+                                              ctypes.c_int32, ctypes.c_int32, ctypes.POINTER(BlockItem),
+                                              ctypes.c_int64, i64p]
+    lib.hspmd_attn_block_plan_create.restype = ctypes.c_int
+    lib.hspmd_attn_block_plan_create.argtypes = [i32p, i32p, i32p, i32p, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32,
+                                                 ctypes.c_int32, vp, ctypes.POINTER(vp)]
+    lib.hspmd_attn_plan_total_kv_tokens.restype = ctypes.c_int64
+    lib.hspmd_attn_plan_total_kv_tokens.argtypes = [vp]
+    lib.hspmd_attn_block_fwd.restype = ctypes.c_int
+    lib.hspmd_attn_block_fwd.argtypes = [vp, vp, vp, vp, ctypes.c_int64, ctypes.c_int64, ctypes.c_float, vp, vp, vp]
+    lib.hspmd_attn_merge.restype = ctypes.c_int
+    lib.hspmd_attn_merge.argtypes = [ctypes.c_int64, ctypes.c_int32, ctypes.c_int32, vp, vp, vp, vp, vp, vp, vp, vp]
+    lib.hspmd_attn_block_bwd.restype = ctypes.c_int
+    lib.hspmd_attn_block_bwd.argtypes = [vp, vp, vp, vp, vp, vp, vp, ctypes.c_int64, ctypes.c_int64, ctypes.c_float,
+                                         vp, ctypes.c_int32, vp, vp, ctypes.c_int32, vp, ctypes.c_size_t, vp]
     lib.hspmd_probe_scratch_bytes.restype = ctypes.c_size_t
     lib.hspmd_probe_scratch_bytes.argtypes = []
     lib.hspmd_probe_mfma_tflops.restype = ctypes.c_int
@@ -244,3 +266,75 @@ def probe_mfma_tflops(scratch, mfma_per_wave: int = 1 << 18, stream=None) -> flo
                                                   scratch.numel() * scratch.element_size(), _stream_handle(stream),
                                                   ctypes.byref(out)))
     return float(out.value)
+
+
+# ---------------------------------------------------------------------------------- block variant
+def block_schedule(kind: int, cu_q: Sequence[int], cu_k: Sequence[int], q_pos: Sequence[int], k_pos: Sequence[int],
+                   q_heads: int, kv_heads: int, num_queues: int = 8) -> np.ndarray:
+    """Host-only: the launch-ordered block work list as an int32 array [slots, 8]
+    (q_start, q_len, k_start, k_len, offset, tile, head, 0); padding slots have tile == -1."""
+    lib = load_library()
+    cq, ck, qp, kp = _i32(cu_q), _i32(cu_k), _i32(q_pos), _i32(k_pos)
+    if not (len(cq) == len(ck) == len(qp) + 1 == len(kp) + 1):
+        raise HspmdError(1, "per-sequence arrays differ in length")
+    n = ctypes.c_int64(0)
+    args = (kind, _ptr32(cq), _ptr32(ck), _ptr32(qp), _ptr32(kp), len(qp), q_heads, kv_heads, num_queues)
+    _check(lib.hspmd_attn_block_schedule(*args, None, 0, ctypes.byref(n)))
+    out = np.zeros((n.value, 8), dtype=np.int32)
+    if n.value:
+        _check(lib.hspmd_attn_block_schedule(*args, out.ctypes.data_as(ctypes.POINTER(BlockItem)), n.value, ctypes.byref(n)))
+    return out
+
+
+class BlockPlan(Plan):
+    """Work lists of one step of context-parallel attention: per sequence a query chunk and a key chunk."""
+
+    def __init__(self, cu_q: Sequence[int], cu_k: Sequence[int], q_pos: Sequence[int], k_pos: Sequence[int],
+                 q_heads: int, kv_heads: int, head_dim: int, stream: int = 0):
+        lib = load_library()
+        cq, ck, qp, kp = _i32(cu_q), _i32(cu_k), _i32(q_pos), _i32(k_pos)
+        if not (len(cq) == len(ck) == len(qp) + 1 == len(kp) + 1):
+            raise HspmdError(1, "per-sequence arrays differ in length")
+        handle = ctypes.c_void_p(None)
+        _check(lib.hspmd_attn_block_plan_create(_ptr32(cq), _ptr32(ck), _ptr32(qp), _ptr32(kp), len(qp), q_heads,
+                                                kv_heads, head_dim, ctypes.c_void_p(stream), ctypes.byref(handle)))
+        self._h = handle
+        self.q_heads, self.kv_heads, self.head_dim = q_heads, kv_heads, head_dim
+        self.total_tokens = int(lib.hspmd_attn_plan_total_tokens(handle))
+        self.total_kv_tokens = int(lib.hspmd_attn_plan_total_kv_tokens(handle))
+
+
+def _token_stride(t, heads: int, head_dim: int) -> int:
+    return t.stride(0) if t.dim() == 3 and t.shape[0] > 1 else heads * head_dim
+
+
+def _opt_ptr(t) -> ctypes.c_void_p:
+    return ctypes.c_void_p(None) if t is None else _dev_ptr(t)
+
+
+def attn_block_fwd(plan: BlockPlan, q, k, v, o_partial, lse_partial, softmax_scale: float = 0.0, stream=None) -> None:
+    """q [Tq,Hq,d], k/v [Tk,Hkv,d] bf16; o_partial fp32 [Tq,Hq,d] and lse_partial fp32 [Hq,Tq] are written."""
+    _check(load_library().hspmd_attn_block_fwd(plan.handle, _dev_ptr(q), _dev_ptr(k), _dev_ptr(v),
+                                               _token_stride(q, plan.q_heads, plan.head_dim),
+                                               _token_stride(k, plan.kv_heads, plan.head_dim), float(softmax_scale),
+                                               _dev_ptr(o_partial), _dev_ptr(lse_partial), _stream_handle(stream)))
+
+
+def attn_merge(o_a, lse_a, o_b, lse_b, o_out, lse_out, o_out_bf16=None, stream=None) -> None:
+    """(o_out, lse_out) = (o_a, lse_a) merged with (o_b, lse_b); the output may be the `a` buffers."""
+    T, hq, d = o_a.shape
+    _check(load_library().hspmd_attn_merge(T, hq, d, _dev_ptr(o_a), _dev_ptr(lse_a), _dev_ptr(o_b), _dev_ptr(lse_b),
+                                           _dev_ptr(o_out), _dev_ptr(lse_out), _opt_ptr(o_out_bf16),
+                                           _stream_handle(stream)))
+
+
+def attn_block_bwd(plan: BlockPlan, q, k, v, o, lse, d_o, dq, dk, dv, workspace, softmax_scale: float = 0.0,
+                   dq_accumulate: bool = False, reuse_statistics: bool = False, stream=None) -> None:
+    """o (bf16) / lse: merged results of the whole rows; dq fp32 (overwritten or accumulated), dk/dv fp32 written."""
+    _check(load_library().hspmd_attn_block_bwd(plan.handle, _dev_ptr(q), _dev_ptr(k), _dev_ptr(v), _opt_ptr(o),
+                                               _opt_ptr(lse), _dev_ptr(d_o),
+                                               _token_stride(q, plan.q_heads, plan.head_dim),
+                                               _token_stride(k, plan.kv_heads, plan.head_dim), float(softmax_scale),
+                                               _dev_ptr(dq), 1 if dq_accumulate else 0, _dev_ptr(dk), _dev_ptr(dv),
+                                               1 if reuse_statistics else 0, _dev_ptr(workspace),
+                                               workspace.numel() * workspace.element_size(), _stream_handle(stream)))

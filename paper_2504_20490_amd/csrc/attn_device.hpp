@@ -14,6 +14,8 @@
 //     A operand of that product is fetched with the matching permutation.
 #pragma once
 #include <hip/hip_runtime.h>
+
+#include "../../include/hspmd_attn.h"
 #include <stdint.h>
 
 namespace hspmd {
@@ -260,6 +262,23 @@ struct InterleaveHint {
         }
     }
 };
+
+// Geometry of one work item.  The packed self-attention lists carry (token_start, seq_len); the block variant
+// carries separate query and key chunks and the shift of the causal mask.  With BLOCK = false the chunk fields
+// are copies and offset is the constant 0, so the general index arithmetic folds back to the plain one.
+struct ItemGeom {
+    int q_start, q_len, k_start, k_len, offset, tile, head;
+};
+template <bool BLOCK>
+__device__ __forceinline__ ItemGeom load_item(const hspmd_work_item* items, const hspmd_block_item* block_items, int idx) {
+    if constexpr (BLOCK) {
+        const hspmd_block_item it = block_items[idx];
+        return ItemGeom{it.q_start, it.q_len, it.k_start, it.k_len, it.offset, it.tile, it.head};
+    } else {
+        const hspmd_work_item it = items[idx];
+        return ItemGeom{it.token_start, it.seq_len, it.token_start, it.seq_len, 0, it.tile, it.head};
+    }
+}
 
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 

@@ -195,33 +195,46 @@ __device__ __forceinline__ void dkv_iteration(DkvState<D>& st, const char* lds, 
 
 }  // namespace
 
-template <int D>
+template <int D, bool BLOCK>
 __global__ __launch_bounds__(kThreads, 1) void bwd_dkv_kernel(BwdParams p) {
     using G = DkvGeom<D>;
     constexpr int BKV = kDkvKTile, BQ = kDkvQTile;
     constexpr int KK = G::KK, DB = G::DB;
     __shared__ __attribute__((aligned(1024))) char lds[G::kStages * G::kStageBytes];
 
-    const hspmd_work_item item = p.items[blockIdx.x];
+    const ItemGeom item = load_item<BLOCK>(p.items, p.block_items, blockIdx.x);
     if (item.tile < 0) return;
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int L = item.seq_len, g = item.head;
+    const int L = item.q_len, Lk = item.k_len, shift = item.offset, g = item.head;   // L: rows of the chunk
     const int key0 = item.tile * BKV;
     const int wave_key0 = key0 + wave * 32;
     const int my_key = wave_key0 + (lane & 31);
     const int hh = lane >> 5;
-    const bool valid = my_key < L;
+    const bool valid = my_key < Lk;
 
-    const uint16_t* kbase = p.k + (int64_t)item.token_start * p.kv_stride + (int64_t)g * D;
-    const uint16_t* vbase = p.v + (int64_t)item.token_start * p.kv_stride + (int64_t)g * D;
+    const uint16_t* kbase = p.k + (int64_t)item.k_start * p.kv_stride + (int64_t)g * D;
+    const uint16_t* vbase = p.v + (int64_t)item.k_start * p.kv_stride + (int64_t)g * D;
 
     constexpr int kLoadsPerTile = 2 * (BQ * D * 2 / 1024) / 4 + 1;   // per wave: Q and dO chunks + one statistics copy
-    // tiles: for each head of the group, q tiles first_qt .. n_qt-1 (rows at or below the diagonal)
-    const int first_qt = key0 / BQ;
+    // tiles: for each head of the group, q tiles first_qt .. n_qt-1 (rows at or below the diagonal: row r sees
+    // key j iff j <= r + shift, so the tile's first key is seen by the rows from key0 - shift on)
+    const int first_qt = max(0, key0 - shift) / BQ;
     const int n_qt = (L + BQ - 1) / BQ;
-    const int per_head = n_qt - first_qt;
+    const int per_head = max(0, n_qt - first_qt);
     const int n_tiles = per_head * p.group;
+    if (BLOCK && per_head == 0) {
+        // no row of the chunk sees these keys
+        if (valid) {
+            const int64_t row_elem = ((int64_t)(item.k_start + my_key) * p.kv_heads + g) * D;
+#pragma unroll
+            for (int c4 = 0; c4 < D / 8; ++c4) {
+                store_grad4(p.dk, row_elem + hh * (D / 2) + c4 * 4, p.grad_f32 != 0, 0.f, 0.f, 0.f, 0.f);
+                store_grad4(p.dv, row_elem + hh * (D / 2) + c4 * 4, p.grad_f32 != 0, 0.f, 0.f, 0.f, 0.f);
+            }
+        }
+        return;
+    }
 
     // global -> LDS copy of tile u (flattened over heads) into a stage, statistics included
     const uint32_t lds0 = lds_address(lds);   // copy destinations are LDS byte addresses
@@ -232,13 +245,13 @@ __global__ __launch_bounds__(kThreads, 1) void bwd_dkv_kernel(BwdParams p) {
         const uint32_t stage = lds0 + stage_index * G::kStageBytes;
         const int hq = g * p.group + u / per_head;
         const int row0 = (n_qt - 1 - u % per_head) * BQ;   // q tiles are walked from the end of the sequence down
-        const uint16_t* qb = p.q + (int64_t)item.token_start * p.q_stride + (int64_t)hq * D;
-        const uint16_t* dob = p.d_o + ((int64_t)item.token_start * p.q_heads + hq) * D;
+        const uint16_t* qb = p.q + (int64_t)item.q_start * p.q_stride + (int64_t)hq * D;
+        const uint16_t* dob = p.d_o + ((int64_t)item.q_start * p.q_heads + hq) * D;
         // even waves: -LSE/scale of the 64 rows; odd waves: -D (waves 2, 3 repeat the copies of waves 0, 1 so that
         // every wave has the same number of loads in flight)
         const int which = wave & 1;
         const uint32_t stat_dst = stage + 2 * G::kTileBytes + which * 256;
-        const int64_t stat0 = (int64_t)hq * p.total_tokens + item.token_start + row0;
+        const int64_t stat0 = (int64_t)hq * p.total_tokens + item.q_start + row0;
         if (row0 + BQ <= L) {
             qcopy.issue_full(stage, qb, p.q_stride, row0, wave);
             docopy.issue_full(stage + G::kTileBytes, dob, (int64_t)p.q_heads * D, row0, wave);
@@ -349,7 +362,7 @@ __global__ __launch_bounds__(kThreads, 1) void bwd_dkv_kernel(BwdParams p) {
         const DkvAddr<D> cur = at_stage(stage);
         // block 2u+2 lives in the next tile; the last tile has none: it re-reads itself (result unused)
         const DkvAddr<D> next = at_stage(u + 1 < n_tiles ? stage1 : stage);
-        const int dkey0 = my_key - qt * BQ - 4 * hh;
+        const int dkey0 = my_key - shift - qt * BQ - 4 * hh;
         dkv_iteration<D, 0, kMask, false>(st, lds, cur, cur, dkey0, c, no_load);
         dkv_iteration<D, 1, kMask, false>(st, lds, next, cur, dkey0 - 32, c, no_load);
         stage = stage1;
@@ -369,7 +382,7 @@ __global__ __launch_bounds__(kThreads, 1) void bwd_dkv_kernel(BwdParams p) {
         load.stat_dst = load.stage + 2 * G::kTileBytes + (wave & 1) * 256;
         const DkvAddr<D> cur = at_stage(stage);
         const DkvAddr<D> next = at_stage(stage1);
-        const int dkey0 = my_key - qt * BQ - 4 * hh;
+        const int dkey0 = my_key - shift - qt * BQ - 4 * hh;
         dkv_iteration<D, 0, false, true>(st, lds, cur, cur, dkey0, c, load);
         dkv_iteration<D, 1, false, true>(st, lds, next, cur, dkey0 - 32, c, load);
         load.q_row -= (int64_t)BQ * p.q_stride;
@@ -381,12 +394,16 @@ __global__ __launch_bounds__(kThreads, 1) void bwd_dkv_kernel(BwdParams p) {
     // run on one XCD at about the same time; walking down from the common end keeps them on the same Q / dO
     // tiles at the same time (one L2 fill serves them all), whereas walking up from each item's own diagonal
     // would spread them over the whole sequence.
-    const int n_masked = min(2, per_head);
+    // q tiles that hold some (row, key) pair above the shifted diagonal for the keys of this workgroup:
+    // qt BQ + shift < key0 + BKV - 1; the two nearest the diagonal when there is no shift
+    const int n_masked = BLOCK ? (key0 + BKV - 2 - shift < 0 ? 0 : max(0, min(per_head, (key0 + BKV - 2 - shift) / BQ - first_qt + 1)))
+                               : min(2, per_head);
+    const int n_general = max(3, n_masked);   // tiles below this index (from the diagonal) take the general path
     for (int h = 0, u = 0; h < p.group; ++h) {
         int j = per_head - 1;
-        if (j >= 3) {
+        if (j >= n_general) {
             const int hq = g * p.group + h;
-            const int64_t row = item.token_start + (int64_t)(first_qt + j - 3) * BQ;   // first row of the tile loaded first
+            const int64_t row = item.q_start + (int64_t)(first_qt + j - 3) * BQ;   // first row of the tile loaded first
             DkvTileLoad<D> load;
             load.qcopy = &qcopy;
             load.docopy = &docopy;
@@ -395,7 +412,7 @@ __global__ __launch_bounds__(kThreads, 1) void bwd_dkv_kernel(BwdParams p) {
             load.stat = ((wave & 1) == 0 ? p.nlse : p.negd) + (int64_t)hq * p.total_tokens + row;
             load.wave = wave;
             load.lane = lane;
-            for (; j >= 3; --j, ++u) tile_step_spread(u, first_qt + j, load);
+            for (; j >= n_general; --j, ++u) tile_step_spread(u, first_qt + j, load);
         }
         for (; j >= n_masked; --j, ++u) tile_step(u, first_qt + j, std::false_type{});
         for (; j >= 0; --j, ++u) tile_step(u, first_qt + j, std::true_type{});
@@ -410,7 +427,7 @@ __global__ __launch_bounds__(kThreads, 1) void bwd_dkv_kernel(BwdParams p) {
     }
 
     if (valid) {
-        const int64_t row_elem = ((int64_t)(item.token_start + my_key) * p.kv_heads + g) * D;
+        const int64_t row_elem = ((int64_t)(item.k_start + my_key) * p.kv_heads + g) * D;
         const bool f32 = p.grad_f32 != 0;
 #pragma unroll
         for (int db = 0; db < DB; ++db)
@@ -425,13 +442,15 @@ __global__ __launch_bounds__(kThreads, 1) void bwd_dkv_kernel(BwdParams p) {
     }
 }
 
-hipError_t launch_bwd_dkv(const BwdParams& p, int head_dim, int64_t num_items, hipStream_t stream) {
+hipError_t launch_bwd_dkv(const BwdParams& p, int head_dim, int64_t num_items, bool block, hipStream_t stream) {
     if (num_items == 0) return hipSuccess;
-    const dim3 grid((unsigned)num_items), block(kThreads);
+    const dim3 grid((unsigned)num_items), threads(kThreads);
     if (head_dim == 128) {
-        hipLaunchKernelGGL(bwd_dkv_kernel<128>, grid, block, 0, stream, p);
+        if (block) hipLaunchKernelGGL((bwd_dkv_kernel<128, true>), grid, threads, 0, stream, p);
+        else hipLaunchKernelGGL((bwd_dkv_kernel<128, false>), grid, threads, 0, stream, p);
     } else {
-        hipLaunchKernelGGL(bwd_dkv_kernel<64>, grid, block, 0, stream, p);
+        if (block) hipLaunchKernelGGL((bwd_dkv_kernel<64, true>), grid, threads, 0, stream, p);
+        else hipLaunchKernelGGL((bwd_dkv_kernel<64, false>), grid, threads, 0, stream, p);
     }
     return hipGetLastError();
 }

@@ -40,37 +40,54 @@ __global__ __launch_bounds__(kThreads) void bwd_dsum_kernel(BwdParams p) {
     if (row < n_rows && c == 0) {
         const int64_t t = row / p.q_heads, h = row % p.q_heads;
         p.negd[h * p.total_tokens + t] = -s;
-        p.nlse[h * p.total_tokens + t] = -p.lse[h * p.total_tokens + t] / p.scale;
+        // a row without any visible key (lse = -inf; possible only for partial results) takes no part: P = 0
+        const float l = p.lse[h * p.total_tokens + t];
+        p.nlse[h * p.total_tokens + t] = l == -INFINITY ? -INFINITY : -l / p.scale;
     }
     if (blockIdx.x == 0 && threadIdx.x < 16) p.ninf_pad[threadIdx.x] = -INFINITY;
 }
 
 // --------------------------------------------------------------------------------- dQ pass
-template <int D>
+template <int D, bool BLOCK>
 __global__ __launch_bounds__(kThreads, 2) void bwd_dq_kernel(BwdParams p) {
     constexpr int BQ = kFwdQTile, BK = kFwdKTile;
     constexpr int KK = D / 16, DB = D / 32;
     constexpr int kTileBytes = BK * D * 2;
     __shared__ __attribute__((aligned(1024))) char lds[2 * 2 * kTileBytes];   // {K, V} x 2 stages
 
-    const hspmd_work_item item = p.items[blockIdx.x];
+    const ItemGeom item = load_item<BLOCK>(p.items, p.block_items, blockIdx.x);
     if (item.tile < 0) return;
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int L = item.seq_len, h = item.head, hk = h / p.group;
+    const int Lq = item.q_len, L = item.k_len, off = item.offset;   // L: keys of the chunk (= rows when !BLOCK)
+    const int h = item.head, hk = h / p.group;
     const int q_row0 = item.tile * BQ;
     const int wave_row0 = q_row0 + wave * 32;
     const int my_row = wave_row0 + (lane & 31);
     const int hh = lane >> 5;
-    const bool valid = my_row < L;
+    const bool valid = my_row < Lq;
+    // last key this lane's row may see (index into the chunk), and the same for the wave's last row
+    const int my_limit = BLOCK ? min(my_row + off, L - 1) : my_row;
+    const int wave_limit = BLOCK ? min(wave_row0 + 31 + off, L - 1) : wave_row0 + 31;
 
-    const uint16_t* qbase = p.q + (int64_t)item.token_start * p.q_stride + (int64_t)h * D;
-    const uint16_t* dobase = p.d_o + ((int64_t)item.token_start * p.q_heads + h) * D;
-    const uint16_t* kbase = p.k + (int64_t)item.token_start * p.kv_stride + (int64_t)hk * D;
-    const uint16_t* vbase = p.v + (int64_t)item.token_start * p.kv_stride + (int64_t)hk * D;
+    const uint16_t* qbase = p.q + (int64_t)item.q_start * p.q_stride + (int64_t)h * D;
+    const uint16_t* dobase = p.d_o + ((int64_t)item.q_start * p.q_heads + h) * D;
+    const uint16_t* kbase = p.k + (int64_t)item.k_start * p.kv_stride + (int64_t)hk * D;
+    const uint16_t* vbase = p.v + (int64_t)item.k_start * p.kv_stride + (int64_t)hk * D;
 
-    const int kv_end = min(L, q_row0 + BQ);
+    // key j is visible to row r iff j <= r + off: the tile's last row sees keys 0 .. kv_end-1
+    const int kv_end = max(0, min(L, min(Lq, q_row0 + BQ) + off));
     const int n_tiles = (kv_end + BK - 1) / BK;
+    if (BLOCK && n_tiles == 0) {
+        // nothing visible: this block's share of dQ is zero
+        if (valid && !p.dq_accumulate) {
+            float* row = static_cast<float*>(p.dq) + ((int64_t)(item.q_start + my_row) * p.q_heads + h) * D;
+#pragma unroll
+            for (int c4 = 0; c4 < D / 8; ++c4)
+                *reinterpret_cast<f32x4*>(row + hh * (D / 2) + c4 * 4) = f32x4{0.f, 0.f, 0.f, 0.f};
+        }
+        return;
+    }
 
     TileCopy<D, BK> kvcopy;   // K and V share stride and geometry
     kvcopy.init(p.kv_stride, wave, lane);
@@ -91,7 +108,7 @@ __global__ __launch_bounds__(kThreads, 2) void bwd_dq_kernel(BwdParams p) {
         qf[kk] = a.v;
         dof[kk] = b.v;
     }
-    const int64_t stat = (int64_t)h * p.total_tokens + item.token_start + my_row;
+    const int64_t stat = (int64_t)h * p.total_tokens + item.q_start + my_row;
     const float c = p.scale_log2;
     const float nlse2 = valid ? p.nlse[stat] * c : -INFINITY;   // -LSE log2(e); rows past the end get P = 0
     const float negd = valid ? p.negd[stat] : 0.f;
@@ -162,7 +179,7 @@ __global__ __launch_bounds__(kThreads, 2) void bwd_dq_kernel(BwdParams p) {
 #pragma unroll
         for (int i = 0; i < 16; ++i) {
             float pr = fast_exp2(fmaf(sacc[i], c, nlse2));
-            if (kMask && kb + acc_row(i, lane) > my_row) pr = 0.f;
+            if (kMask && kb + acc_row(i, lane) > my_limit) pr = 0.f;
             sacc[i] = pr * (dp[i] + negd);   // dS^T
         }
         const bf16x8 dsf[2] = {frag_to_bf16(sacc, 0), frag_to_bf16(sacc, 1)};
@@ -192,7 +209,7 @@ __global__ __launch_bounds__(kThreads, 2) void bwd_dq_kernel(BwdParams p) {
 #pragma unroll
         for (int jb = 0; jb < 2; ++jb) {
             const int kb = kt * BK + jb * 32;
-            if (!kMask || kb <= wave_row0 + 31) block(ktile, vtile, jb, kb, masked, std::false_type{}, none);
+            if (!kMask || kb <= wave_limit) block(ktile, vtile, jb, kb, masked, std::false_type{}, none);
         }
     };
     // An unmasked tile whose successor is a whole tile: the successor's copies are issued from inside the blocks,
@@ -214,7 +231,9 @@ __global__ __launch_bounds__(kThreads, 2) void bwd_dq_kernel(BwdParams p) {
     };
     // separate loops instead of tests per tile: tiles wholly below the diagonal (with and without a whole
     // successor), then the (at most two) tiles on the diagonal
-    const int n_interior = min(n_tiles, 2 * item.tile);
+    // tiles whose every key exists and is visible to every row of this q tile (with the shift, keys past the end
+    // of the chunk need the mask: the last, partial tile is never an interior one)
+    const int n_interior = BLOCK ? max(0, min(min(n_tiles, (q_row0 + off + 1) / BK), L / BK)) : min(n_tiles, 2 * item.tile);
     const int n_spread = max(0, min(min(n_interior, n_tiles - 1), L / BK - 1));
     int kt = 0;
     for (; kt < n_spread; ++kt) step_spread(kt);
@@ -222,14 +241,29 @@ __global__ __launch_bounds__(kThreads, 2) void bwd_dq_kernel(BwdParams p) {
     for (; kt < n_tiles; ++kt) step(kt, std::true_type{});
 
     if (valid) {
-        const int64_t row_elem = ((int64_t)(item.token_start + my_row) * p.q_heads + h) * D;
+        const int64_t row_elem = ((int64_t)(item.q_start + my_row) * p.q_heads + h) * D;
+        if (BLOCK && p.dq_accumulate) {
+            // this block's share is added to what earlier blocks left (fp32)
+            float* row = static_cast<float*>(p.dq) + row_elem;
 #pragma unroll
-        for (int db = 0; db < DB; ++db)
+            for (int db = 0; db < DB; ++db)
 #pragma unroll
-            for (int i4 = 0; i4 < 4; ++i4)
-                store_grad4(p.dq, row_elem + db * 32 + i4 * 8 + hh * 4, p.grad_f32 != 0,
-                            acc[db][4 * i4 + 0] * p.scale, acc[db][4 * i4 + 1] * p.scale,
-                            acc[db][4 * i4 + 2] * p.scale, acc[db][4 * i4 + 3] * p.scale);
+                for (int i4 = 0; i4 < 4; ++i4) {
+                    f32x4* dst = reinterpret_cast<f32x4*>(row + db * 32 + i4 * 8 + hh * 4);
+                    f32x4 old = *dst;
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) old[j] += acc[db][4 * i4 + j] * p.scale;
+                    *dst = old;
+                }
+        } else {
+#pragma unroll
+            for (int db = 0; db < DB; ++db)
+#pragma unroll
+                for (int i4 = 0; i4 < 4; ++i4)
+                    store_grad4(p.dq, row_elem + db * 32 + i4 * 8 + hh * 4, p.grad_f32 != 0,
+                                acc[db][4 * i4 + 0] * p.scale, acc[db][4 * i4 + 1] * p.scale,
+                                acc[db][4 * i4 + 2] * p.scale, acc[db][4 * i4 + 3] * p.scale);
+        }
     }
 }
 
@@ -247,13 +281,15 @@ hipError_t launch_bwd_dsum(const BwdParams& p, int head_dim, hipStream_t stream)
     return hipGetLastError();
 }
 
-hipError_t launch_bwd_dq(const BwdParams& p, int head_dim, int64_t num_items, hipStream_t stream) {
+hipError_t launch_bwd_dq(const BwdParams& p, int head_dim, int64_t num_items, bool block, hipStream_t stream) {
     if (num_items == 0) return hipSuccess;
-    const dim3 grid((unsigned)num_items), block(kThreads);
+    const dim3 grid((unsigned)num_items), threads(kThreads);
     if (head_dim == 128) {
-        hipLaunchKernelGGL(bwd_dq_kernel<128>, grid, block, 0, stream, p);
+        if (block) hipLaunchKernelGGL((bwd_dq_kernel<128, true>), grid, threads, 0, stream, p);
+        else hipLaunchKernelGGL((bwd_dq_kernel<128, false>), grid, threads, 0, stream, p);
     } else {
-        hipLaunchKernelGGL(bwd_dq_kernel<64>, grid, block, 0, stream, p);
+        if (block) hipLaunchKernelGGL((bwd_dq_kernel<64, true>), grid, threads, 0, stream, p);
+        else hipLaunchKernelGGL((bwd_dq_kernel<64, false>), grid, threads, 0, stream, p);
     }
     return hipGetLastError();
 }

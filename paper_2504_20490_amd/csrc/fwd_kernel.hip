@@ -75,7 +75,9 @@ __device__ __forceinline__ float pair_max(float x) {
 // tiles, one instruction at a time at fixed places among its LDS reads (copies are ordered against LDS
 // accesses and the reads are tied to the MFMAs by the scheduling hints).  Issued back to back after the
 // barrier, the copies of all waves queue up in front of the CU's one address unit.
-template <int D, bool MASK, bool LAST, bool SPREAD>
+// BLOCK: a lane's row may have no visible key so far (its running max is still -inf): the maximum that the
+// exponentials are taken against is then replaced by 0, which keeps every weight and the rescale factor at 0.
+template <int D, bool MASK, bool LAST, bool SPREAD, bool BLOCK>
 __device__ __forceinline__ void fwd_iteration(FwdState<D>& st, const char* kbuf, const char* vbuf, float c,
                                               int dkey /* my_row - key0 - 4 * (lane / 32) */,
                                               const FwdTileLoad<D>& load) {
@@ -99,8 +101,9 @@ __device__ __forceinline__ void fwd_iteration(FwdState<D>& st, const char* kbuf,
         for (int i = (jb == 0 ? 2 : 0); i < 16; ++i) tmax = fmaxf(tmax, st.s[jb][i]);
     tmax = pair_max(tmax);
     const float m_new = fmaxf(st.m, tmax);
-    const float alpha = fast_exp2((st.m - m_new) * c);
-    const float mc = m_new * c;
+    const float m_ref = (BLOCK && m_new == -INFINITY) ? 0.f : m_new;
+    const float alpha = fast_exp2((st.m - m_ref) * c);
+    const float mc = m_ref * c;
     if (__any(m_new > st.m)) {      // wave-uniform: skip the accumulator rescale when no lane's max moved
 #pragma unroll
         for (int db = 0; db < DB; ++db)
@@ -190,7 +193,7 @@ __device__ __forceinline__ void fwd_iteration(FwdState<D>& st, const char* kbuf,
 
 }  // namespace
 
-template <int D>
+template <int D, bool BLOCK>
 __global__ __launch_bounds__(kThreads, 2) void fwd_kernel(FwdParams p) {
     using G = FwdGeom<D>;
     constexpr int BQ = kFwdQTile, BK = kFwdKTile;
@@ -202,23 +205,41 @@ __global__ __launch_bounds__(kThreads, 2) void fwd_kernel(FwdParams p) {
     char* const vbuf0 = lds + 2 * kTileBytes;
     const uint32_t kdst0 = lds_address(lds), vdst0 = kdst0 + 2 * kTileBytes;   // the same buffers as copy destinations
 
-    const hspmd_work_item item = p.items[blockIdx.x];
+    const ItemGeom item = load_item<BLOCK>(p.items, p.block_items, blockIdx.x);
     if (item.tile < 0) return;
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int L = item.seq_len, h = item.head, hk = h / p.group;
+    const int Lq = item.q_len, L = item.k_len, off = item.offset;   // L: keys of the chunk (= rows when !BLOCK)
+    const int h = item.head, hk = h / p.group;
     const int q_row0 = item.tile * BQ;
     const int wave_row0 = q_row0 + wave * 32;
     const int my_row = wave_row0 + (lane & 31);
     const int hh = lane >> 5;
 
-    const uint16_t* qbase = p.q + (int64_t)item.token_start * p.q_stride + (int64_t)h * D;
-    const uint16_t* kbase = p.k + (int64_t)item.token_start * p.kv_stride + (int64_t)hk * D;
-    const uint16_t* vbase = p.v + (int64_t)item.token_start * p.kv_stride + (int64_t)hk * D;
+    const uint16_t* qbase = p.q + (int64_t)item.q_start * p.q_stride + (int64_t)h * D;
+    const uint16_t* kbase = p.k + (int64_t)item.k_start * p.kv_stride + (int64_t)hk * D;
+    const uint16_t* vbase = p.v + (int64_t)item.k_start * p.kv_stride + (int64_t)hk * D;
 
-    const int kv_end = min(L, q_row0 + BQ);
+    // key j is visible to row r iff j <= r + off: the tile's last row sees keys 0 .. kv_end-1
+    const int kv_end = max(0, min(L, min(Lq, q_row0 + BQ) + off));
     const int n_tiles = (kv_end + BK - 1) / BK;
-    const int n_interior = min(n_tiles, 2 * item.tile);   // tiles whose every key precedes every row of this q tile
+    // tiles whose every key exists and is visible to every row of this q tile: (kt + 1) BK - 1 <= q_row0 + off
+    // (without the shift, keys past the end of the sequence lie above every row's diagonal; with it they need the
+    // mask, so the chunk's last, partial tile is never an interior one)
+    const int n_interior = BLOCK ? max(0, min(min(n_tiles, (q_row0 + off + 1) / BK), L / BK)) : min(n_tiles, 2 * item.tile);
+    // last key this lane's row may see, as an index into the chunk
+    const int my_limit = BLOCK ? min(my_row + off, L - 1) : my_row;
+    if (BLOCK && n_tiles == 0) {
+        // no key of the chunk is visible to any row of the tile: O = 0, LSE = -inf
+        if (my_row < Lq) {
+            float* orow = p.o_f32 + ((int64_t)(item.q_start + my_row) * p.q_heads + h) * D;
+#pragma unroll
+            for (int c4 = 0; c4 < D / 8; ++c4)
+                *reinterpret_cast<f32x4*>(orow + hh * (D / 2) + c4 * 4) = f32x4{0.f, 0.f, 0.f, 0.f};
+            if (hh == 0) p.lse[(int64_t)h * p.total_tokens + item.q_start + my_row] = -INFINITY;
+        }
+        return;
+    }
 
     TileCopy<D, BK> kvcopy;   // K and V share stride and geometry
     kvcopy.init(p.kv_stride, wave, lane);
@@ -232,7 +253,7 @@ __global__ __launch_bounds__(kThreads, 2) void fwd_kernel(FwdParams p) {
     for (int kk = 0; kk < KK; ++kk) {
         union { u32x4 u; bf16x8 v; } t;
         t.u = u32x4{0u, 0u, 0u, 0u};
-        if (my_row < L) t.u = *reinterpret_cast<const u32x4*>(qbase + (int64_t)my_row * p.q_stride + kk * 16 + hh * 8);
+        if (my_row < Lq) t.u = *reinterpret_cast<const u32x4*>(qbase + (int64_t)my_row * p.q_stride + kk * 16 + hh * 8);
         st.qf[kk] = t.v;
     }
 #pragma unroll
@@ -277,8 +298,8 @@ __global__ __launch_bounds__(kThreads, 2) void fwd_kernel(FwdParams p) {
         }
         if (kt + 2 < n_tiles) kvcopy.issue(kdst0 + (kt & 1) * kTileBytes, kbase, p.kv_stride, (kt + 2) * BK, L, wave, lane);
         if (kt + 1 < n_tiles) kvcopy.issue(vdst0 + ((kt + 1) & 1) * kTileBytes, vbase, p.kv_stride, (kt + 1) * BK, L, wave, lane);
-        fwd_iteration<D, decltype(masked)::value, decltype(last)::value, false>(
-            st, kbuf0 + ((kt + 1) & 1) * kTileBytes, vbuf0 + (kt & 1) * kTileBytes, c, my_row - kt * BK - 4 * hh, no_load);
+        fwd_iteration<D, decltype(masked)::value, decltype(last)::value, false, BLOCK>(
+            st, kbuf0 + ((kt + 1) & 1) * kTileBytes, vbuf0 + (kt & 1) * kTileBytes, c, my_limit - kt * BK - 4 * hh, no_load);
     };
     // the same for an unmasked tile whose successors kt+1 and kt+2 are whole tiles: their copies need no case
     // distinction and are issued from inside the iteration
@@ -294,8 +315,8 @@ __global__ __launch_bounds__(kThreads, 2) void fwd_kernel(FwdParams p) {
         load.k_dst = kdst0 + (kt & 1) * kTileBytes;
         load.v_dst = vdst0 + ((kt + 1) & 1) * kTileBytes;
         load.wave = wave;
-        fwd_iteration<D, false, false, true>(st, kbuf0 + ((kt + 1) & 1) * kTileBytes, vbuf0 + (kt & 1) * kTileBytes, c,
-                                             my_row - kt * BK - 4 * hh, load);
+        fwd_iteration<D, false, false, true, BLOCK>(st, kbuf0 + ((kt + 1) & 1) * kTileBytes, vbuf0 + (kt & 1) * kTileBytes, c,
+                                                    my_limit - kt * BK - 4 * hh, load);
     };
     // separate loops instead of branches inside one: unmasked tiles (with and without whole successors), masked
     // tiles, and the final tile (which has no successor to compute scores for); the large register state then
@@ -306,32 +327,50 @@ __global__ __launch_bounds__(kThreads, 2) void fwd_kernel(FwdParams p) {
     for (; kt < n_spread; ++kt) step_spread(kt);
     for (; kt < n_plain; ++kt) step(kt, std::false_type{}, std::false_type{});
     for (; kt < n_tiles - 1; ++kt) step(kt, std::true_type{}, std::false_type{});
-    step(kt, std::true_type{}, std::true_type{});   // the final tile always touches the diagonal
+    step(kt, std::true_type{}, std::true_type{});   // the final tile touches the diagonal (always, when !BLOCK)
 
     const float l_row = st.l + partner32(st.l);
-    if (my_row < L) {
-        const float inv = 1.f / l_row;
-        uint16_t* orow = p.o + ((int64_t)(item.token_start + my_row) * p.q_heads + h) * D;
+    if (my_row < Lq) {
+        if constexpr (BLOCK) {
+            // partial result in fp32; a row that saw no key has l = 0 and m = -inf: O = 0, LSE = -inf
+            const float inv = l_row > 0.f ? 1.f / l_row : 0.f;
+            float* orow = p.o_f32 + ((int64_t)(item.q_start + my_row) * p.q_heads + h) * D;
 #pragma unroll
-        for (int db = 0; db < DB; ++db)
+            for (int db = 0; db < DB; ++db)
 #pragma unroll
-            for (int i4 = 0; i4 < 4; ++i4) {
-                u32x2 w;
-                w[0] = pack_bf16(st.acc[db][4 * i4 + 0] * inv, st.acc[db][4 * i4 + 1] * inv);
-                w[1] = pack_bf16(st.acc[db][4 * i4 + 2] * inv, st.acc[db][4 * i4 + 3] * inv);
-                *reinterpret_cast<u32x2*>(orow + db * 32 + i4 * 8 + hh * 4) = w;
-            }
-        if (hh == 0) p.lse[(int64_t)h * p.total_tokens + item.token_start + my_row] = (st.m * c + __log2f(l_row)) * kLn2;
+                for (int i4 = 0; i4 < 4; ++i4)
+                    *reinterpret_cast<f32x4*>(orow + db * 32 + i4 * 8 + hh * 4) =
+                        f32x4{st.acc[db][4 * i4 + 0] * inv, st.acc[db][4 * i4 + 1] * inv, st.acc[db][4 * i4 + 2] * inv,
+                              st.acc[db][4 * i4 + 3] * inv};
+            if (hh == 0)
+                p.lse[(int64_t)h * p.total_tokens + item.q_start + my_row] =
+                    l_row > 0.f ? (st.m * c + __log2f(l_row)) * kLn2 : -INFINITY;
+        } else {
+            const float inv = 1.f / l_row;
+            uint16_t* orow = p.o + ((int64_t)(item.q_start + my_row) * p.q_heads + h) * D;
+#pragma unroll
+            for (int db = 0; db < DB; ++db)
+#pragma unroll
+                for (int i4 = 0; i4 < 4; ++i4) {
+                    u32x2 w;
+                    w[0] = pack_bf16(st.acc[db][4 * i4 + 0] * inv, st.acc[db][4 * i4 + 1] * inv);
+                    w[1] = pack_bf16(st.acc[db][4 * i4 + 2] * inv, st.acc[db][4 * i4 + 3] * inv);
+                    *reinterpret_cast<u32x2*>(orow + db * 32 + i4 * 8 + hh * 4) = w;
+                }
+            if (hh == 0) p.lse[(int64_t)h * p.total_tokens + item.q_start + my_row] = (st.m * c + __log2f(l_row)) * kLn2;
+        }
     }
 }
 
-hipError_t launch_fwd(const FwdParams& p, int head_dim, int64_t num_items, hipStream_t stream) {
+hipError_t launch_fwd(const FwdParams& p, int head_dim, int64_t num_items, bool block, hipStream_t stream) {
     if (num_items == 0) return hipSuccess;
-    const dim3 grid((unsigned)num_items), block(kThreads);
+    const dim3 grid((unsigned)num_items), threads(kThreads);
     if (head_dim == 128) {
-        hipLaunchKernelGGL(fwd_kernel<128>, grid, block, 0, stream, p);
+        if (block) hipLaunchKernelGGL((fwd_kernel<128, true>), grid, threads, 0, stream, p);
+        else hipLaunchKernelGGL((fwd_kernel<128, false>), grid, threads, 0, stream, p);
     } else {
-        hipLaunchKernelGGL(fwd_kernel<64>, grid, block, 0, stream, p);
+        if (block) hipLaunchKernelGGL((fwd_kernel<64, true>), grid, threads, 0, stream, p);
+        else hipLaunchKernelGGL((fwd_kernel<64, false>), grid, threads, 0, stream, p);
     }
     return hipGetLastError();
 }

@@ -75,6 +75,10 @@ struct hspmd_attn_plan {
     int64_t count[3] = {0, 0, 0};
     hspmd_work_item* items[3] = {nullptr, nullptr, nullptr};   // device; three views into one allocation
     void* device_block = nullptr;
+    // block variant (hspmd_attn_block_plan_create): total_tokens counts query tokens
+    bool is_block = false;
+    int64_t total_kv_tokens = 0;
+    hspmd_block_item* block_items[3] = {nullptr, nullptr, nullptr};
 };
 
 extern "C" {
@@ -233,6 +237,7 @@ hspmd_status hspmd_attn_varlen_fwd(const hspmd_attn_plan* plan, const void* q, c
                                    int64_t q_token_stride, int64_t kv_token_stride, float softmax_scale,
                                    void* o, float* lse, void* stream) {
     if (!plan) return fail(HSPMD_ERR_INVALID_ARG, "plan is NULL");
+    if (plan->is_block) return fail(HSPMD_ERR_INVALID_ARG, "plan was made by hspmd_attn_block_plan_create");
     if (plan->total_tokens == 0) return HSPMD_OK;
     if (!q || !k || !v || !o || !lse) return fail(HSPMD_ERR_INVALID_ARG, "null tensor pointer");
     if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(o))
@@ -254,7 +259,7 @@ hspmd_status hspmd_attn_varlen_fwd(const hspmd_attn_plan* plan, const void* q, c
     p.group = plan->q_heads / plan->kv_heads;
     p.scale_log2 = scale * 1.4426950408889634f;
     hipStream_t s = static_cast<hipStream_t>(stream);
-    const hipError_t e = timed_launch(0, s, [&] { return hspmd::launch_fwd(p, plan->head_dim, plan->count[HSPMD_LIST_FWD], s); });
+    const hipError_t e = timed_launch(0, s, [&] { return hspmd::launch_fwd(p, plan->head_dim, plan->count[HSPMD_LIST_FWD], false, s); });
     if (e != hipSuccess) return fail_hip(e, "forward launch");
     return HSPMD_OK;
 }
@@ -265,6 +270,7 @@ hspmd_status hspmd_attn_varlen_bwd(const hspmd_attn_plan* plan, const void* q, c
                                    void* dq, void* dk, void* dv, hspmd_grad_dtype grad_dtype,
                                    void* workspace, size_t workspace_bytes, void* stream) {
     if (!plan) return fail(HSPMD_ERR_INVALID_ARG, "plan is NULL");
+    if (plan->is_block) return fail(HSPMD_ERR_INVALID_ARG, "plan was made by hspmd_attn_block_plan_create");
     if (grad_dtype != HSPMD_GRAD_BF16 && grad_dtype != HSPMD_GRAD_F32)
         return fail(HSPMD_ERR_UNSUPPORTED, "grad_dtype must be HSPMD_GRAD_BF16 or HSPMD_GRAD_F32");
     if (plan->total_tokens == 0) return HSPMD_OK;
@@ -304,11 +310,208 @@ hspmd_status hspmd_attn_varlen_bwd(const hspmd_attn_plan* plan, const void* q, c
     hipError_t e = timed_launch(1, s, [&] { return hspmd::launch_bwd_dsum(p, plan->head_dim, s); });
     if (e != hipSuccess) return fail_hip(e, "backward D launch");
     p.items = plan->items[HSPMD_LIST_DQ];
-    e = timed_launch(2, s, [&] { return hspmd::launch_bwd_dq(p, plan->head_dim, plan->count[HSPMD_LIST_DQ], s); });
+    e = timed_launch(2, s, [&] { return hspmd::launch_bwd_dq(p, plan->head_dim, plan->count[HSPMD_LIST_DQ], false, s); });
     if (e != hipSuccess) return fail_hip(e, "backward dQ launch");
     p.items = plan->items[HSPMD_LIST_DKV];
-    e = timed_launch(3, s, [&] { return hspmd::launch_bwd_dkv(p, plan->head_dim, plan->count[HSPMD_LIST_DKV], s); });
+    e = timed_launch(3, s, [&] { return hspmd::launch_bwd_dkv(p, plan->head_dim, plan->count[HSPMD_LIST_DKV], false, s); });
     if (e != hipSuccess) return fail_hip(e, "backward dK/dV launch");
+    return HSPMD_OK;
+}
+
+// ------------------------------------------------------------------------------ block variant
+hspmd_status hspmd_attn_block_schedule(hspmd_list_kind kind, const int32_t* cu_q, const int32_t* cu_k,
+                                       const int32_t* q_pos, const int32_t* k_pos, int32_t num_seqs,
+                                       int32_t local_q_heads, int32_t local_kv_heads, int32_t num_queues,
+                                       hspmd_block_item* items, int64_t capacity, int64_t* count) {
+    if (kind != HSPMD_LIST_FWD && kind != HSPMD_LIST_DQ && kind != HSPMD_LIST_DKV)
+        return fail(HSPMD_ERR_INVALID_ARG, "unknown list kind");
+    if (!count) return fail(HSPMD_ERR_INVALID_ARG, "count is NULL");
+    if (num_queues < 1) return fail(HSPMD_ERR_INVALID_ARG, "num_queues must be >= 1");
+    if (capacity < 0 || (capacity > 0 && !items)) return fail(HSPMD_ERR_INVALID_ARG, "items is NULL");
+    const std::string why = hspmd::check_block_pack(cu_q, cu_k, q_pos, k_pos, num_seqs, local_q_heads, local_kv_heads);
+    if (!why.empty()) return fail(HSPMD_ERR_INVALID_ARG, why);
+    std::vector<hspmd_block_item> list;
+    try {
+        list = hspmd::build_block_list(kind, cu_q, cu_k, q_pos, k_pos, num_seqs, local_q_heads, local_kv_heads, num_queues);
+    } catch (const std::bad_alloc&) {
+        return fail(HSPMD_ERR_INVALID_ARG, "out of host memory while building the work list");
+    }
+    *count = (int64_t)list.size();
+    if (capacity == 0) return HSPMD_OK;
+    if ((int64_t)list.size() > capacity) return fail(HSPMD_ERR_INVALID_ARG, "items buffer too small");
+    if (!list.empty()) std::memcpy(items, list.data(), list.size() * sizeof(hspmd_block_item));
+    return HSPMD_OK;
+}
+
+hspmd_status hspmd_attn_block_plan_create(const int32_t* cu_q_host, const int32_t* cu_k_host, const int32_t* q_pos_host,
+                                          const int32_t* k_pos_host, int32_t num_seqs, int32_t local_q_heads,
+                                          int32_t local_kv_heads, int32_t head_dim, void* stream, hspmd_attn_plan** out) {
+    if (!out) return fail(HSPMD_ERR_INVALID_ARG, "out is NULL");
+    *out = nullptr;
+    const std::string why =
+        hspmd::check_block_pack(cu_q_host, cu_k_host, q_pos_host, k_pos_host, num_seqs, local_q_heads, local_kv_heads);
+    if (!why.empty()) return fail(HSPMD_ERR_INVALID_ARG, why);
+    if (head_dim != 64 && head_dim != 128) return fail(HSPMD_ERR_UNSUPPORTED, "head_dim must be 64 or 128");
+    hspmd_attn_plan* plan = new (std::nothrow) hspmd_attn_plan();
+    if (!plan) return fail(HSPMD_ERR_INVALID_ARG, "out of host memory");
+    plan->is_block = true;
+    plan->num_seqs = num_seqs;
+    plan->q_heads = local_q_heads;
+    plan->kv_heads = local_kv_heads;
+    plan->head_dim = head_dim;
+    plan->total_tokens = cu_q_host[num_seqs];
+    plan->total_kv_tokens = cu_k_host[num_seqs];
+    std::vector<hspmd_block_item> all;
+    size_t offset[3] = {0, 0, 0};
+    try {
+        for (int kind = 0; kind < 3; ++kind) {
+            const std::vector<hspmd_block_item> list =
+                hspmd::build_block_list((hspmd_list_kind)kind, cu_q_host, cu_k_host, q_pos_host, k_pos_host, num_seqs,
+                                        local_q_heads, local_kv_heads, hspmd::kNumXcd);
+            plan->count[kind] = (int64_t)list.size();
+            offset[kind] = all.size();
+            all.insert(all.end(), list.begin(), list.end());
+        }
+    } catch (const std::bad_alloc&) {
+        delete plan;
+        return fail(HSPMD_ERR_INVALID_ARG, "out of host memory while building the work lists");
+    }
+    if (!all.empty()) {
+        hipStream_t s = static_cast<hipStream_t>(stream);
+        const size_t bytes = all.size() * sizeof(hspmd_block_item);
+        hipError_t e = hipMalloc(&plan->device_block, bytes);
+        if (e != hipSuccess) {
+            delete plan;
+            return fail_hip(e, "hipMalloc(work lists)");
+        }
+        e = hipMemcpyAsync(plan->device_block, all.data(), bytes, hipMemcpyHostToDevice, s);
+        if (e == hipSuccess) e = hipStreamSynchronize(s);
+        if (e != hipSuccess) {
+            hspmd_attn_plan_destroy(plan);
+            return fail_hip(e, "hipMemcpyAsync(work lists)");
+        }
+        for (int kind = 0; kind < 3; ++kind)
+            if (plan->count[kind] > 0)
+                plan->block_items[kind] = static_cast<hspmd_block_item*>(plan->device_block) + offset[kind];
+    }
+    *out = plan;
+    return HSPMD_OK;
+}
+
+int64_t hspmd_attn_plan_total_kv_tokens(const hspmd_attn_plan* plan) {
+    if (!plan) return -1;
+    return plan->is_block ? plan->total_kv_tokens : plan->total_tokens;
+}
+
+hspmd_status hspmd_attn_block_fwd(const hspmd_attn_plan* plan, const void* q, const void* k, const void* v,
+                                  int64_t q_token_stride, int64_t kv_token_stride, float softmax_scale,
+                                  float* o_partial, float* lse_partial, void* stream) {
+    if (!plan) return fail(HSPMD_ERR_INVALID_ARG, "plan is NULL");
+    if (!plan->is_block) return fail(HSPMD_ERR_INVALID_ARG, "plan was not made by hspmd_attn_block_plan_create");
+    if (plan->total_tokens == 0) return HSPMD_OK;
+    if (!q || !o_partial || !lse_partial || (plan->total_kv_tokens > 0 && (!k || !v)))
+        return fail(HSPMD_ERR_INVALID_ARG, "null tensor pointer");
+    if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(o_partial))
+        return fail(HSPMD_ERR_INVALID_ARG, "q, k, v, o_partial must be 16-byte aligned");
+    if (hspmd_status rc = check_strides(plan, q_token_stride, kv_token_stride)) return rc;
+    if (!(softmax_scale <= 0.f) && !std::isfinite(softmax_scale)) return fail(HSPMD_ERR_INVALID_ARG, "softmax_scale is not finite");
+    const float scale = softmax_scale > 0.f ? softmax_scale : 1.0f / std::sqrt((float)plan->head_dim);
+    hspmd::FwdParams p{};
+    p.q = static_cast<const uint16_t*>(q);
+    p.k = static_cast<const uint16_t*>(k);
+    p.v = static_cast<const uint16_t*>(v);
+    p.o_f32 = o_partial;
+    p.lse = lse_partial;
+    p.block_items = plan->block_items[HSPMD_LIST_FWD];
+    p.q_stride = q_token_stride;
+    p.kv_stride = kv_token_stride;
+    p.total_tokens = plan->total_tokens;
+    p.q_heads = plan->q_heads;
+    p.group = plan->q_heads / plan->kv_heads;
+    p.scale_log2 = scale * 1.4426950408889634f;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const hipError_t e = timed_launch(0, s, [&] { return hspmd::launch_fwd(p, plan->head_dim, plan->count[HSPMD_LIST_FWD], true, s); });
+    if (e != hipSuccess) return fail_hip(e, "block forward launch");
+    return HSPMD_OK;
+}
+
+hspmd_status hspmd_attn_merge(int64_t total_tokens, int32_t local_q_heads, int32_t head_dim, const float* o_a,
+                              const float* lse_a, const float* o_b, const float* lse_b, float* o_out, float* lse_out,
+                              void* o_out_bf16, void* stream) {
+    if (total_tokens < 0 || local_q_heads <= 0) return fail(HSPMD_ERR_INVALID_ARG, "bad token or head count");
+    if (head_dim != 64 && head_dim != 128) return fail(HSPMD_ERR_UNSUPPORTED, "head_dim must be 64 or 128");
+    if (total_tokens == 0) return HSPMD_OK;
+    if (!o_a || !lse_a || !o_b || !lse_b || !o_out || !lse_out) return fail(HSPMD_ERR_INVALID_ARG, "null tensor pointer");
+    if (!aligned16(o_a) || !aligned16(o_b) || !aligned16(o_out) || !aligned16(o_out_bf16))
+        return fail(HSPMD_ERR_INVALID_ARG, "O tensors must be 16-byte aligned");
+    if (o_out == o_b || lse_out == lse_b) return fail(HSPMD_ERR_INVALID_ARG, "the output may alias operand a only");
+    hspmd::MergeParams p{};
+    p.o_a = o_a; p.lse_a = lse_a; p.o_b = o_b; p.lse_b = lse_b;
+    p.o_out = o_out; p.lse_out = lse_out;
+    p.o_out_bf16 = static_cast<uint16_t*>(o_out_bf16);
+    p.total_tokens = total_tokens;
+    p.q_heads = local_q_heads;
+    p.head_dim = head_dim;
+    const hipError_t e = hspmd::launch_merge(p, static_cast<hipStream_t>(stream));
+    if (e != hipSuccess) return fail_hip(e, "merge launch");
+    return HSPMD_OK;
+}
+
+hspmd_status hspmd_attn_block_bwd(const hspmd_attn_plan* plan, const void* q, const void* k, const void* v,
+                                  const void* o, const float* lse, const void* d_o,
+                                  int64_t q_token_stride, int64_t kv_token_stride, float softmax_scale,
+                                  float* dq, int32_t dq_accumulate, float* dk, float* dv, int32_t reuse_statistics,
+                                  void* workspace, size_t workspace_bytes, void* stream) {
+    if (!plan) return fail(HSPMD_ERR_INVALID_ARG, "plan is NULL");
+    if (!plan->is_block) return fail(HSPMD_ERR_INVALID_ARG, "plan was not made by hspmd_attn_block_plan_create");
+    if (plan->total_tokens == 0 && plan->total_kv_tokens == 0) return HSPMD_OK;
+    if (!workspace) return fail(HSPMD_ERR_INVALID_ARG, "null tensor pointer");
+    if (plan->total_tokens > 0 && (!q || !d_o || !dq || (!reuse_statistics && (!o || !lse))))
+        return fail(HSPMD_ERR_INVALID_ARG, "null tensor pointer");
+    if (plan->total_kv_tokens > 0 && (!k || !v || !dk || !dv)) return fail(HSPMD_ERR_INVALID_ARG, "null tensor pointer");
+    if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(o) || !aligned16(d_o) || !aligned16(dq) ||
+        !aligned16(dk) || !aligned16(dv) || !aligned16(workspace))
+        return fail(HSPMD_ERR_INVALID_ARG, "tensors and workspace must be 16-byte aligned");
+    if (hspmd_status rc = check_strides(plan, q_token_stride, kv_token_stride)) return rc;
+    if (workspace_bytes < hspmd_attn_bwd_workspace_bytes(plan))
+        return fail(HSPMD_ERR_WORKSPACE_TOO_SMALL, "workspace smaller than hspmd_attn_bwd_workspace_bytes(plan)");
+    if (!(softmax_scale <= 0.f) && !std::isfinite(softmax_scale)) return fail(HSPMD_ERR_INVALID_ARG, "softmax_scale is not finite");
+    const float scale = softmax_scale > 0.f ? softmax_scale : 1.0f / std::sqrt((float)plan->head_dim);
+    hspmd::BwdParams p{};
+    p.q = static_cast<const uint16_t*>(q);
+    p.k = static_cast<const uint16_t*>(k);
+    p.v = static_cast<const uint16_t*>(v);
+    p.o = static_cast<const uint16_t*>(o);
+    p.d_o = static_cast<const uint16_t*>(d_o);
+    p.lse = lse;
+    p.negd = static_cast<float*>(workspace);
+    p.nlse = p.negd + (size_t)plan->q_heads * (size_t)plan->total_tokens;
+    p.ninf_pad = p.nlse + (size_t)plan->q_heads * (size_t)plan->total_tokens;
+    p.dq = dq;
+    p.dk = dk;
+    p.dv = dv;
+    p.q_stride = q_token_stride;
+    p.kv_stride = kv_token_stride;
+    p.total_tokens = plan->total_tokens;
+    p.q_heads = plan->q_heads;
+    p.kv_heads = plan->kv_heads;
+    p.group = plan->q_heads / plan->kv_heads;
+    p.grad_f32 = 1;
+    p.dq_accumulate = dq_accumulate ? 1 : 0;
+    p.scale = scale;
+    p.scale_log2 = scale * 1.4426950408889634f;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    hipError_t e = hipSuccess;
+    if (!reuse_statistics && plan->total_tokens > 0) {
+        e = timed_launch(1, s, [&] { return hspmd::launch_bwd_dsum(p, plan->head_dim, s); });
+        if (e != hipSuccess) return fail_hip(e, "backward D launch");
+    }
+    p.block_items = plan->block_items[HSPMD_LIST_DQ];
+    e = timed_launch(2, s, [&] { return hspmd::launch_bwd_dq(p, plan->head_dim, plan->count[HSPMD_LIST_DQ], true, s); });
+    if (e != hipSuccess) return fail_hip(e, "block backward dQ launch");
+    p.block_items = plan->block_items[HSPMD_LIST_DKV];
+    e = timed_launch(3, s, [&] { return hspmd::launch_bwd_dkv(p, plan->head_dim, plan->count[HSPMD_LIST_DKV], true, s); });
+    if (e != hipSuccess) return fail_hip(e, "block backward dK/dV launch");
     return HSPMD_OK;
 }
 

@@ -14,8 +14,10 @@ struct FwdParams {
     uint16_t* o;
     float* lse;
     const hspmd_work_item* items;
+    const hspmd_block_item* block_items;   // block variant only (items is then unused)
+    float* o_f32;                  // block variant only: partial O as fp32 [Tq, Hq, d] (o is then unused)
     int64_t q_stride, kv_stride;   // token strides in elements
-    int64_t total_tokens;
+    int64_t total_tokens;          // query tokens (rows of lse)
     int32_t q_heads, group;
     float scale_log2;              // softmax_scale * log2(e)
 };
@@ -34,18 +36,36 @@ struct BwdParams {
     void* dk;
     void* dv;
     const hspmd_work_item* items;
+    const hspmd_block_item* block_items;   // block variant only (items is then unused)
     int64_t q_stride, kv_stride;
-    int64_t total_tokens;
+    int64_t total_tokens;          // query tokens (rows of lse, D)
     int32_t q_heads, kv_heads, group;
     int32_t grad_f32;              // 1: gradients are fp32, 0: bf16
+    int32_t dq_accumulate;         // block variant only: dq += this block's share (fp32) instead of dq = ...
     float scale;                   // softmax_scale
     float scale_log2;              // softmax_scale * log2(e)
 };
 
-hipError_t launch_fwd(const FwdParams& p, int head_dim, int64_t num_items, hipStream_t stream);
+// `block`: the items are hspmd_block_item (separate query / key chunks, shifted causal mask)
+hipError_t launch_fwd(const FwdParams& p, int head_dim, int64_t num_items, bool block, hipStream_t stream);
 hipError_t launch_bwd_dsum(const BwdParams& p, int head_dim, hipStream_t stream);
-hipError_t launch_bwd_dq(const BwdParams& p, int head_dim, int64_t num_items, hipStream_t stream);
-hipError_t launch_bwd_dkv(const BwdParams& p, int head_dim, int64_t num_items, hipStream_t stream);
+hipError_t launch_bwd_dq(const BwdParams& p, int head_dim, int64_t num_items, bool block, hipStream_t stream);
+hipError_t launch_bwd_dkv(const BwdParams& p, int head_dim, int64_t num_items, bool block, hipStream_t stream);
+
+// merge of two partial results of the same rows over disjoint key sets (fp32 O [T, Hq, d], LSE [Hq, T]):
+// out = a (+) b; out may alias a.  out_bf16 (may be NULL) also receives the merged O rounded to bf16.
+struct MergeParams {
+    const float* o_a;
+    const float* lse_a;
+    const float* o_b;
+    const float* lse_b;
+    float* o_out;
+    float* lse_out;
+    uint16_t* o_out_bf16;
+    int64_t total_tokens;
+    int32_t q_heads, head_dim;
+};
+hipError_t launch_merge(const MergeParams& p, hipStream_t stream);
 
 // matrix-core rate probe: `grid` workgroups of kProbeThreads threads, each wave issues 16 * rounds MFMAs and
 // every thread writes one float to out[grid * kProbeThreads]

@@ -49,14 +49,77 @@ int64_t item_cost(hspmd_list_kind kind, int32_t seq_len, int32_t tile, int32_t g
     return ceil_div(last_key, kFwdKTile);
 }
 
-namespace {
-struct Segment {
-    int64_t cost = 0;
-    int64_t first_cost = 0;
-    int64_t order = 0;                 // creation index: keeps ties deterministic
-    std::vector<hspmd_work_item> items;
-};
-}  // namespace
+// Steps 2-5 of the placement, shared by the packed and the block lists: cut chains into segments, assign the
+// segments to queues by the longest-processing-time rule, order each queue, interleave the queues.
+template <typename Item, typename Cost>
+static std::vector<Item> place_chains(std::vector<std::vector<Item>>& chains, int64_t total_cost, int32_t num_queues,
+                                      Cost cost_of, Item pad) {
+    struct Seg {
+        int64_t cost = 0;
+        int64_t first_cost = 0;
+        int64_t order = 0;                 // creation index: keeps ties deterministic
+        std::vector<Item> items;
+    };
+    if (chains.empty()) return {};
+    // 2. cut chains into segments no heavier than 1/(4 * queues) of the total
+    const int64_t cap = std::max<int64_t>(1, total_cost / ((int64_t)num_queues * 4));
+    std::vector<Seg> segments;
+    for (auto& chain : chains) {
+        Seg seg;
+        for (const auto& it : chain) {
+            const int64_t c = cost_of(it);
+            if (!seg.items.empty() && seg.cost + c > cap) {
+                seg.order = (int64_t)segments.size();
+                segments.push_back(std::move(seg));
+                seg = Seg();
+            }
+            if (seg.items.empty()) seg.first_cost = c;
+            seg.items.push_back(it);
+            seg.cost += c;
+        }
+        if (!seg.items.empty()) {
+            seg.order = (int64_t)segments.size();
+            segments.push_back(std::move(seg));
+        }
+    }
+
+    // 3. longest-processing-time assignment of segments to queues
+    std::vector<size_t> by_cost(segments.size());
+    std::iota(by_cost.begin(), by_cost.end(), 0);
+    std::stable_sort(by_cost.begin(), by_cost.end(),
+                     [&](size_t a, size_t b) { return segments[a].cost > segments[b].cost; });
+    using Load = std::pair<int64_t, int32_t>;  // (load, queue)
+    std::priority_queue<Load, std::vector<Load>, std::greater<Load>> loads;
+    for (int32_t x = 0; x < num_queues; ++x) loads.push({0, x});
+    std::vector<std::vector<size_t>> queue_segments(num_queues);
+    for (size_t idx : by_cost) {
+        Load l = loads.top();
+        loads.pop();
+        queue_segments[l.second].push_back(idx);
+        l.first += segments[idx].cost;
+        loads.push(l);
+    }
+
+    // 4. inside a queue: segments by their most expensive item, then creation order
+    std::vector<std::vector<Item>> queues(num_queues);
+    size_t longest = 0;
+    for (int32_t x = 0; x < num_queues; ++x) {
+        auto& segs = queue_segments[x];
+        std::stable_sort(segs.begin(), segs.end(), [&](size_t a, size_t b) {
+            if (segments[a].first_cost != segments[b].first_cost) return segments[a].first_cost > segments[b].first_cost;
+            return segments[a].order < segments[b].order;
+        });
+        for (size_t idx : segs)
+            queues[x].insert(queues[x].end(), segments[idx].items.begin(), segments[idx].items.end());
+        longest = std::max(longest, queues[x].size());
+    }
+
+    // 5. interleave: slot p belongs to queue p % num_queues; pad short queues
+    std::vector<Item> out(longest * (size_t)num_queues, pad);
+    for (int32_t x = 0; x < num_queues; ++x)
+        for (size_t i = 0; i < queues[x].size(); ++i) out[i * (size_t)num_queues + (size_t)x] = queues[x][i];
+    return out;
+}
 
 // The two orders without placement: used only to measure what the default order buys.
 static std::vector<hspmd_work_item> build_plain_list(hspmd_list_kind kind, const int32_t* cu, int32_t num_seqs,
@@ -104,66 +167,81 @@ std::vector<hspmd_work_item> build_work_list(hspmd_list_kind kind, const int32_t
             chains.push_back(std::move(chain));
         }
     }
-    if (chains.empty()) return {};
+    return place_chains<hspmd_work_item>(
+        chains, total_cost, num_queues, [&](const hspmd_work_item& it) { return item_cost(kind, it.seq_len, it.tile, group); },
+        hspmd_work_item{0, 0, -1, 0});
+}
 
-    // 2. cut chains into segments no heavier than 1/(4 * queues) of the total
-    const int64_t cap = std::max<int64_t>(1, total_cost / ((int64_t)num_queues * 4));
-    std::vector<Segment> segments;
-    for (auto& chain : chains) {
-        Segment seg;
-        for (const auto& it : chain) {
-            const int64_t c = item_cost(kind, it.seq_len, it.tile, group);
-            if (!seg.items.empty() && seg.cost + c > cap) {
-                seg.order = (int64_t)segments.size();
-                segments.push_back(std::move(seg));
-                seg = Segment();
+// ------------------------------------------------------------------------------ block variant
+std::string check_block_pack(const int32_t* cu_q, const int32_t* cu_k, const int32_t* q_pos, const int32_t* k_pos,
+                             int32_t num_seqs, int32_t hq, int32_t hkv) {
+    if (!cu_q || !cu_k) return "cu_seqlens is NULL";
+    if (num_seqs < 0) return "num_seqs is negative";
+    if (num_seqs > 0 && (!q_pos || !k_pos)) return "chunk positions are NULL";
+    if (hq <= 0 || hkv <= 0) return "head counts must be positive";
+    if (hq % hkv != 0) return "local_q_heads must be a multiple of local_kv_heads (cut an uneven share on KV-group boundaries)";
+    if (cu_q[0] != 0 || cu_k[0] != 0) return "cu_seqlens[0] must be 0";
+    for (int32_t i = 0; i < num_seqs; ++i) {
+        if (cu_q[i + 1] < cu_q[i] || cu_k[i + 1] < cu_k[i]) return "cu_seqlens must be non-decreasing";
+        if (q_pos[i] < 0 || k_pos[i] < 0) return "chunk positions must be non-negative";
+        // positions of the last row / key must stay in int32 together with the tile arithmetic
+        if ((int64_t)q_pos[i] + (cu_q[i + 1] - cu_q[i]) > (int64_t)1 << 30 ||
+            (int64_t)k_pos[i] + (cu_k[i + 1] - cu_k[i]) > (int64_t)1 << 30)
+            return "chunk position + length above 2^30";
+    }
+    return std::string();
+}
+
+int64_t block_item_cost(hspmd_list_kind kind, const hspmd_block_item& it, int32_t group) {
+    if (kind == HSPMD_LIST_DKV) {
+        // rows r >= key0 - offset see the tile's first key
+        if ((int64_t)it.tile * kDkvKTile >= it.k_len) return 0;
+        const int64_t first_row = std::max<int64_t>(0, (int64_t)it.tile * kDkvKTile - it.offset);
+        const int64_t first_qt = first_row / kDkvQTile;
+        const int64_t n_qt = ceil_div(it.q_len, kDkvQTile);
+        return std::max<int64_t>(0, n_qt - first_qt) * group;
+    }
+    if ((int64_t)it.tile * kFwdQTile >= it.q_len) return 0;
+    const int64_t last_row = std::min<int64_t>(it.q_len, (int64_t)(it.tile + 1) * kFwdQTile);   // exclusive
+    const int64_t kv_end = std::max<int64_t>(0, std::min<int64_t>(it.k_len, last_row + it.offset));
+    return ceil_div(kv_end, kFwdKTile);
+}
+
+std::vector<hspmd_block_item> build_block_list(hspmd_list_kind kind, const int32_t* cu_q, const int32_t* cu_k,
+                                               const int32_t* q_pos, const int32_t* k_pos, int32_t num_seqs,
+                                               int32_t hq, int32_t hkv, int32_t num_queues) {
+    const int32_t group = hq / hkv;
+    std::vector<std::vector<hspmd_block_item>> chains;
+    int64_t total_cost = 0;
+    for (int32_t s = 0; s < num_seqs; ++s) {
+        const int32_t q_len = cu_q[s + 1] - cu_q[s], k_len = cu_k[s + 1] - cu_k[s];
+        const int32_t rows = (kind == HSPMD_LIST_DKV) ? k_len : q_len;     // rows of the outputs the list owns
+        if (rows <= 0) continue;
+        const int tile_rows = (kind == HSPMD_LIST_DKV) ? kDkvKTile : kFwdQTile;
+        const int32_t n_tiles = (int32_t)ceil_div(rows, tile_rows);
+        const hspmd_block_item proto{cu_q[s], q_len, cu_k[s], k_len, q_pos[s] - k_pos[s], 0, 0, 0};
+        for (int32_t g = 0; g < hkv; ++g) {
+            std::vector<hspmd_block_item> chain;
+            auto add = [&](int32_t tile, int32_t head) {
+                hspmd_block_item it = proto;
+                it.tile = tile;
+                it.head = head;
+                chain.push_back(it);
+            };
+            if (kind == HSPMD_LIST_DKV) {
+                for (int32_t t = 0; t < n_tiles; ++t) add(t, g);
+            } else {
+                for (int32_t t = n_tiles - 1; t >= 0; --t)
+                    for (int32_t h = g * group; h < (g + 1) * group; ++h) add(t, h);
             }
-            if (seg.items.empty()) seg.first_cost = c;
-            seg.items.push_back(it);
-            seg.cost += c;
-        }
-        if (!seg.items.empty()) {
-            seg.order = (int64_t)segments.size();
-            segments.push_back(std::move(seg));
+            // most expensive first inside a chain (with a shift the cost is still monotone in the tile index)
+            for (const auto& it : chain) total_cost += block_item_cost(kind, it, group);
+            chains.push_back(std::move(chain));
         }
     }
-
-    // 3. longest-processing-time assignment of segments to queues
-    std::vector<size_t> by_cost(segments.size());
-    std::iota(by_cost.begin(), by_cost.end(), 0);
-    std::stable_sort(by_cost.begin(), by_cost.end(),
-                     [&](size_t a, size_t b) { return segments[a].cost > segments[b].cost; });
-    using Load = std::pair<int64_t, int32_t>;  // (load, queue)
-    std::priority_queue<Load, std::vector<Load>, std::greater<Load>> loads;
-    for (int32_t x = 0; x < num_queues; ++x) loads.push({0, x});
-    std::vector<std::vector<size_t>> queue_segments(num_queues);
-    for (size_t idx : by_cost) {
-        Load l = loads.top();
-        loads.pop();
-        queue_segments[l.second].push_back(idx);
-        l.first += segments[idx].cost;
-        loads.push(l);
-    }
-
-    // 4. inside a queue: segments by their most expensive item, then creation order
-    std::vector<std::vector<hspmd_work_item>> queues(num_queues);
-    size_t longest = 0;
-    for (int32_t x = 0; x < num_queues; ++x) {
-        auto& segs = queue_segments[x];
-        std::stable_sort(segs.begin(), segs.end(), [&](size_t a, size_t b) {
-            if (segments[a].first_cost != segments[b].first_cost) return segments[a].first_cost > segments[b].first_cost;
-            return segments[a].order < segments[b].order;
-        });
-        for (size_t idx : segs)
-            queues[x].insert(queues[x].end(), segments[idx].items.begin(), segments[idx].items.end());
-        longest = std::max(longest, queues[x].size());
-    }
-
-    // 5. interleave: slot p belongs to queue p % num_queues; pad short queues
-    std::vector<hspmd_work_item> out(longest * (size_t)num_queues, hspmd_work_item{0, 0, -1, 0});
-    for (int32_t x = 0; x < num_queues; ++x)
-        for (size_t i = 0; i < queues[x].size(); ++i) out[i * (size_t)num_queues + (size_t)x] = queues[x][i];
-    return out;
+    return place_chains<hspmd_block_item>(
+        chains, total_cost, num_queues, [&](const hspmd_block_item& it) { return block_item_cost(kind, it, group); },
+        hspmd_block_item{0, 0, 0, 0, 0, -1, 0, 0});
 }
 
 }  // namespace hspmd

@@ -26,4 +26,18 @@ std::vector<hspmd_work_item> build_work_list(hspmd_list_kind kind, const int32_t
                                              int32_t hq, int32_t hkv, int32_t num_queues,
                                              hspmd_order order = HSPMD_ORDER_XCD_COST);
 
+// ---- block variant (one step of context-parallel attention): per sequence a query chunk and a key chunk
+// with positions inside the sequence; key j is visible to row r iff j <= r + (q_pos - k_pos).
+std::string check_block_pack(const int32_t* cu_q, const int32_t* cu_k, const int32_t* q_pos, const int32_t* k_pos,
+                             int32_t num_seqs, int32_t hq, int32_t hkv);
+
+// Cost (number of inner steps) of one block item; 0 when the item only writes zeros.
+int64_t block_item_cost(hspmd_list_kind kind, const hspmd_block_item& item, int32_t group);
+
+// Launch-ordered list of the block variant: same placement rules as build_work_list.  Every tile that owns
+// output rows gets an item, also when nothing is visible to it (it then writes zeros).
+std::vector<hspmd_block_item> build_block_list(hspmd_list_kind kind, const int32_t* cu_q, const int32_t* cu_k,
+                                               const int32_t* q_pos, const int32_t* k_pos, int32_t num_seqs,
+                                               int32_t hq, int32_t hkv, int32_t num_queues);
+
 }  // namespace hspmd

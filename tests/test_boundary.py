@@ -180,3 +180,74 @@ def test_plan_create_validates_before_touching_the_gpu():
     assert lib.hspmd_attn_plan_destroy(None) == 0
     assert lib.hspmd_attn_varlen_fwd(None, None, None, None, 0, 0, 0.0, None, None, None) == 1
     assert lib.hspmd_attn_plan_total_tokens(None) == -1 and lib.hspmd_attn_bwd_workspace_bytes(None) == 0
+
+
+# ------------------------------------------------------------------------------ block variant (host logic)
+def _block_cost(kind, it, group):
+    """Inner steps of a block item, from the definition: key j visible to row r iff j <= r + offset."""
+    q_len, k_len, off, tile = int(it[1]), int(it[3]), int(it[4]), int(it[5])
+    if kind == A.LIST_DKV:
+        rows = [r for r in range(q_len) if r + off >= tile * 128]          # rows that see the tile's first key
+        if tile * 128 >= k_len or not rows:
+            return 0
+        return (-(-q_len // 64) - rows[0] // 64) * group
+    last = min(q_len, (tile + 1) * 128) - 1
+    keys = max(0, min(k_len, last + off + 1))
+    return -(-keys // 64) if tile * 128 < q_len else 0
+
+
+@pytest.mark.parametrize("kind", [A.LIST_FWD, A.LIST_DQ, A.LIST_DKV])
+def test_block_work_list_invariants(kind):
+    ql = [300, 129, 64, 200, 0, 77, 1, 2000]
+    kl = [200, 257, 130, 128, 90, 0, 300, 1500]
+    qp = [100, 0, 700, 0, 5, 9, 299, 1000]
+    kp = [0, 64, 0, 200, 0, 0, 0, 0]
+    cq, ck = np.concatenate([[0], np.cumsum(ql)]), np.concatenate([[0], np.cumsum(kl)])
+    hq, hkv = 4, 2
+    items = A.block_schedule(kind, cq, ck, qp, kp, hq, hkv)
+    assert items.shape[1] == 8 and items.shape[0] % 8 == 0
+    real = items[items[:, 5] >= 0]
+    assert np.all(items[items[:, 5] < 0][:, 5] == -1) and np.all(real[:, 7] == 0)
+    # every tile that owns output rows appears exactly once per head, with its sequence's geometry
+    expected = set()
+    for i in range(len(ql)):
+        rows, per = (kl[i], 128) if kind == A.LIST_DKV else (ql[i], 128)
+        heads = hkv if kind == A.LIST_DKV else hq
+        for t in range(-(-rows // per)):
+            for h in range(heads):
+                expected.add((int(cq[i]), ql[i], int(ck[i]), kl[i], qp[i] - kp[i], t, h))
+    got = [tuple(int(x) for x in r[:7]) for r in real]
+    assert len(got) == len(set(got)) and set(got) == expected
+    # queues (slots p % 8) are balanced by the cost from the definition
+    group = hq // hkv
+    loads = [sum(_block_cost(kind, it, group) for it in items[x::8] if it[5] >= 0) for x in range(8)]
+    heaviest = max(_block_cost(kind, it, group) for it in real)
+    assert max(loads) - min(loads) <= max(heaviest, sum(loads) // 32 + heaviest)
+
+
+def test_block_schedule_without_shift_matches_the_packed_schedule():
+    lengths = [300, 0, 1000, 64]
+    cu = np.concatenate([[0], np.cumsum(lengths)])
+    for kind in (A.LIST_FWD, A.LIST_DQ, A.LIST_DKV):
+        packed = A.schedule(kind, cu, 4, 2)
+        block = A.block_schedule(kind, cu, cu, [0] * 4, [0] * 4, 4, 2)
+        assert packed.shape[0] == block.shape[0]
+        real = block[:, 5] >= 0
+        assert np.array_equal(real, packed[:, 2] >= 0)
+        assert np.array_equal(block[real][:, [0, 1, 5, 6]], packed[real])
+        assert np.array_equal(block[real][:, [2, 3]], packed[real][:, [0, 1]]) and np.all(block[real][:, 4] == 0)
+
+
+def test_block_schedule_rejects_bad_arguments():
+    ok = ([0, 10], [0, 12], [3], [0], 2, 2)
+    A.block_schedule(A.LIST_FWD, *ok)
+    for bad in [([0, 10], [0, 12], [-1], [0], 2, 2), ([0, 10], [0, 12], [0], [-2], 2, 2),
+                ([1, 10], [0, 12], [0], [0], 2, 2), ([0, 10], [0, 12, 11], [0, 0], [0, 0], 2, 2),
+                ([0, 10], [0, 12], [0], [0], 3, 2), ([0, 10], [0, 12], [0], [0], 0, 0),
+                ([0, 10], [0, 12], [2 ** 30], [0], 2, 2)]:
+        with pytest.raises(A.HspmdError):
+            A.block_schedule(A.LIST_FWD, *bad)
+    with pytest.raises(A.HspmdError):
+        A.block_schedule(A.LIST_FWD, [0, 10], [0, 12], [0, 0], [0], 2, 2)      # arrays differ in length
+    with pytest.raises(A.HspmdError):
+        A.block_schedule(7, *ok)

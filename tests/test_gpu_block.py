@@ -1,0 +1,232 @@
+"""GPU parity of the block variant (one step of context-parallel attention) through the C ABI, against the
+fp64 block oracle and, for a whole emulated ring, against the packed oracle."""
+import math
+
+import numpy as np
+import pytest
+
+import hspmd_workloads as w
+import oracle
+from oracle import block as ob
+import gpu_util
+from gpu_util import LSE_ABS, assert_close, f64, to_dev
+
+pytestmark = pytest.mark.gpu
+
+
+def _bits(seed, name, T, h, d, scale=1.0):
+    return w.make_tensor(seed, name, T * h * d, scale).reshape(T, h, d)
+
+
+def _cu(lengths):
+    return np.concatenate([[0], np.cumsum(lengths)]).astype(np.int32)
+
+
+def _assert_lse(name, got, ref):
+    """-inf entries must match exactly; the finite ones to LSE_ABS."""
+    assert not np.isnan(got).any(), f"{name}: NaN"
+    inf_ref = np.isneginf(ref)
+    assert np.array_equal(np.isneginf(got), inf_ref), f"{name}: -inf pattern differs"
+    if (~inf_ref).any():
+        assert np.max(np.abs(got[~inf_ref] - ref[~inf_ref])) <= LSE_ABS, f"{name}: finite entries differ"
+
+
+class BlockRun:
+    def __init__(self, ql, kl, qp, kp, hq, hkv, d, seed, scale=0.0):
+        import torch
+        import paper_2504_20490_amd as A
+        self.A, self.torch = A, torch
+        self.geom = (list(ql), list(kl), list(qp), list(kp))
+        Tq, Tk = int(sum(ql)), int(sum(kl))
+        self.qb, self.kb, self.vb, self.dob = (_bits(seed, "q", Tq, hq, d), _bits(seed, "k", Tk, hkv, d),
+                                                _bits(seed, "v", Tk, hkv, d), _bits(seed, "do", Tq, hq, d))
+        self.plan = A.BlockPlan(_cu(ql), _cu(kl), qp, kp, hq, hkv, d)
+        self.q, self.k, self.v, self.do = (to_dev(x) for x in (self.qb, self.kb, self.vb, self.dob))
+        nan = float("nan")
+        self.o = torch.full((Tq, hq, d), nan, dtype=torch.float32, device="cuda")
+        self.lse = torch.full((hq, Tq), nan, dtype=torch.float32, device="cuda")
+        self.dq = torch.full((Tq, hq, d), nan, dtype=torch.float32, device="cuda")
+        self.dk = torch.full((Tk, hkv, d), nan, dtype=torch.float32, device="cuda")
+        self.dv = torch.full((Tk, hkv, d), nan, dtype=torch.float32, device="cuda")
+        self.ws = torch.empty(max(self.plan.bwd_workspace_bytes(), 16), dtype=torch.uint8, device="cuda")
+        self.scale = scale
+        self.s = scale if scale > 0 else 1.0 / math.sqrt(d)
+
+    def host(self, name):
+        return getattr(self, name).float().cpu().numpy().astype(np.float64)
+
+
+def _check_single_block(ql, kl, qp, kp, hq, hkv, d, seed, case):
+    """Forward of one block against the oracle; backward with the block's own (LSE, O) as the statistics of the whole
+    rows, i.e. as if this block were all there is (rows without a visible key keep LSE = -inf and must take no
+    part).  Statistics that differ from the block's own are exercised by the emulated ring below."""
+    gpu_util.CONTEXT["case"] = case
+    r = BlockRun(ql, kl, qp, kp, hq, hkv, d, seed)
+    torch, A = r.torch, r.A
+    A.attn_block_fwd(r.plan, r.q, r.k, r.v, r.o, r.lse)
+    torch.cuda.synchronize()
+    ro, rl = ob.block_fwd(f64(r.qb), f64(r.kb), f64(r.vb), *r.geom, r.s)
+    assert_close("O partial", r.host("o"), ro)
+    _assert_lse("LSE partial", r.host("lse"), rl)
+    # rows without a visible key: exactly zero
+    assert np.all(r.host("o")[np.isneginf(rl).T] == 0.0)
+
+    lse_rows = rl                                                      # whole-row statistics handed to backward
+    o_rows_bits = w.bf16_bits(ro.astype(np.float32))
+    lse_dev = torch.from_numpy(lse_rows.astype(np.float32)).cuda()
+    o_dev = to_dev(o_rows_bits)
+    A.attn_block_bwd(r.plan, r.q, r.k, r.v, o_dev, lse_dev, r.do, r.dq, r.dk, r.dv, r.ws)
+    torch.cuda.synchronize()
+    dsum = ob.row_dot(f64(o_rows_bits), f64(r.dob))
+    lse_ref = lse_dev.cpu().numpy().astype(np.float64)
+    lse_ref = np.where(np.isneginf(lse_ref), np.inf, lse_ref)          # exp(S - inf) = 0: such rows take no part
+    rdq, rdk, rdv = ob.block_bwd(f64(r.qb), f64(r.kb), f64(r.vb), f64(r.dob), lse_ref, dsum, *r.geom, r.s)
+    assert_close("dQ share", r.host("dq"), rdq)
+    assert_close("dK block", r.host("dk"), rdk)
+    assert_close("dV block", r.host("dv"), rdv)
+    return r, (rdq, rdk, rdv), (o_dev, lse_dev)
+
+
+def test_mixed_geometries_d128():
+    """One pack whose sequences cover the cases: shifted diagonal inside the block (both signs), block wholly in
+    the past, wholly in the future, empty query chunk, empty key chunk, ragged tails, a single row / key."""
+    ql = [300, 129, 64, 200, 0, 77, 1, 260]
+    kl = [200, 257, 130, 128, 90, 0, 300, 1]
+    qp = [100, 0, 700, 0, 5, 9, 299, 0]
+    kp = [0, 64, 0, 200, 0, 0, 0, 130]
+    _check_single_block(ql, kl, qp, kp, 4, 2, 128, 21, "block_mixed_d128")
+
+
+def test_mixed_geometries_d64_accumulate_and_reuse():
+    ql, kl, qp, kp = [150, 90, 333], [400, 31, 200], [250, 0, 64], [0, 40, 0]
+    r, (rdq, rdk, rdv), (o_dev, lse_dev) = _check_single_block(ql, kl, qp, kp, 2, 2, 64, 22, "block_mixed_d64")
+    torch, A = r.torch, r.A
+    # a second call that reuses the statistics and accumulates into dq: dq doubles, dk / dv are rewritten
+    r.dk.fill_(float("nan")); r.dv.fill_(float("nan"))
+    before = r.dq.clone()
+    A.attn_block_bwd(r.plan, r.q, r.k, r.v, None, None, r.do, r.dq, r.dk, r.dv, r.ws, dq_accumulate=True,
+                     reuse_statistics=True)
+    torch.cuda.synchronize()
+    assert torch.equal(r.dq, 2 * before)
+    assert_close("dK block (reused statistics)", r.host("dk"), rdk)
+    assert_close("dV block (reused statistics)", r.host("dv"), rdv)
+
+
+@pytest.mark.parametrize("hq,hkv,d", [(4, 2, 128), (2, 2, 64)])
+def test_emulated_ring_reproduces_whole_attention(hq, hkv, d):
+    """Every sequence of a pack is cut into 3 chunks by position; 'device' c holds chunk c of every sequence and
+    meets the key chunks one after the other (block forward + merge, block backward with dq accumulation).  The
+    merged O / LSE, the summed dQ and the per-chunk dK / dV summed over the devices equal whole-sequence attention
+    (packed fp64 oracle)."""
+    import torch
+    import paper_2504_20490_amd as A
+    gpu_util.CONTEXT["case"] = f"block_ring_d{d}"
+    lengths = [700, 1500, 260, 97]
+    n_dev = 3
+    T = sum(lengths)
+    seed = 31
+    qb, kb, vb, dob = _bits(seed, "q", T, hq, d), _bits(seed, "k", T, hkv, d), _bits(seed, "v", T, hkv, d), _bits(seed, "do", T, hq, d)
+    s = 1.0 / math.sqrt(d)
+    ro, rl = oracle.attn_fwd(f64(qb), f64(kb), f64(vb), lengths, s)
+    rdq, rdk, rdv = oracle.attn_bwd(f64(qb), f64(kb), f64(vb), f64(dob), lengths, s)
+    cu = np.concatenate([[0], np.cumsum(lengths)])
+    # chunk c of sequence i: positions [edges[i][c], edges[i][c+1]) -- uneven on purpose, one chunk can be empty
+    edges = [[0, L // 4, (2 * L) // 3, L] for L in lengths]
+    edges[3] = [0, 0, 50, 97]
+    tok = lambda c: np.concatenate([np.arange(cu[i] + edges[i][c], cu[i] + edges[i][c + 1]) for i in range(len(lengths))])
+    lens = lambda c: [edges[i][c + 1] - edges[i][c] for i in range(len(lengths))]
+    pos = lambda c: [edges[i][c] for i in range(len(lengths))]
+    dk_total = np.zeros((T, hkv, d)); dv_total = np.zeros((T, hkv, d))
+    for c in range(n_dev):
+        tq = tok(c)
+        q, do = to_dev(qb[tq]), to_dev(dob[tq])
+        Tq = len(tq)
+        o_acc = torch.zeros(Tq, hq, d, dtype=torch.float32, device="cuda")
+        lse_acc = torch.full((hq, Tq), float("-inf"), dtype=torch.float32, device="cuda")
+        o_part = torch.empty_like(o_acc); lse_part = torch.empty_like(lse_acc)
+        o_bf16 = torch.full((Tq, hq, d), float("nan"), dtype=torch.bfloat16, device="cuda")
+        plans, kvs = [], []
+        for kc in range(n_dev):
+            tk = tok(kc)
+            k, v = to_dev(kb[tk]), to_dev(vb[tk])
+            plan = A.BlockPlan(gpu_util_cu(lens(c)), gpu_util_cu(lens(kc)), pos(c), pos(kc), hq, hkv, d)
+            A.attn_block_fwd(plan, q, k, v, o_part, lse_part)
+            A.attn_merge(o_acc, lse_acc, o_part, lse_part, o_acc, lse_acc, o_bf16 if kc == n_dev - 1 else None)
+            plans.append(plan); kvs.append((tk, k, v))
+        torch.cuda.synchronize()
+        assert_close(f"O merged, device {c}", o_bf16.float().cpu().numpy().astype(np.float64), ro[tq])
+        got_lse = lse_acc.cpu().numpy().astype(np.float64)
+        assert np.max(np.abs(got_lse - rl[:, tq])) <= LSE_ABS
+        dq = torch.full((Tq, hq, d), float("nan"), dtype=torch.float32, device="cuda")
+        ws = torch.empty(max(plans[0].bwd_workspace_bytes(), 16), dtype=torch.uint8, device="cuda")
+        for kc, (plan, (tk, k, v)) in enumerate(zip(plans, kvs)):
+            dk = torch.full((len(tk), hkv, d), float("nan"), dtype=torch.float32, device="cuda")
+            dv = torch.full_like(dk, float("nan"))
+            A.attn_block_bwd(plan, q, k, v, o_bf16, lse_acc, do, dq, dk, dv, ws, dq_accumulate=kc > 0,
+                             reuse_statistics=kc > 0)
+            torch.cuda.synchronize()
+            got_dk, got_dv = dk.cpu().numpy().astype(np.float64), dv.cpu().numpy().astype(np.float64)
+            assert not np.isnan(got_dk).any() and not np.isnan(got_dv).any()
+            dk_total[tk] += got_dk
+            dv_total[tk] += got_dv
+        assert_close(f"dQ summed over blocks, device {c}", dq.cpu().numpy().astype(np.float64), rdq[tq])
+    assert_close("dK summed over devices", dk_total, rdk)
+    assert_close("dV summed over devices", dv_total, rdv)
+
+
+def gpu_util_cu(lengths):
+    return _cu(lengths)
+
+
+def test_block_equals_packed_kernels_when_there_is_no_shift():
+    """Query chunk = key chunk = whole sequence: the block path must reproduce the packed path (O after rounding,
+    LSE and gradients to the parity tolerance, since the two instantiations differ only in index arithmetic)."""
+    import torch
+    import paper_2504_20490_amd as A
+    lengths = [200, 0, 513, 64]
+    hq, hkv, d = 4, 2, 128
+    T = sum(lengths)
+    qb, kb, vb, dob = _bits(41, "q", T, hq, d), _bits(41, "k", T, hkv, d), _bits(41, "v", T, hkv, d), _bits(41, "do", T, hq, d)
+    q, k, v, do = (to_dev(x) for x in (qb, kb, vb, dob))
+    cu = _cu(lengths)
+    plan = A.Plan(cu, hq, hkv, d)
+    o = torch.empty(T, hq, d, dtype=torch.bfloat16, device="cuda"); lse = torch.empty(hq, T, dtype=torch.float32, device="cuda")
+    A.attn_varlen_fwd(plan, q, k, v, o, lse)
+    bplan = A.BlockPlan(cu, cu, [0] * 4, [0] * 4, hq, hkv, d)
+    o32 = torch.empty(T, hq, d, dtype=torch.float32, device="cuda"); lse2 = torch.empty_like(lse)
+    A.attn_block_fwd(bplan, q, k, v, o32, lse2)
+    torch.cuda.synchronize()
+    assert torch.equal(o32.to(torch.bfloat16), o)
+    assert torch.equal(lse2, lse)
+    ws = torch.empty(plan.bwd_workspace_bytes(), dtype=torch.uint8, device="cuda")
+    g = lambda h: torch.empty(T, h, d, dtype=torch.float32, device="cuda")
+    dq, dk, dv, dq2, dk2, dv2 = g(hq), g(hkv), g(hkv), g(hq), g(hkv), g(hkv)
+    A.attn_varlen_bwd(plan, q, k, v, o, lse, do, dq, dk, dv, ws, grad_dtype=A.GRAD_F32)
+    A.attn_block_bwd(bplan, q, k, v, o, lse, do, dq2, dk2, dv2, ws)
+    torch.cuda.synchronize()
+    assert torch.equal(dq2, dq) and torch.equal(dk2, dk) and torch.equal(dv2, dv)
+
+
+def test_block_validation():
+    import torch
+    import paper_2504_20490_amd as A
+    with pytest.raises(A.HspmdError):
+        A.BlockPlan([0, 10], [0, 10], [-1], [0], 2, 2, 64)           # negative position
+    with pytest.raises(A.HspmdError):
+        A.BlockPlan([0, 10], [0, 10, 20], [0], [0], 2, 2, 64)        # arrays differ
+    with pytest.raises(A.HspmdError):
+        A.BlockPlan([0, 10], [0, 10], [0], [0], 3, 2, 64)            # heads not a whole number of groups
+    with pytest.raises(A.HspmdError):
+        A.BlockPlan([0, 10], [0, 10], [0], [0], 2, 2, 96)            # head_dim
+    bplan = A.BlockPlan([0, 10], [0, 12], [2], [0], 2, 2, 64)
+    plan = A.Plan([0, 10], 2, 2, 64)
+    assert bplan.total_tokens == 10 and bplan.total_kv_tokens == 12
+    q = torch.zeros(10, 2, 64, dtype=torch.bfloat16, device="cuda"); k = torch.zeros(12, 2, 64, dtype=torch.bfloat16, device="cuda")
+    o32 = torch.zeros(10, 2, 64, dtype=torch.float32, device="cuda"); lse = torch.zeros(2, 10, dtype=torch.float32, device="cuda")
+    o16 = torch.zeros(10, 2, 64, dtype=torch.bfloat16, device="cuda")
+    with pytest.raises(A.HspmdError):
+        A.attn_block_fwd(plan, q, k, k, o32, lse)                    # packed plan in a block call
+    with pytest.raises(A.HspmdError):
+        A.attn_varlen_fwd(bplan, q, q, q, o16, lse)                  # block plan in a packed call
+    with pytest.raises(A.HspmdError):
+        A.attn_merge(o32, lse, o32, lse, o32, lse)                   # output aliases operand b
