@@ -76,6 +76,154 @@ def cpu_baseline(cfg, lengths, q, k, v, do):
                       f"fwd+bwd in fp64, {dt:.1f} s"}
 
 
+def run_ring(args) -> int:
+    """One rank of an emulated context-parallel ring: every sequence of the pack is cut into N chunks by position,
+    this rank owns chunk `--ring-rank` of every sequence as queries and meets the N key/value chunks one after the
+    other (block forward + merge; block backward with dQ accumulation).  A step = N block plans (host) + all of
+    that.  The sends and receives of a real ring are not part of it."""
+    import numpy as np
+    import torch
+    import hspmd_workloads as w
+    import paper_2504_20490_amd as A
+
+    if not torch.cuda.is_available():
+        print("bench.py needs a GPU", file=sys.stderr)
+        return 2
+    A.load_library()
+    cfg = w.config_by_name(args.workload)
+    lengths, q, k, v, do = w.make_inputs(cfg)
+    hq, hkv, d = cfg.q_heads, cfg.kv_heads, cfg.head_dim
+    n, rank = args.ring, (args.ring - 1 if args.ring_rank < 0 else args.ring_rank)
+    if not 0 <= rank < n:
+        print("--ring-rank must be in [0, --ring)", file=sys.stderr)
+        return 2
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    cu = np.concatenate([[0], np.cumsum(lengths)])
+    edges = [[(L * c) // n for c in range(n + 1)] for L in lengths]
+    tok = lambda c: np.concatenate([np.arange(cu[i] + edges[i][c], cu[i] + edges[i][c + 1]) for i in range(len(lengths))])
+    lens = lambda c: [edges[i][c + 1] - edges[i][c] for i in range(len(lengths))]
+    pos = lambda c: [edges[i][c] for i in range(len(lengths))]
+    cuof = lambda ls: np.concatenate([[0], np.cumsum(ls)]).astype(np.int32)
+
+    def bf(bits):
+        return torch.from_numpy(np.ascontiguousarray(bits).view(np.int16)).view(torch.bfloat16).to(dev)
+
+    tq_idx = tok(rank)
+    Tq = len(tq_idx)
+    tq, tdo = bf(q[tq_idx]), bf(do[tq_idx])
+    kv = [(bf(k[tok(c)]), bf(v[tok(c)])) for c in range(n)]
+    o_acc = torch.empty(Tq, hq, d, dtype=torch.float32, device=dev)
+    lse_acc = torch.empty(hq, Tq, dtype=torch.float32, device=dev)
+    o_part, lse_part = torch.empty_like(o_acc), torch.empty_like(lse_acc)
+    o_bf16 = torch.empty(Tq, hq, d, dtype=torch.bfloat16, device=dev)
+    dq = torch.empty(Tq, hq, d, dtype=torch.float32, device=dev)
+    dkv = [(torch.empty(kk.shape, dtype=torch.float32, device=dev), torch.empty(kk.shape, dtype=torch.float32, device=dev))
+           for kk, _ in kv]
+    ws = torch.empty(2 * hq * Tq * 4 + 256, dtype=torch.uint8, device=dev)
+    stream = torch.cuda.current_stream()
+
+    def step():
+        plans = [A.BlockPlan(cuof(lens(rank)), cuof(lens(c)), pos(rank), pos(c), hq, hkv, d, stream.cuda_stream)
+                 for c in range(n)]
+        for c, plan in enumerate(plans):
+            if c == 0:
+                A.attn_block_fwd(plan, tq, kv[c][0], kv[c][1], o_acc, lse_acc, stream=stream)
+                if n == 1:
+                    A.attn_merge(o_acc, lse_acc, o_acc, lse_acc, o_part, lse_part, o_bf16, stream=stream)
+            else:
+                A.attn_block_fwd(plan, tq, kv[c][0], kv[c][1], o_part, lse_part, stream=stream)
+                A.attn_merge(o_acc, lse_acc, o_part, lse_part, o_acc, lse_acc, o_bf16 if c == n - 1 else None, stream=stream)
+        for c, plan in enumerate(plans):
+            A.attn_block_bwd(plan, tq, kv[c][0], kv[c][1], o_bf16, lse_acc, tdo, dq, dkv[c][0], dkv[c][1], ws,
+                             dq_accumulate=c > 0, reuse_statistics=c > 0, stream=stream)
+        return plans
+
+    keep = []
+    for _ in range(args.warmup):
+        keep.extend(step())
+    torch.cuda.synchronize()
+    for p in keep:
+        p.destroy()
+    keep = []
+    A.profile_enable(True)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        keep.extend(step())
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    A.profile_enable(False)
+    prof = A.profile_read()
+    for p in keep:
+        p.destroy()
+    probe = torch.empty(A.probe_scratch_bytes(), dtype=torch.uint8, device=dev)
+    mfma_measured = A.probe_mfma_tflops(probe, stream=stream)
+
+    # visible (row, key) pairs of this rank's rows: row at position p of its sequence sees p + 1 keys
+    pairs = sum(sum(range(edges[i][rank] + 1, edges[i][rank + 1] + 1)) for i in range(len(lengths)))
+    fwd = 4.0 * d * hq * pairs
+    ms_per_step = elapsed / args.steps * 1e3
+    tflops = 3.5 * fwd / (ms_per_step * 1e-3) / 1e12
+    kern = {name: (ms / max(args.steps, 1)) for name, (ms, cnt) in prof.items()}     # per step: all blocks of a step
+    dominant = max(GEMMS, key=lambda name: kern.get(name, 0.0))
+    achieved = GEMMS[dominant] * (fwd / 2.0) / (kern[dominant] * 1e-3) / 1e12 if kern[dominant] > 0 else 0.0
+    out = {
+        "metric": "context-parallel block step: varlen causal attn fwd+bwd TFLOP/s of one ring rank",
+        "value": round(tflops, 2), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"{cfg.name} cut into {n} chunks by position, rank {rank} (queries: chunk {rank} of every "
+                               f"sequence; keys: all {n} chunks in turn)", "query_tokens": Tq, "q_heads": hq, "kv_heads": hkv,
+                   "head_dim": d, "lengths": lengths, "visible_pairs_per_head": pairs, "fwd_useful_flops": fwd,
+                   "step": f"{n} block plans + {n} block fwd + merges + {n} block bwd (D once, dQ accumulated)"},
+        "pct_of_bf16_mfma_peak": round(100.0 * tflops / PEAK_BF16_TFLOPS, 2),
+        "kernel_ms_per_step": {name: round(ms, 4) for name, ms in kern.items()},
+        "roofline": {"bound": "mfma", "kernel": dominant, "achieved": round(achieved, 2), "peak": PEAK_BF16_TFLOPS,
+                     "unit": "TFLOP/s", "frac": round(achieved / PEAK_BF16_TFLOPS, 4), "traffic": None,
+                     "flops_per_launch": GEMMS[dominant] * (fwd / 2.0) / n,
+                     "measured_mfma_peak": round(mfma_measured, 1),
+                     "note": f"{GEMMS[dominant]} GEMMs over the rank's visible pairs; the {n} launches of a step "
+                             "together, timed with HIP events on the launch stream"},
+    }
+    if not args.no_cpu_baseline:
+        from oracle import block as ob
+        # bounded sample: the shortest sequences of the pack (up to a pair budget), 2 q heads of one KV group
+        f64 = lambda bits: w.bits_to_f32(bits).astype(np.float64)
+        order = sorted(range(len(lengths)), key=lambda i: lengths[i])
+        chosen, budget = [], 0
+        for i in order:
+            p_i = sum(range(edges[i][rank] + 1, edges[i][rank + 1] + 1))
+            if chosen and budget + p_i > 6.0e6:
+                break
+            chosen.append(i); budget += p_i
+        heads = min(hq, 2)
+        s = 1.0 / math.sqrt(d)
+        t1 = time.perf_counter()
+        for i in chosen:
+            rows = np.arange(cu[i] + edges[i][rank], cu[i] + edges[i][rank + 1])
+            qs, dos = f64(q[rows][:, :heads]), f64(do[rows][:, :heads])
+            o_sum = np.zeros((len(rows), heads, d)); l_sum = np.full((heads, len(rows)), -np.inf)
+            blocks = []
+            for c in range(n):
+                keys = np.arange(cu[i] + edges[i][c], cu[i] + edges[i][c + 1])
+                ks, vs = f64(k[keys][:, :1]), f64(v[keys][:, :1])
+                geom = ([len(rows)], [len(keys)], [edges[i][rank]], [edges[i][c]], s)
+                po, pl = ob.block_fwd(qs, ks, vs, *geom)
+                o_sum, l_sum = ob.merge(o_sum, l_sum, po, pl)
+                blocks.append((ks, vs, geom))
+            dsum = ob.row_dot(o_sum, dos)
+            for ks, vs, geom in blocks:
+                ob.block_bwd(qs, ks, vs, dos, l_sum, dsum, *geom)
+        dt = time.perf_counter() - t1
+        out["cpu_baseline"] = {"value": 3.5 * 4.0 * d * heads * budget / dt / 1e12, "unit": "TFLOP/s", "cores": 1,
+                               "kind": "oracle",
+                               "sample": f"block oracle (numpy fp64) on sequences {[lengths[i] for i in chosen]} of the "
+                                         f"same pack, {heads} q heads / 1 kv head, all {n} blocks fwd + merge + bwd, {dt:.1f} s"}
+    print(json.dumps(out))
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -90,11 +238,18 @@ def main() -> int:
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="before the steps, run one plain device copy of 1 GiB (a kernel of known HBM traffic "
                          "that scales the FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run)")
+    ap.add_argument("--ring", type=int, default=0,
+                    help="N > 0: measure the block variant instead: one rank of a context-parallel ring of N chunks "
+                         "(see run_ring); the default 0 measures the packed path")
+    ap.add_argument("--ring-rank", type=int, default=-1, help="which chunk the rank owns (default: the last, heaviest)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU's share of the batch on one GPU; --gpus above 1 is not part of this "
               "build (no collectives, no sharding across GPUs).", file=sys.stderr)
         return 2
+
+    if args.ring > 0:
+        return run_ring(args)
 
     import numpy as np
     import torch

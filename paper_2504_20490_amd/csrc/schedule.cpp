@@ -67,7 +67,9 @@ static std::vector<Item> place_chains(std::vector<std::vector<Item>>& chains, in
     for (auto& chain : chains) {
         Seg seg;
         for (const auto& it : chain) {
-            const int64_t c = cost_of(it);
+            // an item that only writes zeros (block variant) still occupies a workgroup slot: weight 1, so that
+            // such items spread over the queues instead of piling up in one
+            const int64_t c = std::max<int64_t>(1, cost_of(it));
             if (!seg.items.empty() && seg.cost + c > cap) {
                 seg.order = (int64_t)segments.size();
                 segments.push_back(std::move(seg));

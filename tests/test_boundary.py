@@ -251,3 +251,11 @@ def test_block_schedule_rejects_bad_arguments():
         A.block_schedule(A.LIST_FWD, [0, 10], [0, 12], [0, 0], [0], 2, 2)      # arrays differ in length
     with pytest.raises(A.HspmdError):
         A.block_schedule(7, *ok)
+
+
+def test_block_work_list_of_an_invisible_block_is_spread_over_the_queues():
+    """Key chunk wholly in the future: every item only writes zeros (cost 0), and the list must not grow."""
+    cq = [0, 3000]
+    items = A.block_schedule(A.LIST_FWD, cq, [0, 3000], [0], [5000], 4, 2)
+    real = int((items[:, 5] >= 0).sum())
+    assert real == 24 * 4 and items.shape[0] <= real + 8
