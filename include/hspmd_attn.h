@@ -205,6 +205,21 @@ hspmd_status hspmd_attn_varlen_bwd(const hspmd_attn_plan* plan, const void* q, c
                                    void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * Predicted kernel time (milliseconds, MI355X) of forward and backward of a pack on this library's
+ * kernels: the per-operator cost that the paper's planner needs when it dispatches mixed-length
+ * sequences to pipelines by a cost model evaluated on the CPU (Appendix "Scenario-specific Planning",
+ * mixed-length case).  Host only, no GPU needed; costs about as much as building the work lists.
+ * Model: each pass walks its work list; an item weighs (inner steps x a step time + a fixed time per
+ * item), a pass takes a launch time plus the weight of its heaviest XCD queue divided by the
+ * workgroups resident per XCD, and not less than its heaviest item; backward = D pass (an HBM
+ * stream) + dQ pass + dK/dV pass.  The coefficients are fitted to measured kernel times
+ * (paper_2504_20490_amd/fit_cost_model.py refits them): mean error 5-8 % at head_dim 128, up to
+ * 25-35 % on packs that take only a few hundred microseconds.  Host-side plan creation is not included.
+ */
+hspmd_status hspmd_attn_estimate_ms(const int32_t* cu_seqlens, int32_t num_seqs, int32_t local_q_heads,
+                                    int32_t local_kv_heads, int32_t head_dim, double* fwd_ms, double* bwd_ms);
+
+/*
  * ---- Block variant: one step of context-parallel attention on one device ----
  * The paper shards long sequences over devices (context parallelism) with ring-based send-receive
  * inside attention, wrapped in its fused ParallelAttn operator (Section 2.1, data sharding; system

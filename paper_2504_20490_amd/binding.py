@@ -89,6 +89,9 @@ def load_library():
                                           ctypes.c_float, vp, vp, vp, ctypes.c_int, vp, ctypes.c_size_t, vp]
     lib.hspmd_profile_enable.restype = ctypes.c_int
     lib.hspmd_profile_enable.argtypes = [ctypes.c_int32]
+    lib.hspmd_attn_estimate_ms.restype = ctypes.c_int
+    lib.hspmd_attn_estimate_ms.argtypes = [i32p, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32,
+                                           ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_double)]
     lib.hspmd_attn_block_schedule.restype = ctypes.c_int
     lib.hspmd_attn_block_schedule.argtypes = [ctypes.c_int, i32p, i32p, i32p, i32p, ctypes.c_int32, ctypes.c_int32,
                                               ctypes.c_int32, ctypes.c_int32, ctypes.POINTER(BlockItem),
@@ -338,3 +341,12 @@ def attn_block_bwd(plan: BlockPlan, q, k, v, o, lse, d_o, dq, dk, dv, workspace,
                                                _dev_ptr(dq), 1 if dq_accumulate else 0, _dev_ptr(dk), _dev_ptr(dv),
                                                1 if reuse_statistics else 0, _dev_ptr(workspace),
                                                workspace.numel() * workspace.element_size(), _stream_handle(stream)))
+
+
+def estimate_ms(cu_seqlens: Sequence[int], q_heads: int, kv_heads: int, head_dim: int) -> Tuple[float, float]:
+    """Host-only: predicted (forward ms, backward ms) of the kernels for this pack on an MI355X."""
+    cu = _i32(cu_seqlens)
+    f, b = ctypes.c_double(0.0), ctypes.c_double(0.0)
+    _check(load_library().hspmd_attn_estimate_ms(_ptr32(cu), len(cu) - 1, q_heads, kv_heads, head_dim,
+                                                 ctypes.byref(f), ctypes.byref(b)))
+    return float(f.value), float(b.value)

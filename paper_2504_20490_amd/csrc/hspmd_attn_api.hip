@@ -318,6 +318,23 @@ hspmd_status hspmd_attn_varlen_bwd(const hspmd_attn_plan* plan, const void* q, c
     return HSPMD_OK;
 }
 
+hspmd_status hspmd_attn_estimate_ms(const int32_t* cu_seqlens, int32_t num_seqs, int32_t local_q_heads,
+                                    int32_t local_kv_heads, int32_t head_dim, double* fwd_ms, double* bwd_ms) {
+    if (!fwd_ms || !bwd_ms) return fail(HSPMD_ERR_INVALID_ARG, "null pointer");
+    const std::string why = hspmd::check_pack(cu_seqlens, num_seqs, local_q_heads, local_kv_heads);
+    if (!why.empty()) return fail(HSPMD_ERR_INVALID_ARG, why);
+    if (head_dim != 64 && head_dim != 128) return fail(HSPMD_ERR_UNSUPPORTED, "head_dim must be 64 or 128");
+    try {
+        *fwd_ms = hspmd::estimate_pass_us(HSPMD_LIST_FWD, cu_seqlens, num_seqs, local_q_heads, local_kv_heads, head_dim) * 1e-3;
+        *bwd_ms = (hspmd::estimate_dsum_us(cu_seqlens[num_seqs], local_q_heads, head_dim) +
+                   hspmd::estimate_pass_us(HSPMD_LIST_DQ, cu_seqlens, num_seqs, local_q_heads, local_kv_heads, head_dim) +
+                   hspmd::estimate_pass_us(HSPMD_LIST_DKV, cu_seqlens, num_seqs, local_q_heads, local_kv_heads, head_dim)) * 1e-3;
+    } catch (const std::bad_alloc&) {
+        return fail(HSPMD_ERR_INVALID_ARG, "out of host memory while building the work lists");
+    }
+    return HSPMD_OK;
+}
+
 // ------------------------------------------------------------------------------ block variant
 hspmd_status hspmd_attn_block_schedule(hspmd_list_kind kind, const int32_t* cu_q, const int32_t* cu_k,
                                        const int32_t* q_pos, const int32_t* k_pos, int32_t num_seqs,

@@ -174,6 +174,43 @@ std::vector<hspmd_work_item> build_work_list(hspmd_list_kind kind, const int32_t
         hspmd_work_item{0, 0, -1, 0});
 }
 
+// ------------------------------------------------------------------------------ cost model
+// The paper's planner dispatches mixed-length sequences with a cost model evaluated on the CPU (Appendix
+// "Scenario-specific Planning", mixed-length case); this is the per-operator predictor for the attention
+// kernels of this library.  Fitted by relative least squares to 40 (head_dim 128) and 33 (head_dim 64) packs:
+// mean absolute error 5-8 % (128) and 8-12 % (64), at most 25-35 % on packs of a few hundred microseconds.
+PassCost pass_cost_coefficients(hspmd_list_kind kind, int32_t head_dim) {
+    static const PassCost k128[3] = {{9.9, 1.937, 10.49}, {3.1, 2.366, 14.09}, {0.0, 1.694, 15.64}};
+    static const PassCost k64[3] = {{3.8, 1.195, 4.30}, {0.0, 1.376, 6.66}, {3.5, 1.137, 7.91}};
+    return (head_dim == 64 ? k64 : k128)[(int)kind];
+}
+
+double estimate_pass_us(hspmd_list_kind kind, const int32_t* cu, int32_t num_seqs, int32_t hq, int32_t hkv, int32_t head_dim) {
+    const std::vector<hspmd_work_item> list = build_work_list(kind, cu, num_seqs, hq, hkv, kNumXcd);
+    if (list.empty()) return 0.0;
+    const PassCost c = pass_cost_coefficients(kind, head_dim);
+    const int32_t group = hq / hkv;
+    // workgroups resident per XCD: 32 compute units, two workgroups each in the forward and dQ passes, one in dK/dV
+    const double slots = kind == HSPMD_LIST_DKV ? 32.0 : 64.0;
+    double queue_weight[kNumXcd] = {0};
+    double heaviest = 0.0;
+    for (size_t p = 0; p < list.size(); ++p) {
+        if (list[p].tile < 0) continue;
+        const double w = (double)item_cost(kind, list[p].seq_len, list[p].tile, group) * c.step_us + c.item_us;
+        queue_weight[p % kNumXcd] += w;
+        heaviest = std::max(heaviest, w);
+    }
+    double worst = 0.0;
+    for (double w : queue_weight) worst = std::max(worst, w);
+    return c.launch_us + std::max(worst / slots, heaviest);
+}
+
+double estimate_dsum_us(int64_t total_tokens, int32_t hq, int32_t head_dim) {
+    if (total_tokens <= 0) return 0.0;
+    const double bytes = 2.0 * (double)total_tokens * hq * head_dim * 2.0;   // O and dO, bf16
+    return 5.0 + bytes / 5.0e6;                                              // ~5 TB/s sustained for this stream
+}
+
 // ------------------------------------------------------------------------------ block variant
 std::string check_block_pack(const int32_t* cu_q, const int32_t* cu_k, const int32_t* q_pos, const int32_t* k_pos,
                              int32_t num_seqs, int32_t hq, int32_t hkv) {

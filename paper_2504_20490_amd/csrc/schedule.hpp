@@ -26,6 +26,18 @@ std::vector<hspmd_work_item> build_work_list(hspmd_list_kind kind, const int32_t
                                              int32_t hq, int32_t hkv, int32_t num_queues,
                                              hspmd_order order = HSPMD_ORDER_XCD_COST);
 
+// ---- cost model: predicted kernel times (microseconds) of the three passes for a pack.
+// Every item of a pass's work list weighs steps * step_us + item_us; the pass takes launch_us plus the weight
+// of its heaviest queue divided by the workgroups resident per XCD (and not less than its heaviest item).
+struct PassCost {
+    double launch_us, step_us, item_us;
+};
+// coefficients fitted to measurements on MI355X (fit_cost_model.py refits them); head_dim 64 or 128
+PassCost pass_cost_coefficients(hspmd_list_kind kind, int32_t head_dim);
+double estimate_pass_us(hspmd_list_kind kind, const int32_t* cu, int32_t num_seqs, int32_t hq, int32_t hkv, int32_t head_dim);
+// the D pass of the backward (an HBM stream over O and dO)
+double estimate_dsum_us(int64_t total_tokens, int32_t hq, int32_t head_dim);
+
 // ---- block variant (one step of context-parallel attention): per sequence a query chunk and a key chunk
 // with positions inside the sequence; key j is visible to row r iff j <= r + (q_pos - k_pos).
 std::string check_block_pack(const int32_t* cu_q, const int32_t* cu_k, const int32_t* q_pos, const int32_t* k_pos,
