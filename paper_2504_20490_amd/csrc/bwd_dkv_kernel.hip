@@ -305,14 +305,15 @@ __global__ __launch_bounds__(kThreads, 1) void bwd_dkv_kernel(BwdParams p) {
         }
     }
     off.st = 2 * G::kTileBytes + hh * 16;
-    auto at_stage = [&](int stage_index) {
+    // `off` holds the addresses of the current tile's stage and is moved from stage to stage by adding the
+    // distance (one set of address registers instead of one per stage in use)
+    auto shifted = [&](const DkvAddr<D>& a0, int bytes) {
         DkvAddr<D> a;
-        const int base = stage_index * G::kStageBytes;
 #pragma unroll
-        for (int kk = 0; kk < KK; ++kk) a.rm[kk] = off.rm[kk] + base;
+        for (int kk = 0; kk < KK; ++kk) a.rm[kk] = a0.rm[kk] + bytes;
 #pragma unroll
-        for (int db = 0; db < DB; ++db) { a.tr[db][0] = off.tr[db][0] + base; a.tr[db][1] = off.tr[db][1] + base; }
-        a.st = off.st + base;
+        for (int db = 0; db < DB; ++db) { a.tr[db][0] = a0.tr[db][0] + bytes; a.tr[db][1] = a0.tr[db][1] + bytes; }
+        a.st = a0.st + bytes;
         return a;
     };
 
@@ -321,7 +322,7 @@ __global__ __launch_bounds__(kThreads, 1) void bwd_dkv_kernel(BwdParams p) {
 
     // prologue: G1(0) computed directly on top of block 0's statistics; P = dS = 0 for the non-existent block -1
     {
-        const DkvAddr<D> a0 = at_stage(0);
+        const DkvAddr<D>& a0 = off;   // stage 0
 #pragma unroll
         for (int i4 = 0; i4 < 4; ++i4) {
             const f32x4 a = *reinterpret_cast<const f32x4*>(lds + a0.st + i4 * 32);
@@ -359,12 +360,13 @@ __global__ __launch_bounds__(kThreads, 1) void bwd_dkv_kernel(BwdParams p) {
         const int stage1 = stage + 1 == G::kStages ? 0 : stage + 1;
         const int stage3 = (stage + 3) % G::kStages;
         if (u + 3 < n_tiles) load_tile(u + 3, stage3);
-        const DkvAddr<D> cur = at_stage(stage);
         // block 2u+2 lives in the next tile; the last tile has none: it re-reads itself (result unused)
-        const DkvAddr<D> next = at_stage(u + 1 < n_tiles ? stage1 : stage);
+        const int to_next = (stage1 - stage) * G::kStageBytes;
+        const DkvAddr<D> next = shifted(off, u + 1 < n_tiles ? to_next : 0);
         const int dkey0 = my_key - shift - qt * BQ - 4 * hh;
-        dkv_iteration<D, 0, kMask, false>(st, lds, cur, cur, dkey0, c, no_load);
-        dkv_iteration<D, 1, kMask, false>(st, lds, next, cur, dkey0 - 32, c, no_load);
+        dkv_iteration<D, 0, kMask, false>(st, lds, off, off, dkey0, c, no_load);
+        dkv_iteration<D, 1, kMask, false>(st, lds, next, off, dkey0 - 32, c, no_load);
+        off = shifted(off, to_next);
         stage = stage1;
     };
     // The same for an unmasked tile that is at least three tiles above the head's last one: the tile loaded
@@ -380,11 +382,12 @@ __global__ __launch_bounds__(kThreads, 1) void bwd_dkv_kernel(BwdParams p) {
         const int stage3 = stage == 0 ? G::kStages - 1 : stage - 1;   // (stage + 3) % kStages
         load.stage = lds0 + stage3 * G::kStageBytes;
         load.stat_dst = load.stage + 2 * G::kTileBytes + (wave & 1) * 256;
-        const DkvAddr<D> cur = at_stage(stage);
-        const DkvAddr<D> next = at_stage(stage1);
+        const int to_next = (stage1 - stage) * G::kStageBytes;
+        const DkvAddr<D> next = shifted(off, to_next);
         const int dkey0 = my_key - shift - qt * BQ - 4 * hh;
-        dkv_iteration<D, 0, false, true>(st, lds, cur, cur, dkey0, c, load);
-        dkv_iteration<D, 1, false, true>(st, lds, next, cur, dkey0 - 32, c, load);
+        dkv_iteration<D, 0, false, true>(st, lds, off, off, dkey0, c, load);
+        dkv_iteration<D, 1, false, true>(st, lds, next, off, dkey0 - 32, c, load);
+        off = shifted(off, to_next);
         load.q_row -= (int64_t)BQ * p.q_stride;
         load.do_row -= (int64_t)BQ * p.q_heads * D;
         load.stat -= BQ;
