@@ -55,7 +55,7 @@ extern "C" {
 typedef enum {
     HSPMD_OK = 0,
     HSPMD_ERR_INVALID_ARG = 1,        /* null pointer, bad lengths, bad strides, heads not a whole number of groups */
-    HSPMD_ERR_UNSUPPORTED = 2,        /* head_dim other than 64 or 128, unknown dtype */
+    HSPMD_ERR_UNSUPPORTED = 2,        /* head_dim not a multiple of 8 in 8..128, unknown dtype */
     HSPMD_ERR_WORKSPACE_TOO_SMALL = 3,
     HSPMD_ERR_HIP = 4                 /* a HIP runtime call failed; see hspmd_last_error() */
 } hspmd_status;
@@ -156,7 +156,10 @@ hspmd_status hspmd_attn_schedule_ordered(hspmd_list_kind kind, hspmd_order order
  * plan needs a GPU; it synchronises `stream` before returning.
  *   local_q_heads   query heads held by this GPU (any positive count: an uneven share is fine)
  *   local_kv_heads  KV heads held by this GPU; local_q_heads % local_kv_heads must be 0
- *   head_dim        64 or 128
+ *   head_dim        a multiple of 8 in 8..128 (rows move in 16-byte chunks).  The kernels are built for
+ *                   tile widths 64 and 128; other sizes, such as the 104 of the paper's 32B model (model
+ *                   configuration table: hidden 6656, 64 heads), run on the next width up: same results,
+ *                   the matrix-core work of the padded width
  */
 typedef struct hspmd_attn_plan hspmd_attn_plan;
 hspmd_status hspmd_attn_plan_create(const int32_t* cu_seqlens_host, int32_t num_seqs, int32_t local_q_heads,

@@ -120,14 +120,18 @@ struct TileCopy {
     uint32_t off[kPerWave];   // byte offset of this lane's chunk from the tile's first row, per instruction
     int chunk_bytes;          // swizzled column offset (bytes) of this lane's chunk: same for every instruction
     int row_in_instr;
+    int last_chunk;           // head_dim / 8 - 1: the row's last chunk that exists in memory
 
-    // stride: token stride of the tensor in elements (loop-invariant)
-    __device__ __forceinline__ void init(int64_t stride, int wave, int lane) {
+    // stride: token stride of the tensor in elements (loop-invariant).  head_dim (elements per row in memory) may
+    // be smaller than the tile width D: the pad chunks of an LDS row then repeat the row's last valid chunk, so
+    // that they hold finite values (they only ever meet zeros of the other operand, or produce columns nobody stores)
+    __device__ __forceinline__ void init(int64_t stride, int wave, int lane, int head_dim = D) {
         row_in_instr = lane / kChunksPerRow;
+        last_chunk = head_dim / 8 - 1;
 #pragma unroll
         for (int i = 0; i < kPerWave; ++i) {
             const int r = (i * 4 + wave) * kRowsPerInstr + row_in_instr;
-            const int c = swizzle<D>(r, lane % kChunksPerRow);
+            const int c = min(swizzle<D>(r, lane % kChunksPerRow), last_chunk);
             off[i] = (uint32_t)(r * (int)stride + c * 8) * 2u;
         }
     }
@@ -154,7 +158,7 @@ struct TileCopy {
         for (int i = 0; i < kPerWave; ++i) {
             const int blk = i * 4 + wave;
             const int r = blk * kRowsPerInstr + row_in_instr;
-            const int c = swizzle<D>(r, lane % kChunksPerRow);
+            const int c = min(swizzle<D>(r, lane % kChunksPerRow), last_chunk);
             const int row = min(row0 + r, seq_len - 1);
             global_to_lds<16>(slab + (int64_t)row * stride + c * 8, tile + blk * 1024);
         }

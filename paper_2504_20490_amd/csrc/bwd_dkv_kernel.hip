@@ -213,8 +213,9 @@ __global__ __launch_bounds__(kThreads, 1) void bwd_dkv_kernel(BwdParams p) {
     const int hh = lane >> 5;
     const bool valid = my_key < Lk;
 
-    const uint16_t* kbase = p.k + (int64_t)item.k_start * p.kv_stride + (int64_t)g * D;
-    const uint16_t* vbase = p.v + (int64_t)item.k_start * p.kv_stride + (int64_t)g * D;
+    const int hd = p.head_dim;   // elements per head in memory, <= D (columns hd .. D-1 exist only in LDS and registers)
+    const uint16_t* kbase = p.k + (int64_t)item.k_start * p.kv_stride + (int64_t)g * hd;
+    const uint16_t* vbase = p.v + (int64_t)item.k_start * p.kv_stride + (int64_t)g * hd;
 
     constexpr int kLoadsPerTile = 2 * (BQ * D * 2 / 1024) / 4 + 1;   // per wave: Q and dO chunks + one statistics copy
     // tiles: for each head of the group, q tiles first_qt .. n_qt-1 (rows at or below the diagonal: row r sees
@@ -226,9 +227,10 @@ __global__ __launch_bounds__(kThreads, 1) void bwd_dkv_kernel(BwdParams p) {
     if (BLOCK && per_head == 0) {
         // no row of the chunk sees these keys
         if (valid) {
-            const int64_t row_elem = ((int64_t)(item.k_start + my_key) * p.kv_heads + g) * D;
+            const int64_t row_elem = ((int64_t)(item.k_start + my_key) * p.kv_heads + g) * hd;
 #pragma unroll
             for (int c4 = 0; c4 < D / 8; ++c4) {
+                if (hh * (D / 2) + c4 * 4 >= hd) continue;
                 store_grad4(p.dk, row_elem + hh * (D / 2) + c4 * 4, p.grad_f32 != 0, 0.f, 0.f, 0.f, 0.f);
                 store_grad4(p.dv, row_elem + hh * (D / 2) + c4 * 4, p.grad_f32 != 0, 0.f, 0.f, 0.f, 0.f);
             }
@@ -239,14 +241,14 @@ __global__ __launch_bounds__(kThreads, 1) void bwd_dkv_kernel(BwdParams p) {
     // global -> LDS copy of tile u (flattened over heads) into a stage, statistics included
     const uint32_t lds0 = lds_address(lds);   // copy destinations are LDS byte addresses
     TileCopy<D, BQ> qcopy, docopy;
-    qcopy.init(p.q_stride, wave, lane);
-    docopy.init((int64_t)p.q_heads * D, wave, lane);
+    qcopy.init(p.q_stride, wave, lane, hd);
+    docopy.init((int64_t)p.q_heads * hd, wave, lane, hd);
     auto load_tile = [&](int u, int stage_index) {
         const uint32_t stage = lds0 + stage_index * G::kStageBytes;
         const int hq = g * p.group + u / per_head;
         const int row0 = (n_qt - 1 - u % per_head) * BQ;   // q tiles are walked from the end of the sequence down
-        const uint16_t* qb = p.q + (int64_t)item.q_start * p.q_stride + (int64_t)hq * D;
-        const uint16_t* dob = p.d_o + ((int64_t)item.q_start * p.q_heads + hq) * D;
+        const uint16_t* qb = p.q + (int64_t)item.q_start * p.q_stride + (int64_t)hq * hd;
+        const uint16_t* dob = p.d_o + ((int64_t)item.q_start * p.q_heads + hq) * hd;
         // even waves: -LSE/scale of the 64 rows; odd waves: -D (waves 2, 3 repeat the copies of waves 0, 1 so that
         // every wave has the same number of loads in flight)
         const int which = wave & 1;
@@ -254,12 +256,12 @@ __global__ __launch_bounds__(kThreads, 1) void bwd_dkv_kernel(BwdParams p) {
         const int64_t stat0 = (int64_t)hq * p.total_tokens + item.q_start + row0;
         if (row0 + BQ <= L) {
             qcopy.issue_full(stage, qb, p.q_stride, row0, wave);
-            docopy.issue_full(stage + G::kTileBytes, dob, (int64_t)p.q_heads * D, row0, wave);
+            docopy.issue_full(stage + G::kTileBytes, dob, (int64_t)p.q_heads * hd, row0, wave);
             global_to_lds<4>((which == 0 ? p.nlse : p.negd) + stat0, (uint32_t)lane * 4u, stat_dst);
         } else {
             // last tile of a head: rows past the end read a finite duplicate; their -LSE/scale reads -inf, so P = 0
             qcopy.issue_clamped(stage, qb, p.q_stride, row0, L, wave, lane);
-            docopy.issue_clamped(stage + G::kTileBytes, dob, (int64_t)p.q_heads * D, row0, L, wave, lane);
+            docopy.issue_clamped(stage + G::kTileBytes, dob, (int64_t)p.q_heads * hd, row0, L, wave, lane);
             const int r = row0 + lane;
             const int64_t stat = stat0 + min(lane, L - 1 - row0);
             const float* src = (which == 0) ? ((r < L) ? p.nlse + stat : p.ninf_pad) : p.negd + stat;
@@ -277,7 +279,7 @@ __global__ __launch_bounds__(kThreads, 1) void bwd_dkv_kernel(BwdParams p) {
         union { u32x4 u; bf16x8 v; } a, b;
         a.u = u32x4{0u, 0u, 0u, 0u};
         b.u = u32x4{0u, 0u, 0u, 0u};
-        if (valid) {
+        if (valid && kk * 16 + hh * 8 < hd) {
             a.u = *reinterpret_cast<const u32x4*>(kbase + (int64_t)my_key * p.kv_stride + kk * 16 + hh * 8);
             b.u = *reinterpret_cast<const u32x4*>(vbase + (int64_t)my_key * p.kv_stride + kk * 16 + hh * 8);
         }
@@ -389,7 +391,7 @@ __global__ __launch_bounds__(kThreads, 1) void bwd_dkv_kernel(BwdParams p) {
         dkv_iteration<D, 1, false, true>(st, lds, next, off, dkey0 - 32, c, load);
         off = shifted(off, to_next);
         load.q_row -= (int64_t)BQ * p.q_stride;
-        load.do_row -= (int64_t)BQ * p.q_heads * D;
+        load.do_row -= (int64_t)BQ * p.q_heads * hd;
         load.stat -= BQ;
         stage = stage1;
     };
@@ -410,8 +412,8 @@ __global__ __launch_bounds__(kThreads, 1) void bwd_dkv_kernel(BwdParams p) {
             DkvTileLoad<D> load;
             load.qcopy = &qcopy;
             load.docopy = &docopy;
-            load.q_row = p.q + row * p.q_stride + (int64_t)hq * D;
-            load.do_row = p.d_o + (row * p.q_heads + hq) * D;
+            load.q_row = p.q + row * p.q_stride + (int64_t)hq * hd;
+            load.do_row = p.d_o + (row * p.q_heads + hq) * hd;
             load.stat = ((wave & 1) == 0 ? p.nlse : p.negd) + (int64_t)hq * p.total_tokens + row;
             load.wave = wave;
             load.lane = lane;
@@ -430,12 +432,13 @@ __global__ __launch_bounds__(kThreads, 1) void bwd_dkv_kernel(BwdParams p) {
     }
 
     if (valid) {
-        const int64_t row_elem = ((int64_t)(item.k_start + my_key) * p.kv_heads + g) * D;
+        const int64_t row_elem = ((int64_t)(item.k_start + my_key) * p.kv_heads + g) * hd;
         const bool f32 = p.grad_f32 != 0;
 #pragma unroll
         for (int db = 0; db < DB; ++db)
 #pragma unroll
             for (int i4 = 0; i4 < 4; ++i4) {
+                if (db * 32 + i4 * 8 + hh * 4 >= hd) continue;
                 const int64_t e = row_elem + db * 32 + i4 * 8 + hh * 4;
                 store_grad4(p.dk, e, f32, st.dk[db][4 * i4 + 0] * p.scale, st.dk[db][4 * i4 + 1] * p.scale,
                             st.dk[db][4 * i4 + 2] * p.scale, st.dk[db][4 * i4 + 3] * p.scale);
@@ -448,7 +451,7 @@ __global__ __launch_bounds__(kThreads, 1) void bwd_dkv_kernel(BwdParams p) {
 hipError_t launch_bwd_dkv(const BwdParams& p, int head_dim, int64_t num_items, bool block, hipStream_t stream) {
     if (num_items == 0) return hipSuccess;
     const dim3 grid((unsigned)num_items), threads(kThreads);
-    if (head_dim == 128) {
+    if (tile_width(head_dim) == 128) {
         if (block) hipLaunchKernelGGL((bwd_dkv_kernel<128, true>), grid, threads, 0, stream, p);
         else hipLaunchKernelGGL((bwd_dkv_kernel<128, false>), grid, threads, 0, stream, p);
     } else {

@@ -27,11 +27,12 @@ __global__ __launch_bounds__(kThreads) void bwd_dsum_kernel(BwdParams p) {
     const int64_t n_rows = p.total_tokens * p.q_heads;
     const int64_t row = (int64_t)blockIdx.x * ROWS + threadIdx.x / LANES;
     const int c = threadIdx.x % LANES;
+    const int hd = p.head_dim;   // elements per row in memory, <= D
     float s = 0.f;
-    if (row < n_rows) {
+    if (row < n_rows && c * 8 < hd) {
         union { u32x4 u; bf16x8 v; } a, b;
-        a.u = *reinterpret_cast<const u32x4*>(p.o + row * D + c * 8);
-        b.u = *reinterpret_cast<const u32x4*>(p.d_o + row * D + c * 8);
+        a.u = *reinterpret_cast<const u32x4*>(p.o + row * hd + c * 8);
+        b.u = *reinterpret_cast<const u32x4*>(p.d_o + row * hd + c * 8);
 #pragma unroll
         for (int i = 0; i < 8; ++i) s += (float)a.v[i] * (float)b.v[i];
     }
@@ -70,10 +71,11 @@ __global__ __launch_bounds__(kThreads, 2) void bwd_dq_kernel(BwdParams p) {
     const int my_limit = BLOCK ? min(my_row + off, L - 1) : my_row;
     const int wave_limit = BLOCK ? min(wave_row0 + 31 + off, L - 1) : wave_row0 + 31;
 
-    const uint16_t* qbase = p.q + (int64_t)item.q_start * p.q_stride + (int64_t)h * D;
-    const uint16_t* dobase = p.d_o + ((int64_t)item.q_start * p.q_heads + h) * D;
-    const uint16_t* kbase = p.k + (int64_t)item.k_start * p.kv_stride + (int64_t)hk * D;
-    const uint16_t* vbase = p.v + (int64_t)item.k_start * p.kv_stride + (int64_t)hk * D;
+    const int hd = p.head_dim;   // elements per head in memory, <= D (columns hd .. D-1 exist only in LDS and registers)
+    const uint16_t* qbase = p.q + (int64_t)item.q_start * p.q_stride + (int64_t)h * hd;
+    const uint16_t* dobase = p.d_o + ((int64_t)item.q_start * p.q_heads + h) * hd;
+    const uint16_t* kbase = p.k + (int64_t)item.k_start * p.kv_stride + (int64_t)hk * hd;
+    const uint16_t* vbase = p.v + (int64_t)item.k_start * p.kv_stride + (int64_t)hk * hd;
 
     // key j is visible to row r iff j <= r + off: the tile's last row sees keys 0 .. kv_end-1
     const int kv_end = max(0, min(L, min(Lq, q_row0 + BQ) + off));
@@ -81,16 +83,17 @@ __global__ __launch_bounds__(kThreads, 2) void bwd_dq_kernel(BwdParams p) {
     if (BLOCK && n_tiles == 0) {
         // nothing visible: this block's share of dQ is zero
         if (valid && !p.dq_accumulate) {
-            float* row = static_cast<float*>(p.dq) + ((int64_t)(item.q_start + my_row) * p.q_heads + h) * D;
+            float* row = static_cast<float*>(p.dq) + ((int64_t)(item.q_start + my_row) * p.q_heads + h) * hd;
 #pragma unroll
             for (int c4 = 0; c4 < D / 8; ++c4)
-                *reinterpret_cast<f32x4*>(row + hh * (D / 2) + c4 * 4) = f32x4{0.f, 0.f, 0.f, 0.f};
+                if (hh * (D / 2) + c4 * 4 < hd)
+                    *reinterpret_cast<f32x4*>(row + hh * (D / 2) + c4 * 4) = f32x4{0.f, 0.f, 0.f, 0.f};
         }
         return;
     }
 
     TileCopy<D, BK> kvcopy;   // K and V share stride and geometry
-    kvcopy.init(p.kv_stride, wave, lane);
+    kvcopy.init(p.kv_stride, wave, lane, hd);
     const uint32_t lds0 = lds_address(lds);   // copy destinations are LDS byte addresses
     kvcopy.issue(lds0, kbase, p.kv_stride, 0, L, wave, lane);
     kvcopy.issue(lds0 + kTileBytes, vbase, p.kv_stride, 0, L, wave, lane);
@@ -101,9 +104,9 @@ __global__ __launch_bounds__(kThreads, 2) void bwd_dq_kernel(BwdParams p) {
         union { u32x4 u; bf16x8 v; } a, b;
         a.u = u32x4{0u, 0u, 0u, 0u};
         b.u = u32x4{0u, 0u, 0u, 0u};
-        if (valid) {
+        if (valid && kk * 16 + hh * 8 < hd) {
             a.u = *reinterpret_cast<const u32x4*>(qbase + (int64_t)my_row * p.q_stride + kk * 16 + hh * 8);
-            b.u = *reinterpret_cast<const u32x4*>(dobase + (int64_t)my_row * p.q_heads * D + kk * 16 + hh * 8);
+            b.u = *reinterpret_cast<const u32x4*>(dobase + (int64_t)my_row * p.q_heads * hd + kk * 16 + hh * 8);
         }
         qf[kk] = a.v;
         dof[kk] = b.v;
@@ -241,7 +244,7 @@ __global__ __launch_bounds__(kThreads, 2) void bwd_dq_kernel(BwdParams p) {
     for (; kt < n_tiles; ++kt) step(kt, std::true_type{});
 
     if (valid) {
-        const int64_t row_elem = ((int64_t)(item.q_start + my_row) * p.q_heads + h) * D;
+        const int64_t row_elem = ((int64_t)(item.q_start + my_row) * p.q_heads + h) * hd;
         if (BLOCK && p.dq_accumulate) {
             // this block's share is added to what earlier blocks left (fp32)
             float* row = static_cast<float*>(p.dq) + row_elem;
@@ -249,6 +252,7 @@ __global__ __launch_bounds__(kThreads, 2) void bwd_dq_kernel(BwdParams p) {
             for (int db = 0; db < DB; ++db)
 #pragma unroll
                 for (int i4 = 0; i4 < 4; ++i4) {
+                    if (db * 32 + i4 * 8 + hh * 4 >= hd) continue;
                     f32x4* dst = reinterpret_cast<f32x4*>(row + db * 32 + i4 * 8 + hh * 4);
                     f32x4 old = *dst;
 #pragma unroll
@@ -260,7 +264,8 @@ __global__ __launch_bounds__(kThreads, 2) void bwd_dq_kernel(BwdParams p) {
             for (int db = 0; db < DB; ++db)
 #pragma unroll
                 for (int i4 = 0; i4 < 4; ++i4)
-                    store_grad4(p.dq, row_elem + db * 32 + i4 * 8 + hh * 4, p.grad_f32 != 0,
+                    if (db * 32 + i4 * 8 + hh * 4 < hd)
+                        store_grad4(p.dq, row_elem + db * 32 + i4 * 8 + hh * 4, p.grad_f32 != 0,
                                 acc[db][4 * i4 + 0] * p.scale, acc[db][4 * i4 + 1] * p.scale,
                                 acc[db][4 * i4 + 2] * p.scale, acc[db][4 * i4 + 3] * p.scale);
         }
@@ -271,9 +276,9 @@ __global__ __launch_bounds__(kThreads, 2) void bwd_dq_kernel(BwdParams p) {
 hipError_t launch_bwd_dsum(const BwdParams& p, int head_dim, hipStream_t stream) {
     const int64_t n_rows = p.total_tokens * p.q_heads;
     if (n_rows == 0) return hipSuccess;
-    const int rows_per_block = kThreads / (head_dim / 8);
+    const int rows_per_block = kThreads / (tile_width(head_dim) / 8);
     const dim3 grid((unsigned)((n_rows + rows_per_block - 1) / rows_per_block)), block(kThreads);
-    if (head_dim == 128) {
+    if (tile_width(head_dim) == 128) {
         hipLaunchKernelGGL(bwd_dsum_kernel<128>, grid, block, 0, stream, p);
     } else {
         hipLaunchKernelGGL(bwd_dsum_kernel<64>, grid, block, 0, stream, p);
@@ -284,7 +289,7 @@ hipError_t launch_bwd_dsum(const BwdParams& p, int head_dim, hipStream_t stream)
 hipError_t launch_bwd_dq(const BwdParams& p, int head_dim, int64_t num_items, bool block, hipStream_t stream) {
     if (num_items == 0) return hipSuccess;
     const dim3 grid((unsigned)num_items), threads(kThreads);
-    if (head_dim == 128) {
+    if (tile_width(head_dim) == 128) {
         if (block) hipLaunchKernelGGL((bwd_dq_kernel<128, true>), grid, threads, 0, stream, p);
         else hipLaunchKernelGGL((bwd_dq_kernel<128, false>), grid, threads, 0, stream, p);
     } else {

@@ -216,9 +216,10 @@ __global__ __launch_bounds__(kThreads, 2) void fwd_kernel(FwdParams p) {
     const int my_row = wave_row0 + (lane & 31);
     const int hh = lane >> 5;
 
-    const uint16_t* qbase = p.q + (int64_t)item.q_start * p.q_stride + (int64_t)h * D;
-    const uint16_t* kbase = p.k + (int64_t)item.k_start * p.kv_stride + (int64_t)hk * D;
-    const uint16_t* vbase = p.v + (int64_t)item.k_start * p.kv_stride + (int64_t)hk * D;
+    const int hd = p.head_dim;   // elements per head in memory, <= D (columns hd .. D-1 exist only in LDS and registers)
+    const uint16_t* qbase = p.q + (int64_t)item.q_start * p.q_stride + (int64_t)h * hd;
+    const uint16_t* kbase = p.k + (int64_t)item.k_start * p.kv_stride + (int64_t)hk * hd;
+    const uint16_t* vbase = p.v + (int64_t)item.k_start * p.kv_stride + (int64_t)hk * hd;
 
     // key j is visible to row r iff j <= r + off: the tile's last row sees keys 0 .. kv_end-1
     const int kv_end = max(0, min(L, min(Lq, q_row0 + BQ) + off));
@@ -232,17 +233,18 @@ __global__ __launch_bounds__(kThreads, 2) void fwd_kernel(FwdParams p) {
     if (BLOCK && n_tiles == 0) {
         // no key of the chunk is visible to any row of the tile: O = 0, LSE = -inf
         if (my_row < Lq) {
-            float* orow = p.o_f32 + ((int64_t)(item.q_start + my_row) * p.q_heads + h) * D;
+            float* orow = p.o_f32 + ((int64_t)(item.q_start + my_row) * p.q_heads + h) * hd;
 #pragma unroll
             for (int c4 = 0; c4 < D / 8; ++c4)
-                *reinterpret_cast<f32x4*>(orow + hh * (D / 2) + c4 * 4) = f32x4{0.f, 0.f, 0.f, 0.f};
+                if (hh * (D / 2) + c4 * 4 < hd)
+                    *reinterpret_cast<f32x4*>(orow + hh * (D / 2) + c4 * 4) = f32x4{0.f, 0.f, 0.f, 0.f};
             if (hh == 0) p.lse[(int64_t)h * p.total_tokens + item.q_start + my_row] = -INFINITY;
         }
         return;
     }
 
     TileCopy<D, BK> kvcopy;   // K and V share stride and geometry
-    kvcopy.init(p.kv_stride, wave, lane);
+    kvcopy.init(p.kv_stride, wave, lane, hd);
     // K(0), V(0), K(1)
     kvcopy.issue(kdst0, kbase, p.kv_stride, 0, L, wave, lane);
     kvcopy.issue(vdst0, vbase, p.kv_stride, 0, L, wave, lane);
@@ -253,7 +255,8 @@ __global__ __launch_bounds__(kThreads, 2) void fwd_kernel(FwdParams p) {
     for (int kk = 0; kk < KK; ++kk) {
         union { u32x4 u; bf16x8 v; } t;
         t.u = u32x4{0u, 0u, 0u, 0u};
-        if (my_row < Lq) t.u = *reinterpret_cast<const u32x4*>(qbase + (int64_t)my_row * p.q_stride + kk * 16 + hh * 8);
+        if (my_row < Lq && kk * 16 + hh * 8 < hd)
+            t.u = *reinterpret_cast<const u32x4*>(qbase + (int64_t)my_row * p.q_stride + kk * 16 + hh * 8);
         st.qf[kk] = t.v;
     }
 #pragma unroll
@@ -334,12 +337,13 @@ __global__ __launch_bounds__(kThreads, 2) void fwd_kernel(FwdParams p) {
         if constexpr (BLOCK) {
             // partial result in fp32; a row that saw no key has l = 0 and m = -inf: O = 0, LSE = -inf
             const float inv = l_row > 0.f ? 1.f / l_row : 0.f;
-            float* orow = p.o_f32 + ((int64_t)(item.q_start + my_row) * p.q_heads + h) * D;
+            float* orow = p.o_f32 + ((int64_t)(item.q_start + my_row) * p.q_heads + h) * hd;
 #pragma unroll
             for (int db = 0; db < DB; ++db)
 #pragma unroll
                 for (int i4 = 0; i4 < 4; ++i4)
-                    *reinterpret_cast<f32x4*>(orow + db * 32 + i4 * 8 + hh * 4) =
+                    if (db * 32 + i4 * 8 + hh * 4 < hd)
+                        *reinterpret_cast<f32x4*>(orow + db * 32 + i4 * 8 + hh * 4) =
                         f32x4{st.acc[db][4 * i4 + 0] * inv, st.acc[db][4 * i4 + 1] * inv, st.acc[db][4 * i4 + 2] * inv,
                               st.acc[db][4 * i4 + 3] * inv};
             if (hh == 0)
@@ -347,7 +351,7 @@ __global__ __launch_bounds__(kThreads, 2) void fwd_kernel(FwdParams p) {
                     l_row > 0.f ? (st.m * c + __log2f(l_row)) * kLn2 : -INFINITY;
         } else {
             const float inv = 1.f / l_row;
-            uint16_t* orow = p.o + ((int64_t)(item.q_start + my_row) * p.q_heads + h) * D;
+            uint16_t* orow = p.o + ((int64_t)(item.q_start + my_row) * p.q_heads + h) * hd;
 #pragma unroll
             for (int db = 0; db < DB; ++db)
 #pragma unroll
@@ -355,7 +359,7 @@ __global__ __launch_bounds__(kThreads, 2) void fwd_kernel(FwdParams p) {
                     u32x2 w;
                     w[0] = pack_bf16(st.acc[db][4 * i4 + 0] * inv, st.acc[db][4 * i4 + 1] * inv);
                     w[1] = pack_bf16(st.acc[db][4 * i4 + 2] * inv, st.acc[db][4 * i4 + 3] * inv);
-                    *reinterpret_cast<u32x2*>(orow + db * 32 + i4 * 8 + hh * 4) = w;
+                    if (db * 32 + i4 * 8 + hh * 4 < hd) *reinterpret_cast<u32x2*>(orow + db * 32 + i4 * 8 + hh * 4) = w;
                 }
             if (hh == 0) p.lse[(int64_t)h * p.total_tokens + item.q_start + my_row] = (st.m * c + __log2f(l_row)) * kLn2;
         }
@@ -365,7 +369,7 @@ __global__ __launch_bounds__(kThreads, 2) void fwd_kernel(FwdParams p) {
 hipError_t launch_fwd(const FwdParams& p, int head_dim, int64_t num_items, bool block, hipStream_t stream) {
     if (num_items == 0) return hipSuccess;
     const dim3 grid((unsigned)num_items), threads(kThreads);
-    if (head_dim == 128) {
+    if (tile_width(head_dim) == 128) {
         if (block) hipLaunchKernelGGL((fwd_kernel<128, true>), grid, threads, 0, stream, p);
         else hipLaunchKernelGGL((fwd_kernel<128, false>), grid, threads, 0, stream, p);
     } else {

@@ -29,6 +29,9 @@ hspmd_status fail_hip(hipError_t e, const char* where) {
 
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
+// rows are moved in 16-byte chunks; the kernels exist for tile widths 64 and 128 and pad up to the next one
+bool supported_head_dim(int32_t head_dim) { return head_dim >= 8 && head_dim <= 128 && head_dim % 8 == 0; }
+
 // ---- optional per-kernel event timing ------------------------------------------------------
 struct ProfileRecord {
     int kernel;
@@ -148,7 +151,7 @@ hspmd_status hspmd_attn_plan_create_ordered(const int32_t* cu_seqlens_host, int3
     *out = nullptr;
     const std::string why = hspmd::check_pack(cu_seqlens_host, num_seqs, local_q_heads, local_kv_heads);
     if (!why.empty()) return fail(HSPMD_ERR_INVALID_ARG, why);
-    if (head_dim != 64 && head_dim != 128) return fail(HSPMD_ERR_UNSUPPORTED, "head_dim must be 64 or 128");
+    if (!supported_head_dim(head_dim)) return fail(HSPMD_ERR_UNSUPPORTED, "head_dim must be a multiple of 8 between 8 and 128");
     if (order != HSPMD_ORDER_XCD_COST && order != HSPMD_ORDER_NATURAL && order != HSPMD_ORDER_COST)
         return fail(HSPMD_ERR_INVALID_ARG, "unknown order");
     hspmd_attn_plan* plan = new (std::nothrow) hspmd_attn_plan();
@@ -257,6 +260,7 @@ hspmd_status hspmd_attn_varlen_fwd(const hspmd_attn_plan* plan, const void* q, c
     p.total_tokens = plan->total_tokens;
     p.q_heads = plan->q_heads;
     p.group = plan->q_heads / plan->kv_heads;
+    p.head_dim = plan->head_dim;
     p.scale_log2 = scale * 1.4426950408889634f;
     hipStream_t s = static_cast<hipStream_t>(stream);
     const hipError_t e = timed_launch(0, s, [&] { return hspmd::launch_fwd(p, plan->head_dim, plan->count[HSPMD_LIST_FWD], false, s); });
@@ -303,6 +307,7 @@ hspmd_status hspmd_attn_varlen_bwd(const hspmd_attn_plan* plan, const void* q, c
     p.q_heads = plan->q_heads;
     p.kv_heads = plan->kv_heads;
     p.group = plan->q_heads / plan->kv_heads;
+    p.head_dim = plan->head_dim;
     p.grad_f32 = grad_dtype == HSPMD_GRAD_F32 ? 1 : 0;
     p.scale = scale;
     p.scale_log2 = scale * 1.4426950408889634f;
@@ -323,8 +328,9 @@ hspmd_status hspmd_attn_estimate_ms(const int32_t* cu_seqlens, int32_t num_seqs,
     if (!fwd_ms || !bwd_ms) return fail(HSPMD_ERR_INVALID_ARG, "null pointer");
     const std::string why = hspmd::check_pack(cu_seqlens, num_seqs, local_q_heads, local_kv_heads);
     if (!why.empty()) return fail(HSPMD_ERR_INVALID_ARG, why);
-    if (head_dim != 64 && head_dim != 128) return fail(HSPMD_ERR_UNSUPPORTED, "head_dim must be 64 or 128");
+    if (!supported_head_dim(head_dim)) return fail(HSPMD_ERR_UNSUPPORTED, "head_dim must be a multiple of 8 between 8 and 128");
     try {
+        head_dim = hspmd::tile_width(head_dim);   // a narrower head runs on the next tile width up
         *fwd_ms = hspmd::estimate_pass_us(HSPMD_LIST_FWD, cu_seqlens, num_seqs, local_q_heads, local_kv_heads, head_dim) * 1e-3;
         *bwd_ms = (hspmd::estimate_dsum_us(cu_seqlens[num_seqs], local_q_heads, head_dim) +
                    hspmd::estimate_pass_us(HSPMD_LIST_DQ, cu_seqlens, num_seqs, local_q_heads, local_kv_heads, head_dim) +
@@ -368,7 +374,7 @@ hspmd_status hspmd_attn_block_plan_create(const int32_t* cu_q_host, const int32_
     const std::string why =
         hspmd::check_block_pack(cu_q_host, cu_k_host, q_pos_host, k_pos_host, num_seqs, local_q_heads, local_kv_heads);
     if (!why.empty()) return fail(HSPMD_ERR_INVALID_ARG, why);
-    if (head_dim != 64 && head_dim != 128) return fail(HSPMD_ERR_UNSUPPORTED, "head_dim must be 64 or 128");
+    if (!supported_head_dim(head_dim)) return fail(HSPMD_ERR_UNSUPPORTED, "head_dim must be a multiple of 8 between 8 and 128");
     hspmd_attn_plan* plan = new (std::nothrow) hspmd_attn_plan();
     if (!plan) return fail(HSPMD_ERR_INVALID_ARG, "out of host memory");
     plan->is_block = true;
@@ -445,6 +451,7 @@ hspmd_status hspmd_attn_block_fwd(const hspmd_attn_plan* plan, const void* q, co
     p.total_tokens = plan->total_tokens;
     p.q_heads = plan->q_heads;
     p.group = plan->q_heads / plan->kv_heads;
+    p.head_dim = plan->head_dim;
     p.scale_log2 = scale * 1.4426950408889634f;
     hipStream_t s = static_cast<hipStream_t>(stream);
     const hipError_t e = timed_launch(0, s, [&] { return hspmd::launch_fwd(p, plan->head_dim, plan->count[HSPMD_LIST_FWD], true, s); });
@@ -456,7 +463,7 @@ hspmd_status hspmd_attn_merge(int64_t total_tokens, int32_t local_q_heads, int32
                               const float* lse_a, const float* o_b, const float* lse_b, float* o_out, float* lse_out,
                               void* o_out_bf16, void* stream) {
     if (total_tokens < 0 || local_q_heads <= 0) return fail(HSPMD_ERR_INVALID_ARG, "bad token or head count");
-    if (head_dim != 64 && head_dim != 128) return fail(HSPMD_ERR_UNSUPPORTED, "head_dim must be 64 or 128");
+    if (!supported_head_dim(head_dim)) return fail(HSPMD_ERR_UNSUPPORTED, "head_dim must be a multiple of 8 between 8 and 128");
     if (total_tokens == 0) return HSPMD_OK;
     if (!o_a || !lse_a || !o_b || !lse_b || !o_out || !lse_out) return fail(HSPMD_ERR_INVALID_ARG, "null tensor pointer");
     if (!aligned16(o_a) || !aligned16(o_b) || !aligned16(o_out) || !aligned16(o_out_bf16))
@@ -513,6 +520,7 @@ hspmd_status hspmd_attn_block_bwd(const hspmd_attn_plan* plan, const void* q, co
     p.q_heads = plan->q_heads;
     p.kv_heads = plan->kv_heads;
     p.group = plan->q_heads / plan->kv_heads;
+    p.head_dim = plan->head_dim;
     p.grad_f32 = 1;
     p.dq_accumulate = dq_accumulate ? 1 : 0;
     p.scale = scale;

@@ -19,6 +19,7 @@ struct FwdParams {
     int64_t q_stride, kv_stride;   // token strides in elements
     int64_t total_tokens;          // query tokens (rows of lse)
     int32_t q_heads, group;
+    int32_t head_dim;              // elements per head in memory (a multiple of 8, at most the kernel's tile width)
     float scale_log2;              // softmax_scale * log2(e)
 };
 
@@ -40,11 +41,16 @@ struct BwdParams {
     int64_t q_stride, kv_stride;
     int64_t total_tokens;          // query tokens (rows of lse, D)
     int32_t q_heads, kv_heads, group;
+    int32_t head_dim;              // elements per head in memory (a multiple of 8, at most the kernel's tile width)
     int32_t grad_f32;              // 1: gradients are fp32, 0: bf16
     int32_t dq_accumulate;         // block variant only: dq += this block's share (fp32) instead of dq = ...
     float scale;                   // softmax_scale
     float scale_log2;              // softmax_scale * log2(e)
 };
+
+// The kernels exist for tile widths 64 and 128 (LDS rows, MFMA contraction); a head_dim below the tile width runs
+// on the next width up: register fragments are zero beyond head_dim, LDS pad columns repeat a valid chunk.
+inline int tile_width(int head_dim) { return head_dim <= 64 ? 64 : 128; }
 
 // `block`: the items are hspmd_block_item (separate query / key chunks, shifted causal mask)
 hipError_t launch_fwd(const FwdParams& p, int head_dim, int64_t num_items, bool block, hipStream_t stream);

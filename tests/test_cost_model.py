@@ -46,6 +46,6 @@ def test_validation():
     with pytest.raises(A.HspmdError):
         A.estimate_ms([0, 10], 3, 2, 128)
     with pytest.raises(A.HspmdError):
-        A.estimate_ms([0, 10], 2, 2, 96)
+        A.estimate_ms([0, 10], 2, 2, 100)
     with pytest.raises(A.HspmdError):
         A.estimate_ms([0, 10, 5], 2, 2, 128)

@@ -217,7 +217,7 @@ def test_block_validation():
     with pytest.raises(A.HspmdError):
         A.BlockPlan([0, 10], [0, 10], [0], [0], 3, 2, 64)            # heads not a whole number of groups
     with pytest.raises(A.HspmdError):
-        A.BlockPlan([0, 10], [0, 10], [0], [0], 2, 2, 96)            # head_dim
+        A.BlockPlan([0, 10], [0, 10], [0], [0], 2, 2, 100)           # head_dim
     bplan = A.BlockPlan([0, 10], [0, 12], [2], [0], 2, 2, 64)
     plan = A.Plan([0, 10], 2, 2, 64)
     assert bplan.total_tokens == 10 and bplan.total_kv_tokens == 12

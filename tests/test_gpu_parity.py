@@ -51,6 +51,42 @@ def test_ragged_lengths_span_tiles_and_tails(hq, hkv, d):
     _full_check(lengths, hq, hkv, d, seed=11 + hq)
 
 
+@pytest.mark.parametrize("hq,hkv,d", [(4, 4, 104), (4, 2, 104), (2, 2, 40), (3, 1, 120), (2, 2, 8)])
+def test_head_dims_between_the_tile_widths(hq, hkv, d):
+    """head_dim 104 is the paper's 32B model (hidden 6656 over 64 heads); any multiple of 8 runs on the next tile
+    width up.  Outputs are written NaN-filled beforehand, so a column that the kernels leave out would show."""
+    _full_check(RAGGED, hq, hkv, d, seed=30 + d)
+
+
+def test_head_dim_104_long_sequences_and_strided_views():
+    """16 of the 64 heads of the paper's 32B model (a 4-way split of the hidden dimension), one sequence long enough
+    for every loop variant, q / k / v as views into one fused QKV buffer."""
+    import torch
+    lengths, hq, hkv, d = [3000, 333], 16, 16, 104
+    q, k, v, do = make_case(lengths, hq, hkv, d, seed=77)
+    T = sum(lengths)
+    fused = torch.zeros(T, (hq + 2 * hkv) * d, dtype=torch.bfloat16, device="cuda")
+    qv = fused[:, : hq * d].view(T, hq, d)
+    kv = fused[:, hq * d: (hq + hkv) * d].view(T, hkv, d)
+    vv = fused[:, (hq + hkv) * d:].view(T, hkv, d)
+    qv.copy_(to_dev(q)); kv.copy_(to_dev(k)); vv.copy_(to_dev(v))
+    gpu_util.CONTEXT["case"] = "d104_long"
+    run = GpuRun(lengths, q, k, v, do, q_dev=qv, k_dev=kv, v_dev=vv).run()
+    s = default_scale(d)
+    rows = np.array([0, 1, 127, 128, 2999, 3000, 3332, 1500], dtype=np.int32)
+    heads = np.array([0, 15, 7, 3, 15, 0, 9, 8], dtype=np.int32)
+    ro, rlse, rdq = oracle.attn_rows(f64(q), f64(k), f64(v), f64(do), lengths, s, rows, heads)
+    assert_close("O rows", run.host("o")[rows, heads], ro)
+    assert np.max(np.abs(run.host("lse")[heads, rows] - rlse)) <= LSE_ABS
+    assert_close("dQ rows", run.host("dq")[rows, heads], rdq)
+    keys = np.array([0, 5, 2999, 3000, 3332, 64], dtype=np.int32)
+    kvh = np.array([0, 15, 2, 9, 15, 4], dtype=np.int32)
+    rdk, rdv = oracle.attn_keys(f64(q), f64(k), f64(v), f64(do), lengths, s, keys, kvh)
+    assert_close("dK keys", run.host("dk")[keys, kvh], rdk)
+    assert_close("dV keys", run.host("dv")[keys, kvh], rdv)
+    assert not np.isnan(run.host("o")).any() and not np.isnan(run.host("dk")).any()
+
+
 def test_several_tiles_and_uneven_heads():
     # 5 and 11 q tiles, 3 local heads (an uneven share), lengths not multiples of any tile
     _full_check([700, 1300], 3, 3, 128, seed=21)
