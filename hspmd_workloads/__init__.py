@@ -155,6 +155,10 @@ CONFIGS: Tuple[Config, ...] = (
            note="24 of 40 heads (3:2 uneven split of a hidden-5120 model), 32768 tokens"),
     Config("C5_bimodal_gqa", 65536, 32, 8, 128, 5, 1005, 1.0 / math.sqrt(128.0), "bimodal",
            lo=256, hi=2048, note="70% U[256,2048], 30% U[16384,32768]; 32 q heads on 8 kv heads"),
+    # the shape of the paper's own 32B model (model configuration table: hidden 6656, 64 heads, head_dim 104) under a
+    # 4-way split of the hidden dimension, on its default workload of 4K-token sequences
+    Config("P1_paper32b_4k", 32768, 16, 16, 104, 6, 0, 1.0, "fixed", fixed_lengths=(4096,) * 8,
+           note="8 x 4096, 16 of 64 heads, head_dim 104"),
 )
 
 
