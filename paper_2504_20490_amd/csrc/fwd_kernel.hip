@@ -142,12 +142,12 @@ __device__ __forceinline__ void fwd_iteration(FwdState<D>& st, const char* kbuf,
         for (int n = 0; n < NM; ++n) {
             if (n + kAheadK < NM) kq[(n + kAheadK) % (kAheadK + 1)] = k_frag(n + kAheadK);
             sn[n / KK] = mfma(kq[n % (kAheadK + 1)], st.qf[n % KK], sn[n / KK]);
-            // 16 score pairs over the NM MFMAs
+            // the first 8 of the 16 score pairs (key block 0, P fragments 0 and 1) spread over the NM MFMAs; the
+            // other 8 go under the first P V MFMAs of phase B, which only need fragments 0 and 1
             if constexpr (NM == 16) {
-                softmax_pair(n);
+                if (n % 2 == 0) softmax_pair(n / 2);
             } else {
-                softmax_pair(2 * n);
-                softmax_pair(2 * n + 1);
+                softmax_pair(n);
             }
             if constexpr (SPREAD) {
                 // all copies early in the iteration: both tiles are needed right after the next barrier
@@ -158,9 +158,8 @@ __device__ __forceinline__ void fwd_iteration(FwdState<D>& st, const char* kbuf,
         }
     } else {
 #pragma unroll
-        for (int n = 0; n < 16; ++n) softmax_pair(n);
+        for (int n = 0; n < 8; ++n) softmax_pair(n);
     }
-    st.l = st.l * alpha + psum;
     __builtin_amdgcn_sched_barrier(0);
 
     // ---------------- phase B: O^T += V(kt)^T P^T(kt), transpose reads kAheadV MFMAs ahead
@@ -182,9 +181,16 @@ __device__ __forceinline__ void fwd_iteration(FwdState<D>& st, const char* kbuf,
         for (int n = 0; n < NM; ++n) {
             if (n + kAheadV < NM) vq[(n + kAheadV) % (kAheadV + 1)] = v_frag(n + kAheadV);
             st.acc[n % DB] = mfma(vq[n % (kAheadV + 1)], pw[n / DB].v, st.acc[n % DB]);
+            // score pairs 8 .. 15 (key block 1, P fragments 2 and 3) under the MFMAs of fragments 0 and 1
+            if constexpr (DB == 4) {
+                if (n < 8) softmax_pair(8 + n);
+            } else {
+                if (n < 4) { softmax_pair(8 + 2 * n); softmax_pair(9 + 2 * n); }
+            }
             __builtin_amdgcn_sched_barrier(0);
         }
     }
+    st.l = st.l * alpha + psum;
     if constexpr (!LAST) {
         st.s[0] = sn[0];
         st.s[1] = sn[1];
