@@ -166,6 +166,12 @@ hspmd_status hspmd_attn_plan_create_ordered(const int32_t* cu_seqlens_host, int3
     size_t offset[3] = {0, 0, 0};
     try {
         for (int kind = 0; kind < 3; ++kind) {
+            if (kind == HSPMD_LIST_DQ) {
+                // same items, costs and order as the forward list: one copy serves both passes
+                plan->count[kind] = plan->count[HSPMD_LIST_FWD];
+                offset[kind] = offset[HSPMD_LIST_FWD];
+                continue;
+            }
             const std::vector<hspmd_work_item> list = hspmd::build_work_list(
                 (hspmd_list_kind)kind, cu_seqlens_host, num_seqs, local_q_heads, local_kv_heads, hspmd::kNumXcd, order);
             plan->count[kind] = (int64_t)list.size();
@@ -388,6 +394,12 @@ hspmd_status hspmd_attn_block_plan_create(const int32_t* cu_q_host, const int32_
     size_t offset[3] = {0, 0, 0};
     try {
         for (int kind = 0; kind < 3; ++kind) {
+            if (kind == HSPMD_LIST_DQ) {
+                // same items, costs and order as the forward list: one copy serves both passes
+                plan->count[kind] = plan->count[HSPMD_LIST_FWD];
+                offset[kind] = offset[HSPMD_LIST_FWD];
+                continue;
+            }
             const std::vector<hspmd_block_item> list =
                 hspmd::build_block_list((hspmd_list_kind)kind, cu_q_host, cu_k_host, q_pos_host, k_pos_host, num_seqs,
                                         local_q_heads, local_kv_heads, hspmd::kNumXcd);

@@ -259,3 +259,12 @@ def test_block_work_list_of_an_invisible_block_is_spread_over_the_queues():
     items = A.block_schedule(A.LIST_FWD, cq, [0, 3000], [0], [5000], 4, 2)
     real = int((items[:, 5] >= 0).sum())
     assert real == 24 * 4 and items.shape[0] <= real + 8
+
+
+def test_forward_and_dq_lists_are_the_same_list():
+    """A plan keeps one device copy for both passes: the two lists must agree slot by slot, in every order."""
+    cu = np.concatenate([[0], np.cumsum([700, 0, 3000, 129, 64])])
+    for order in (A.ORDER_XCD_COST, A.ORDER_NATURAL, A.ORDER_COST):
+        assert np.array_equal(A.schedule(A.LIST_FWD, cu, 6, 2, order=order), A.schedule(A.LIST_DQ, cu, 6, 2, order=order))
+    assert np.array_equal(A.block_schedule(A.LIST_FWD, cu, cu[::-1].cumsum() * 0 + cu, [5, 0, 100, 0, 7], [0, 0, 0, 9, 7], 6, 2),
+                          A.block_schedule(A.LIST_DQ, cu, cu, [5, 0, 100, 0, 7], [0, 0, 0, 9, 7], 6, 2))
