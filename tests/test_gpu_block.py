@@ -56,7 +56,7 @@ class BlockRun:
         return getattr(self, name).float().cpu().numpy().astype(np.float64)
 
 
-def _check_single_block(ql, kl, qp, kp, hq, hkv, d, seed, case):
+def _check_single_block(ql, kl, qp, kp, hq, hkv, d, seed, case, magnitude_slack=False):
     """Forward of one block against the oracle; backward with the block's own (LSE, O) as the statistics of the whole
     rows, i.e. as if this block were all there is (rows without a visible key keep LSE = -inf and must take no
     part).  Statistics that differ from the block's own are exercised by the emulated ring below."""
@@ -81,9 +81,13 @@ def _check_single_block(ql, kl, qp, kp, hq, hkv, d, seed, case):
     lse_ref = lse_dev.cpu().numpy().astype(np.float64)
     lse_ref = np.where(np.isneginf(lse_ref), np.inf, lse_ref)          # exp(S - inf) = 0: such rows take no part
     rdq, rdk, rdv = ob.block_bwd(f64(r.qb), f64(r.kb), f64(r.vb), f64(r.dob), lse_ref, dsum, *r.geom, r.s)
-    assert_close("dQ share", r.host("dq"), rdq)
-    assert_close("dK block", r.host("dk"), rdk)
-    assert_close("dV block", r.host("dv"), rdv)
+    # the stated max-abs bound is for gradients of the benchmark configurations' magnitude (a few units); random
+    # geometries with several heads per KV head reach |dV| > 10, where the bf16 rounding of P alone (2^-9 relative)
+    # exceeds it: such callers add that much slack.  The relative bound stays as it is.
+    slack = (lambda ref: 2.0 ** -9 * float(np.max(np.abs(ref)))) if magnitude_slack else (lambda ref: 0.0)
+    assert_close("dQ share", r.host("dq"), rdq, max_abs=gpu_util.MAX_ABS + slack(rdq))
+    assert_close("dK block", r.host("dk"), rdk, max_abs=gpu_util.MAX_ABS + slack(rdk))
+    assert_close("dV block", r.host("dv"), rdv, max_abs=gpu_util.MAX_ABS + slack(rdv))
     return r, (rdq, rdk, rdv), (o_dev, lse_dev)
 
 
@@ -230,3 +234,20 @@ def test_block_validation():
         A.attn_varlen_fwd(bplan, q, q, q, o16, lse)                  # block plan in a packed call
     with pytest.raises(A.HspmdError):
         A.attn_merge(o32, lse, o32, lse, o32, lse)                   # output aliases operand b
+
+
+def test_random_block_geometries():
+    """Forty small packs with random chunk lengths and positions (seeded), both head dims, MHA and GQA: forward and
+    backward of a block against the block oracle, with the block's own statistics."""
+    rng = np.random.default_rng(20250427)
+    for case in range(40):
+        n = int(rng.integers(1, 5))
+        ql = [int(x) for x in rng.integers(0, 330, n)]
+        kl = [int(x) for x in rng.integers(0, 330, n)]
+        qp = [int(x) for x in rng.integers(0, 400, n)]
+        kp = [int(x) for x in rng.integers(0, 400, n)]
+        if sum(ql) == 0:
+            ql[0] = 5
+        d = int(rng.choice([64, 128, 104]))
+        hq, hkv = [(2, 2), (4, 2), (3, 1)][int(rng.integers(0, 3))]
+        _check_single_block(ql, kl, qp, kp, hq, hkv, d, 1000 + case, f"block_random_{case}", magnitude_slack=True)

@@ -14,7 +14,7 @@ pytestmark = pytest.mark.gpu
 RAGGED = [1, 2, 31, 32, 33, 63, 64, 65, 127, 128, 129, 200, 257, 0, 300]
 
 
-def _full_check(lengths, hq, hkv, d, seed, value_scale=1.0, grad_dtype=None, scale=0.0):
+def _full_check(lengths, hq, hkv, d, seed, value_scale=1.0, grad_dtype=None, scale=0.0, magnitude_slack=False):
     gpu_util.CONTEXT["case"] = f"small pack {len(lengths)} seqs Hq{hq} Hkv{hkv} d{d} seed{seed}"
     q, k, v, do = make_case(lengths, hq, hkv, d, seed, value_scale)
     run = GpuRun(lengths, q, k, v, do, grad_dtype=grad_dtype, scale=scale).run()
@@ -23,10 +23,27 @@ def _full_check(lengths, hq, hkv, d, seed, value_scale=1.0, grad_dtype=None, sca
     rdq, rdk, rdv = oracle.attn_bwd(f64(q), f64(k), f64(v), f64(do), lengths, s)
     assert_close("O", run.host("o"), ro)
     assert np.max(np.abs(run.host("lse") - rlse)) <= LSE_ABS
-    assert_close("dQ", run.host("dq"), rdq)
-    assert_close("dK", run.host("dk"), rdk)
-    assert_close("dV", run.host("dv"), rdv)
+    # magnitude_slack: packs outside the benchmark configurations' value range (several query heads per KV head and
+    # hundreds of rows push |dK|, |dV| above 10) add the bf16 rounding of P / dS at that magnitude to the max-abs bound
+    slack = (lambda ref: 2.0 ** -9 * float(np.max(np.abs(ref)))) if magnitude_slack else (lambda ref: 0.0)
+    assert_close("dQ", run.host("dq"), rdq, max_abs=gpu_util.MAX_ABS + slack(rdq))
+    assert_close("dK", run.host("dk"), rdk, max_abs=gpu_util.MAX_ABS + slack(rdk))
+    assert_close("dV", run.host("dv"), rdv, max_abs=gpu_util.MAX_ABS + slack(rdv))
     return run
+
+
+def test_random_packs():
+    """Thirty small packs with random lengths (including 0 and 1), head counts, group sizes and head dims (seeded)."""
+    rng = np.random.default_rng(4242)
+    for case in range(30):
+        n = int(rng.integers(1, 7))
+        lengths = [int(x) for x in rng.choice([0, 1, 2, 31, 32, 33, 63, 64, 65, 127, 128, 129, 200, 257, 400, 640], n)]
+        if sum(lengths) == 0:
+            lengths[0] = 3
+        hkv = int(rng.integers(1, 4))
+        hq = hkv * int(rng.choice([1, 2, 4]))
+        d = int(rng.choice([64, 128, 104, 80]))
+        _full_check(lengths, hq, hkv, d, seed=500 + case, magnitude_slack=True)
 
 
 def test_c1_tiny_pack():
