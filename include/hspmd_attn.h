@@ -172,8 +172,8 @@ hspmd_status hspmd_attn_plan_destroy(hspmd_attn_plan* plan);      /* NULL is acc
 int64_t hspmd_attn_plan_total_tokens(const hspmd_attn_plan* plan); /* -1 on NULL */
 int64_t hspmd_attn_plan_num_items(const hspmd_attn_plan* plan, hspmd_list_kind kind); /* slots incl. padding */
 
-/* Bytes of device workspace hspmd_attn_varlen_bwd needs (two fp32 [local_q_heads, T] arrays: D and
- * the rescaled logsumexp, plus a few constants). */
+/* Bytes of device workspace the backward needs (two fp32 [local_q_heads, T] arrays: the row statistics
+ * D = rowsum(dO * O) and the logsumexp in the form the kernels consume them, plus a few constants). */
 size_t hspmd_attn_bwd_workspace_bytes(const hspmd_attn_plan* plan);
 
 /*

@@ -7,10 +7,13 @@
 // P^T fragments straight back into MFMA as the B operand of O^T += V^T P^T, V^T being read
 // from the row-major V tile with the LDS transpose read.
 //
-// The loop is software-pipelined by one tile: while the VALU works through the softmax step of tile
-// kt, the MFMAs of S^T(kt+1) run; then the MFMAs of tile kt's P V.  K therefore runs one tile ahead of
-// V in LDS.  Tiles that lie wholly below the diagonal take code without any mask; only the last two
-// tiles of an item compare key and row indices.
+// The loop is software-pipelined by one tile: the MFMAs of S^T(kt+1) run under the exp work of tile kt's
+// first key block, the first MFMAs of tile kt's P V under that of its second key block.  K therefore
+// runs one tile ahead of V in LDS.  Both phases are written MFMA step by MFMA step (operand reads a few
+// steps ahead, a scheduling barrier after each step).  Tiles that lie wholly below the diagonal take
+// code without any mask; only the tiles on the diagonal compare key and row indices.  With BLOCK the
+// query rows and the keys are separate chunks and the diagonal is shifted (one step of context-parallel
+// attention): partial O in fp32, LSE = -inf for rows that see no key.
 #include "attn_device.hpp"
 #include "kernels.hpp"
 #include "schedule.hpp"
@@ -67,14 +70,13 @@ __device__ __forceinline__ float pair_max(float x) {
 
 // One iteration on key tile kt, whose scores are already in st.s:
 //   first  : VALU only: running max of tile kt; accumulator rescale if some lane's max moved
-//   phase A: MFMA S^T(kt+1) = K(kt+1) Q^T   |  VALU: exp2, row sum, bf16 pack of tile kt
-//   phase B: MFMA O^T += V(kt)^T P^T(kt)
+//   phase A: MFMA S^T(kt+1) = K(kt+1) Q^T   |  VALU: exp2, row sum, bf16 pack of tile kt's first key block
+//   phase B: MFMA O^T += V(kt)^T P^T(kt)     |  VALU: the same for its second key block, under the first MFMAs
 // kbuf: K tile kt+1; vbuf: V tile kt.  MASK: tile kt touches the diagonal (keys beyond a lane's own row get
 // weight 0); LAST: there is no tile kt+1.
 // SPREAD: the iteration also issues this wave's share of the copies of K(kt+2) and V(kt+1), both whole
-// tiles, one instruction at a time at fixed places among its LDS reads (copies are ordered against LDS
-// accesses and the reads are tied to the MFMAs by the scheduling hints).  Issued back to back after the
-// barrier, the copies of all waves queue up in front of the CU's one address unit.
+// tiles, one instruction per MFMA step of phase A.  Issued back to back after the barrier, the copies of
+// all waves queue up in front of the CU's one address unit.
 // BLOCK: a lane's row may have no visible key so far (its running max is still -inf): the maximum that the
 // exponentials are taken against is then replaced by 0, which keeps every weight and the rescale factor at 0.
 template <int D, bool MASK, bool LAST, bool SPREAD, bool BLOCK>

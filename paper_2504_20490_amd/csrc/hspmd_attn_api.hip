@@ -230,7 +230,7 @@ int64_t hspmd_attn_plan_num_items(const hspmd_attn_plan* plan, hspmd_list_kind k
 
 size_t hspmd_attn_bwd_workspace_bytes(const hspmd_attn_plan* plan) {
     if (!plan) return 0;
-    // D[Hq,T], LSE*log2(e) [Hq,T], and 16 floats of +inf
+    // -D [Hq,T], -LSE/scale [Hq,T], and 16 floats of -inf
     return (2 * (size_t)plan->q_heads * (size_t)plan->total_tokens + 16) * sizeof(float);
 }
 

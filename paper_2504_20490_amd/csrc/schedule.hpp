@@ -32,7 +32,7 @@ std::vector<hspmd_work_item> build_work_list(hspmd_list_kind kind, const int32_t
 struct PassCost {
     double launch_us, step_us, item_us;
 };
-// coefficients fitted to measurements on MI355X (fit_cost_model.py refits them); head_dim 64 or 128
+// coefficients fitted to measurements on MI355X (fit_cost_model.py refits them); head_dim = the tile width, 64 or 128
 PassCost pass_cost_coefficients(hspmd_list_kind kind, int32_t head_dim);
 double estimate_pass_us(hspmd_list_kind kind, const int32_t* cu, int32_t num_seqs, int32_t hq, int32_t hkv, int32_t head_dim);
 // the D pass of the backward (an HBM stream over O and dO)
