@@ -251,6 +251,71 @@ __device__ __forceinline__ void store_grad4(void* base, int64_t elem, bool f32, 
     }
 }
 
+// Coalesced store of a wave's 32 x D result tile.  The transposed products leave one ROW per lane pair (lane
+// l and l + 32 hold row l % 32: register 4 i4 + j of fragment db is column 32 db + 8 i4 + 4 (l / 32) + j), so a
+// direct store writes 64 scattered 8- or 16-byte pieces per instruction, one partial line each.  The tile goes
+// through a wave-private LDS area instead (32 rows of D elements, 16-byte chunks XOR-swizzled by the row so that
+// writes and reads are conflict-free) and every store instruction then writes whole rows.  The caller makes sure
+// no wave still reads the LDS area (a workgroup barrier after the last tile); the area itself is private to the
+// wave, and LDS accesses of one wave complete in order, so no barrier is needed between its writes and reads.
+//   valid_rows: rows 0 .. valid_rows-1 exist; head_dim: columns that exist in memory (<= D, a multiple of 8)
+//   ACCUM: add to what the destination holds (fp32 only)
+template <int D, bool ACCUM>
+__device__ __forceinline__ void store_tile_f32(char* wave_lds, const f32x16 (&acc)[D / 32], float mul, float* first_row,
+                                               int64_t row_stride, int valid_rows, int head_dim, int lane) {
+    constexpr int kChunks = D / 4;                // 16-byte chunks per row
+    const int r = lane & 31, hh = lane >> 5;
+#pragma unroll
+    for (int db = 0; db < D / 32; ++db)
+#pragma unroll
+        for (int i4 = 0; i4 < 4; ++i4) {
+            const int chunk = (db * 32 + i4 * 8 + hh * 4) / 4;
+            *reinterpret_cast<f32x4*>(wave_lds + (r * kChunks + (chunk ^ (r & (kChunks - 1)))) * 16) =
+                f32x4{acc[db][4 * i4 + 0] * mul, acc[db][4 * i4 + 1] * mul, acc[db][4 * i4 + 2] * mul, acc[db][4 * i4 + 3] * mul};
+        }
+    constexpr int kRowsPerInstr = 64 / kChunks;
+#pragma unroll
+    for (int it = 0; it < 32 / kRowsPerInstr; ++it) {
+        const int row = it * kRowsPerInstr + lane / kChunks, chunk = lane % kChunks;
+        if (row < valid_rows && chunk * 4 < head_dim) {
+            f32x4 v = *reinterpret_cast<const f32x4*>(wave_lds + (row * kChunks + (chunk ^ (row & (kChunks - 1)))) * 16);
+            f32x4* dst = reinterpret_cast<f32x4*>(first_row + row * row_stride + chunk * 4);
+            if constexpr (ACCUM) {
+                const f32x4 old = *dst;
+#pragma unroll
+                for (int j = 0; j < 4; ++j) v[j] += old[j];
+            }
+            *dst = v;
+        }
+    }
+}
+
+// The same for a bf16 destination: rows of D bf16 in LDS (8-byte pieces in, 16-byte chunks out).
+template <int D>
+__device__ __forceinline__ void store_tile_bf16(char* wave_lds, const f32x16 (&acc)[D / 32], float mul, uint16_t* first_row,
+                                                int64_t row_stride, int valid_rows, int head_dim, int lane) {
+    constexpr int kChunks = D / 8;                // 16-byte chunks (8 bf16) per row
+    const int r = lane & 31, hh = lane >> 5;
+#pragma unroll
+    for (int db = 0; db < D / 32; ++db)
+#pragma unroll
+        for (int i4 = 0; i4 < 4; ++i4) {
+            const int col = db * 32 + i4 * 8 + hh * 4;           // 4 elements = half a chunk
+            u32x2 w;
+            w[0] = pack_bf16(acc[db][4 * i4 + 0] * mul, acc[db][4 * i4 + 1] * mul);
+            w[1] = pack_bf16(acc[db][4 * i4 + 2] * mul, acc[db][4 * i4 + 3] * mul);
+            *reinterpret_cast<u32x2*>(wave_lds + (r * kChunks + ((col / 8) ^ (r & (kChunks - 1)))) * 16 + (col & 4) * 2) = w;
+        }
+    constexpr int kRowsPerInstr = 64 / kChunks;
+#pragma unroll
+    for (int it = 0; it < 32 / kRowsPerInstr; ++it) {
+        const int row = it * kRowsPerInstr + lane / kChunks, chunk = lane % kChunks;
+        if (row < valid_rows && chunk * 8 < head_dim)
+            *reinterpret_cast<u32x4*>(first_row + row * row_stride + chunk * 8) =
+                *reinterpret_cast<const u32x4*>(wave_lds + (row * kChunks + (chunk ^ (row & (kChunks - 1)))) * 16);
+    }
+}
+
 // Scheduling hint for one basic block: N times {1 MFMA, DS LDS reads, VA VALU instructions}, in that
 // order, as one pipeline with the given id (llvm.amdgcn.sched.group.barrier; arguments must be constants).
 // VMASK selects what counts as a VALU instruction: 0x002 plain VALU, 0x402 plain VALU and transcendentals
