@@ -243,32 +243,26 @@ __global__ __launch_bounds__(kThreads, 2) void bwd_dq_kernel(BwdParams p) {
     for (; kt < n_interior; ++kt) step(kt, std::false_type{});
     for (; kt < n_tiles; ++kt) step(kt, std::true_type{});
 
-    if (valid) {
+    if (p.grad_f32 != 0) {
+        // whole rows per store instruction, staged through LDS (free once every wave has left the tile loop)
+        __syncthreads();
+        char* wave_lds = lds + wave * (32 * D * 4);
+        float* first_row = static_cast<float*>(p.dq) + ((int64_t)(item.q_start + wave_row0) * p.q_heads + h) * hd;
+        const int rows = min(32, Lq - wave_row0);
+        if (BLOCK && p.dq_accumulate)
+            store_tile_f32<D, true>(wave_lds, acc, p.scale, first_row, (int64_t)p.q_heads * hd, rows, hd, lane);
+        else
+            store_tile_f32<D, false>(wave_lds, acc, p.scale, first_row, (int64_t)p.q_heads * hd, rows, hd, lane);
+    } else if (valid) {
         const int64_t row_elem = ((int64_t)(item.q_start + my_row) * p.q_heads + h) * hd;
-        if (BLOCK && p.dq_accumulate) {
-            // this block's share is added to what earlier blocks left (fp32)
-            float* row = static_cast<float*>(p.dq) + row_elem;
 #pragma unroll
-            for (int db = 0; db < DB; ++db)
+        for (int db = 0; db < DB; ++db)
 #pragma unroll
-                for (int i4 = 0; i4 < 4; ++i4) {
-                    if (db * 32 + i4 * 8 + hh * 4 >= hd) continue;
-                    f32x4* dst = reinterpret_cast<f32x4*>(row + db * 32 + i4 * 8 + hh * 4);
-                    f32x4 old = *dst;
-#pragma unroll
-                    for (int j = 0; j < 4; ++j) old[j] += acc[db][4 * i4 + j] * p.scale;
-                    *dst = old;
-                }
-        } else {
-#pragma unroll
-            for (int db = 0; db < DB; ++db)
-#pragma unroll
-                for (int i4 = 0; i4 < 4; ++i4)
-                    if (db * 32 + i4 * 8 + hh * 4 < hd)
-                        store_grad4(p.dq, row_elem + db * 32 + i4 * 8 + hh * 4, p.grad_f32 != 0,
+            for (int i4 = 0; i4 < 4; ++i4)
+                if (db * 32 + i4 * 8 + hh * 4 < hd)
+                    store_grad4(p.dq, row_elem + db * 32 + i4 * 8 + hh * 4, false,
                                 acc[db][4 * i4 + 0] * p.scale, acc[db][4 * i4 + 1] * p.scale,
                                 acc[db][4 * i4 + 2] * p.scale, acc[db][4 * i4 + 3] * p.scale);
-        }
     }
 }
 

@@ -341,37 +341,26 @@ __global__ __launch_bounds__(kThreads, 2) void fwd_kernel(FwdParams p) {
     step(kt, std::true_type{}, std::true_type{});   // the final tile touches the diagonal (always, when !BLOCK)
 
     const float l_row = st.l + partner32(st.l);
-    if (my_row < Lq) {
-        if constexpr (BLOCK) {
-            // partial result in fp32; a row that saw no key has l = 0 and m = -inf: O = 0, LSE = -inf
-            const float inv = l_row > 0.f ? 1.f / l_row : 0.f;
-            float* orow = p.o_f32 + ((int64_t)(item.q_start + my_row) * p.q_heads + h) * hd;
+    // O leaves through LDS (free once every wave has left the tile loop) so that every store instruction writes
+    // whole rows; a row that saw no key (BLOCK only) has l = 0 and m = -inf: O = 0, LSE = -inf
+    __syncthreads();
+    const float inv = (!BLOCK || l_row > 0.f) ? 1.f / l_row : 0.f;
+    const int rows = min(32, Lq - wave_row0);
+    const int64_t row0_elem = ((int64_t)(item.q_start + wave_row0) * p.q_heads + h) * hd;
+    // the normaliser differs per row (= per lane): scale the fragments in place, then store with factor 1
 #pragma unroll
-            for (int db = 0; db < DB; ++db)
+    for (int db = 0; db < DB; ++db)
 #pragma unroll
-                for (int i4 = 0; i4 < 4; ++i4)
-                    if (db * 32 + i4 * 8 + hh * 4 < hd)
-                        *reinterpret_cast<f32x4*>(orow + db * 32 + i4 * 8 + hh * 4) =
-                        f32x4{st.acc[db][4 * i4 + 0] * inv, st.acc[db][4 * i4 + 1] * inv, st.acc[db][4 * i4 + 2] * inv,
-                              st.acc[db][4 * i4 + 3] * inv};
-            if (hh == 0)
-                p.lse[(int64_t)h * p.total_tokens + item.q_start + my_row] =
-                    l_row > 0.f ? (st.m * c + __log2f(l_row)) * kLn2 : -INFINITY;
-        } else {
-            const float inv = 1.f / l_row;
-            uint16_t* orow = p.o + ((int64_t)(item.q_start + my_row) * p.q_heads + h) * hd;
-#pragma unroll
-            for (int db = 0; db < DB; ++db)
-#pragma unroll
-                for (int i4 = 0; i4 < 4; ++i4) {
-                    u32x2 w;
-                    w[0] = pack_bf16(st.acc[db][4 * i4 + 0] * inv, st.acc[db][4 * i4 + 1] * inv);
-                    w[1] = pack_bf16(st.acc[db][4 * i4 + 2] * inv, st.acc[db][4 * i4 + 3] * inv);
-                    if (db * 32 + i4 * 8 + hh * 4 < hd) *reinterpret_cast<u32x2*>(orow + db * 32 + i4 * 8 + hh * 4) = w;
-                }
-            if (hh == 0) p.lse[(int64_t)h * p.total_tokens + item.q_start + my_row] = (st.m * c + __log2f(l_row)) * kLn2;
-        }
+        for (int i = 0; i < 16; ++i) st.acc[db][i] *= inv;
+    if constexpr (BLOCK) {
+        store_tile_f32<D, false>(lds + wave * (32 * D * 4), st.acc, 1.f, p.o_f32 + row0_elem, (int64_t)p.q_heads * hd, rows,
+                                 hd, lane);
+    } else {
+        store_tile_bf16<D>(lds + wave * (32 * D * 2), st.acc, 1.f, p.o + row0_elem, (int64_t)p.q_heads * hd, rows, hd, lane);
     }
+    if (my_row < Lq && hh == 0)
+        p.lse[(int64_t)h * p.total_tokens + item.q_start + my_row] =
+            (!BLOCK || l_row > 0.f) ? (st.m * c + __log2f(l_row)) * kLn2 : -INFINITY;
 }
 
 hipError_t launch_fwd(const FwdParams& p, int head_dim, int64_t num_items, bool block, hipStream_t stream) {
