@@ -208,6 +208,45 @@ hspmd_status hspmd_attn_varlen_bwd(const hspmd_attn_plan* plan, const void* q, c
                                    void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * Rotary position embedding around the attention of a pack.  The paper's models are Llama-style with RoPE as
+ * position encoding (experimental setup, model configuration table) and give no formula; this is the published
+ * definition in the rotate-half pairing: with theta_i = base^(-2i/head_dim), i = 0 .. head_dim/2-1, a token at
+ * position p INSIDE ITS SEQUENCE (positions restart at every sequence of the pack) has every head vector x of
+ * q and k replaced by
+ *     y_i = x_i cos(p theta_i) - x_{i+head_dim/2} sin(p theta_i),
+ *     y_{i+head_dim/2} = x_{i+head_dim/2} cos(p theta_i) + x_i sin(p theta_i).
+ * Division of the work: q and k are rotated by one elementwise kernel before the forward (hspmd_rope_qk; K and Q
+ * tiles are streamed many times by the attention kernels, so rotating them at tile load would repeat the work
+ * per tile); in the backward the transposed rotation of dQ and dK is applied inside the epilogues of the two
+ * passes (hspmd_attn_varlen_bwd_rope), which saves a pass over the gradients.
+ *
+ * hspmd_rope_table: fills a device table (cos, sin) pairs, fp32 [positions, head_dim/2, 2], evaluated in fp64.
+ *   table     device, hspmd_rope_table_bytes(positions, head_dim) bytes, 16-byte aligned, caller-owned
+ *   base      the frequency base (10000 in Llama); must be positive
+ * hspmd_rope_qk: q_out, k_out = rope(q), rope(k) (inverse != 0: the rotation by the opposite angle).
+ *   q, k, q_out, k_out  bf16, layouts and stride rules as in hspmd_attn_varlen_fwd, each with its own token
+ *                       stride; q_out == q and k_out == k (in place) are allowed, other overlaps are not
+ *   table_positions     positions the table holds; must be >= the longest sequence of the plan
+ *   Arithmetic in fp32, one rounding to bf16.  Packed plans only (not the block variant).
+ * hspmd_attn_varlen_bwd_rope: hspmd_attn_varlen_bwd where q and k are the ROTATED tensors the forward consumed
+ *   and dq, dk are returned with respect to the unrotated ones (dv is unaffected).  Other arguments, workspace and
+ *   errors as hspmd_attn_varlen_bwd.
+ * Errors: INVALID_ARG for NULL / misaligned pointers, bad strides, a table that is too short, a block plan;
+ * UNSUPPORTED for a head_dim outside the supported set.  Nothing is launched on error.
+ */
+size_t hspmd_rope_table_bytes(int32_t positions, int32_t head_dim);   /* 0 on bad arguments */
+hspmd_status hspmd_rope_table(float* table, int32_t positions, int32_t head_dim, double base, void* stream);
+hspmd_status hspmd_rope_qk(const hspmd_attn_plan* plan, const void* q, const void* k, int64_t q_token_stride,
+                           int64_t kv_token_stride, void* q_out, void* k_out, int64_t q_out_token_stride,
+                           int64_t kv_out_token_stride, const float* table, int32_t table_positions, int32_t inverse,
+                           void* stream);
+hspmd_status hspmd_attn_varlen_bwd_rope(const hspmd_attn_plan* plan, const void* q, const void* k, const void* v,
+                                        const void* o, const float* lse, const void* d_o, int64_t q_token_stride,
+                                        int64_t kv_token_stride, float softmax_scale, void* dq, void* dk, void* dv,
+                                        hspmd_grad_dtype grad_dtype, const float* table, int32_t table_positions,
+                                        void* workspace, size_t workspace_bytes, void* stream);
+
+/*
  * Predicted kernel time (milliseconds, MI355X) of forward and backward of a pack on this library's
  * kernels: the per-operator cost that the paper's planner needs when it dispatches mixed-length
  * sequences to pipelines by a cost model evaluated on the CPU (Appendix "Scenario-specific Planning",
@@ -300,12 +339,13 @@ hspmd_status hspmd_attn_block_bwd(const hspmd_attn_plan* plan, const void* q, co
  * calling process is bracketed by a pair of HIP events recorded on the launch stream.
  * hspmd_profile_read waits for the recorded events, adds each kernel's elapsed time and launch
  * count to the caller's arrays and forgets the records.
- *   kernel index: 0 forward, 1 backward D = rowsum(dO*O), 2 backward dQ pass, 3 backward dK/dV pass
+ *   kernel index: 0 forward, 1 backward D = rowsum(dO*O), 2 backward dQ pass, 3 backward dK/dV pass,
+ *                 4 rotary embedding of q and k
  *   ms, launches  host, [HSPMD_NUM_KERNELS] each, accumulated into (the caller zeroes them)
  * Not thread-safe: enable, launch and read from one thread.  Events are created on first use and
  * reused; enabling allocates nothing on the device.
  */
-#define HSPMD_NUM_KERNELS 4
+#define HSPMD_NUM_KERNELS 5
 hspmd_status hspmd_profile_enable(int32_t on);
 hspmd_status hspmd_profile_read(double* ms, int64_t* launches);
 const char* hspmd_kernel_name(int32_t kernel);   /* symbol-like name, NULL if out of range */

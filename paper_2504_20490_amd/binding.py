@@ -89,6 +89,17 @@ def load_library():
                                           ctypes.c_float, vp, vp, vp, ctypes.c_int, vp, ctypes.c_size_t, vp]
     lib.hspmd_profile_enable.restype = ctypes.c_int
     lib.hspmd_profile_enable.argtypes = [ctypes.c_int32]
+    lib.hspmd_rope_table_bytes.restype = ctypes.c_size_t
+    lib.hspmd_rope_table_bytes.argtypes = [ctypes.c_int32, ctypes.c_int32]
+    lib.hspmd_rope_table.restype = ctypes.c_int
+    lib.hspmd_rope_table.argtypes = [vp, ctypes.c_int32, ctypes.c_int32, ctypes.c_double, vp]
+    lib.hspmd_rope_qk.restype = ctypes.c_int
+    lib.hspmd_rope_qk.argtypes = [vp, vp, vp, ctypes.c_int64, ctypes.c_int64, vp, vp, ctypes.c_int64, ctypes.c_int64, vp,
+                                  ctypes.c_int32, ctypes.c_int32, vp]
+    lib.hspmd_attn_varlen_bwd_rope.restype = ctypes.c_int
+    lib.hspmd_attn_varlen_bwd_rope.argtypes = [vp, vp, vp, vp, vp, vp, vp, ctypes.c_int64, ctypes.c_int64,
+                                               ctypes.c_float, vp, vp, vp, ctypes.c_int, vp, ctypes.c_int32, vp,
+                                               ctypes.c_size_t, vp]
     lib.hspmd_attn_estimate_ms.restype = ctypes.c_int
     lib.hspmd_attn_estimate_ms.argtypes = [i32p, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32,
                                            ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_double)]
@@ -241,7 +252,44 @@ def attn_varlen_bwd(plan: Plan, q, k, v, o, lse, d_o, dq, dk, dv, workspace, sof
                                      _stream_handle(stream)))
 
 
-NUM_KERNELS = 4
+def _token_stride(x, heads: int, head_dim: int) -> int:
+    return x.stride(0) if x.dim() == 3 and x.shape[0] > 1 else heads * head_dim
+
+
+def rope_table_bytes(positions: int, head_dim: int) -> int:
+    return int(load_library().hspmd_rope_table_bytes(int(positions), int(head_dim)))
+
+
+def rope_table(table, positions: int, head_dim: int, base: float = 10000.0, stream=None) -> None:
+    """Fills `table` (device fp32 tensor of at least rope_table_bytes(positions, head_dim) bytes) with the
+    (cos, sin) pairs [positions, head_dim / 2, 2]."""
+    if table.numel() * table.element_size() < rope_table_bytes(positions, head_dim):
+        raise ValueError("table tensor is too small")
+    _check(load_library().hspmd_rope_table(_dev_ptr(table), int(positions), int(head_dim), float(base),
+                                           _stream_handle(stream)))
+
+
+def rope_qk(plan: Plan, q, k, q_out, k_out, table, table_positions: int, inverse: bool = False, stream=None) -> None:
+    """q_out, k_out = rope(q), rope(k) (in place when q_out is q and k_out is k)."""
+    _check(load_library().hspmd_rope_qk(plan.handle, _dev_ptr(q), _dev_ptr(k),
+                                        _token_stride(q, plan.q_heads, plan.head_dim),
+                                        _token_stride(k, plan.kv_heads, plan.head_dim), _dev_ptr(q_out), _dev_ptr(k_out),
+                                        _token_stride(q_out, plan.q_heads, plan.head_dim),
+                                        _token_stride(k_out, plan.kv_heads, plan.head_dim), _dev_ptr(table),
+                                        int(table_positions), 1 if inverse else 0, _stream_handle(stream)))
+
+
+def attn_varlen_bwd_rope(plan: Plan, q, k, v, o, lse, d_o, dq, dk, dv, workspace, table, table_positions: int,
+                         softmax_scale: float = 0.0, grad_dtype: int = GRAD_BF16, stream=None) -> None:
+    """attn_varlen_bwd for rotated q, k; dq and dk come back with respect to the unrotated tensors."""
+    _check(load_library().hspmd_attn_varlen_bwd_rope(
+        plan.handle, _dev_ptr(q), _dev_ptr(k), _dev_ptr(v), _dev_ptr(o), _dev_ptr(lse), _dev_ptr(d_o),
+        _token_stride(q, plan.q_heads, plan.head_dim), _token_stride(k, plan.kv_heads, plan.head_dim),
+        float(softmax_scale), _dev_ptr(dq), _dev_ptr(dk), _dev_ptr(dv), int(grad_dtype), _dev_ptr(table),
+        int(table_positions), _dev_ptr(workspace), workspace.numel() * workspace.element_size(), _stream_handle(stream)))
+
+
+NUM_KERNELS = 5
 
 
 def profile_enable(on: bool) -> None:

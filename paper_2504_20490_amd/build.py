@@ -7,7 +7,7 @@ import subprocess
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIBRARY = os.path.join(HERE, "libhspmd_attn.so")
-SOURCES = ["hspmd_attn_api.hip", "schedule.cpp", "fwd_kernel.hip", "bwd_kernels.hip", "bwd_dkv_kernel.hip", "merge_kernel.hip", "probe.hip"]
+SOURCES = ["hspmd_attn_api.hip", "schedule.cpp", "fwd_kernel.hip", "bwd_kernels.hip", "bwd_dkv_kernel.hip", "merge_kernel.hip", "probe.hip", "rope_kernel.hip"]
 HEADERS = ["attn_device.hpp", "kernels.hpp", "schedule.hpp", os.path.join("..", "..", "include", "hspmd_attn.h")]
 
 # Packed fp32 VALU forms are switched off for all device code of this library.

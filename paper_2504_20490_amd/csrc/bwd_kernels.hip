@@ -243,7 +243,14 @@ __global__ __launch_bounds__(kThreads, 2) void bwd_dq_kernel(BwdParams p) {
     for (; kt < n_interior; ++kt) step(kt, std::false_type{});
     for (; kt < n_tiles; ++kt) step(kt, std::true_type{});
 
-    if (p.grad_f32 != 0) {
+    if (!BLOCK && p.rope_table != nullptr) {
+        // dQ with respect to the queries before their rotary embedding; row positions = index in the sequence
+        __syncthreads();
+        store_tile_rope_transposed<D>(lds + wave * (32 * D * 4), acc, p.scale, p.dq,
+                                      ((int64_t)(item.q_start + wave_row0) * p.q_heads + h) * hd, p.grad_f32 != 0,
+                                      (int64_t)p.q_heads * hd, min(32, Lq - wave_row0), hd,
+                                      p.rope_table + (int64_t)wave_row0 * hd, lane);
+    } else if (p.grad_f32 != 0) {
         // whole rows per store instruction, staged through LDS (free once every wave has left the tile loop)
         __syncthreads();
         char* wave_lds = lds + wave * (32 * D * 4);

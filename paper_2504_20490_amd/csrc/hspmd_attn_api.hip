@@ -75,6 +75,7 @@ struct hspmd_attn_plan {
     int32_t num_seqs = 0;
     int32_t q_heads = 0, kv_heads = 0, head_dim = 0;
     int64_t total_tokens = 0;
+    int32_t max_seq_len = 0;
     int64_t count[3] = {0, 0, 0};
     hspmd_work_item* items[3] = {nullptr, nullptr, nullptr};   // device; three views into one allocation
     void* device_block = nullptr;
@@ -161,6 +162,8 @@ hspmd_status hspmd_attn_plan_create_ordered(const int32_t* cu_seqlens_host, int3
     plan->kv_heads = local_kv_heads;
     plan->head_dim = head_dim;
     plan->total_tokens = cu_seqlens_host[num_seqs];
+    for (int32_t i = 0; i < num_seqs; ++i)
+        plan->max_seq_len = std::max(plan->max_seq_len, cu_seqlens_host[i + 1] - cu_seqlens_host[i]);
     // the three lists back to back in one host vector -> one allocation, one copy, one synchronisation
     std::vector<hspmd_work_item> all;
     size_t offset[3] = {0, 0, 0};
@@ -274,11 +277,11 @@ hspmd_status hspmd_attn_varlen_fwd(const hspmd_attn_plan* plan, const void* q, c
     return HSPMD_OK;
 }
 
-hspmd_status hspmd_attn_varlen_bwd(const hspmd_attn_plan* plan, const void* q, const void* k, const void* v,
-                                   const void* o, const float* lse, const void* d_o,
-                                   int64_t q_token_stride, int64_t kv_token_stride, float softmax_scale,
-                                   void* dq, void* dk, void* dv, hspmd_grad_dtype grad_dtype,
-                                   void* workspace, size_t workspace_bytes, void* stream) {
+// rope_table == NULL: plain backward
+static hspmd_status varlen_bwd(const hspmd_attn_plan* plan, const void* q, const void* k, const void* v, const void* o,
+                               const float* lse, const void* d_o, int64_t q_token_stride, int64_t kv_token_stride,
+                               float softmax_scale, void* dq, void* dk, void* dv, hspmd_grad_dtype grad_dtype,
+                               const float* rope_table, void* workspace, size_t workspace_bytes, void* stream) {
     if (!plan) return fail(HSPMD_ERR_INVALID_ARG, "plan is NULL");
     if (plan->is_block) return fail(HSPMD_ERR_INVALID_ARG, "plan was made by hspmd_attn_block_plan_create");
     if (grad_dtype != HSPMD_GRAD_BF16 && grad_dtype != HSPMD_GRAD_F32)
@@ -315,6 +318,7 @@ hspmd_status hspmd_attn_varlen_bwd(const hspmd_attn_plan* plan, const void* q, c
     p.group = plan->q_heads / plan->kv_heads;
     p.head_dim = plan->head_dim;
     p.grad_f32 = grad_dtype == HSPMD_GRAD_F32 ? 1 : 0;
+    p.rope_table = rope_table;
     p.scale = scale;
     p.scale_log2 = scale * 1.4426950408889634f;
     hipStream_t s = static_cast<hipStream_t>(stream);
@@ -327,6 +331,86 @@ hspmd_status hspmd_attn_varlen_bwd(const hspmd_attn_plan* plan, const void* q, c
     e = timed_launch(3, s, [&] { return hspmd::launch_bwd_dkv(p, plan->head_dim, plan->count[HSPMD_LIST_DKV], false, s); });
     if (e != hipSuccess) return fail_hip(e, "backward dK/dV launch");
     return HSPMD_OK;
+}
+
+hspmd_status hspmd_attn_varlen_bwd(const hspmd_attn_plan* plan, const void* q, const void* k, const void* v,
+                                   const void* o, const float* lse, const void* d_o,
+                                   int64_t q_token_stride, int64_t kv_token_stride, float softmax_scale,
+                                   void* dq, void* dk, void* dv, hspmd_grad_dtype grad_dtype,
+                                   void* workspace, size_t workspace_bytes, void* stream) {
+    return varlen_bwd(plan, q, k, v, o, lse, d_o, q_token_stride, kv_token_stride, softmax_scale, dq, dk, dv, grad_dtype,
+                      nullptr, workspace, workspace_bytes, stream);
+}
+
+// ---- rotary position embedding ---------------------------------------------------------------------------------
+
+static hspmd_status check_rope_table(const hspmd_attn_plan* plan, const float* table, int32_t table_positions) {
+    if (!plan) return fail(HSPMD_ERR_INVALID_ARG, "plan is NULL");
+    if (plan->is_block) return fail(HSPMD_ERR_INVALID_ARG, "plan was made by hspmd_attn_block_plan_create");
+    if (plan->total_tokens == 0) return HSPMD_OK;
+    if (!table) return fail(HSPMD_ERR_INVALID_ARG, "rope table is NULL");
+    if (!aligned16(table)) return fail(HSPMD_ERR_INVALID_ARG, "rope table must be 16-byte aligned");
+    if (table_positions < plan->max_seq_len)
+        return fail(HSPMD_ERR_INVALID_ARG, "rope table has fewer positions than the longest sequence of the plan");
+    return HSPMD_OK;
+}
+
+size_t hspmd_rope_table_bytes(int32_t positions, int32_t head_dim) {
+    if (positions < 0 || !supported_head_dim(head_dim)) return 0;
+    return (size_t)positions * (size_t)(head_dim / 2) * 2 * sizeof(float);
+}
+
+hspmd_status hspmd_rope_table(float* table, int32_t positions, int32_t head_dim, double base, void* stream) {
+    if (positions < 0) return fail(HSPMD_ERR_INVALID_ARG, "positions is negative");
+    if (!supported_head_dim(head_dim)) return fail(HSPMD_ERR_UNSUPPORTED, "head_dim must be a multiple of 8 between 8 and 128");
+    if (!(base > 0.0) || !std::isfinite(base)) return fail(HSPMD_ERR_INVALID_ARG, "base must be positive and finite");
+    if (positions == 0) return HSPMD_OK;
+    if (!table) return fail(HSPMD_ERR_INVALID_ARG, "table is NULL");
+    if (!aligned16(table)) return fail(HSPMD_ERR_INVALID_ARG, "table must be 16-byte aligned");
+    const hipError_t e = hspmd::launch_rope_table(table, positions, head_dim, base, static_cast<hipStream_t>(stream));
+    if (e != hipSuccess) return fail_hip(e, "rope table launch");
+    return HSPMD_OK;
+}
+
+hspmd_status hspmd_rope_qk(const hspmd_attn_plan* plan, const void* q, const void* k, int64_t q_token_stride,
+                           int64_t kv_token_stride, void* q_out, void* k_out, int64_t q_out_token_stride,
+                           int64_t kv_out_token_stride, const float* table, int32_t table_positions, int32_t inverse,
+                           void* stream) {
+    if (hspmd_status rc = check_rope_table(plan, table, table_positions)) return rc;
+    if (plan->total_tokens == 0) return HSPMD_OK;
+    if (!q || !k || !q_out || !k_out) return fail(HSPMD_ERR_INVALID_ARG, "null tensor pointer");
+    if (!aligned16(q) || !aligned16(k) || !aligned16(q_out) || !aligned16(k_out))
+        return fail(HSPMD_ERR_INVALID_ARG, "q, k, q_out, k_out must be 16-byte aligned");
+    if (hspmd_status rc = check_strides(plan, q_token_stride, kv_token_stride)) return rc;
+    if (hspmd_status rc = check_strides(plan, q_out_token_stride, kv_out_token_stride)) return rc;
+    hspmd::RopeParams p{};
+    p.q = static_cast<const uint16_t*>(q);
+    p.k = static_cast<const uint16_t*>(k);
+    p.q_out = static_cast<uint16_t*>(q_out);
+    p.k_out = static_cast<uint16_t*>(k_out);
+    p.table = table;
+    p.items = plan->items[HSPMD_LIST_FWD];
+    p.q_stride = q_token_stride;
+    p.kv_stride = kv_token_stride;
+    p.q_out_stride = q_out_token_stride;
+    p.kv_out_stride = kv_out_token_stride;
+    p.group = plan->q_heads / plan->kv_heads;
+    p.head_dim = plan->head_dim;
+    p.sin_sign = inverse ? -1.f : 1.f;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const hipError_t e = timed_launch(4, s, [&] { return hspmd::launch_rope_qk(p, plan->count[HSPMD_LIST_FWD], s); });
+    if (e != hipSuccess) return fail_hip(e, "rope launch");
+    return HSPMD_OK;
+}
+
+hspmd_status hspmd_attn_varlen_bwd_rope(const hspmd_attn_plan* plan, const void* q, const void* k, const void* v,
+                                        const void* o, const float* lse, const void* d_o, int64_t q_token_stride,
+                                        int64_t kv_token_stride, float softmax_scale, void* dq, void* dk, void* dv,
+                                        hspmd_grad_dtype grad_dtype, const float* table, int32_t table_positions,
+                                        void* workspace, size_t workspace_bytes, void* stream) {
+    if (hspmd_status rc = check_rope_table(plan, table, table_positions)) return rc;
+    return varlen_bwd(plan, q, k, v, o, lse, d_o, q_token_stride, kv_token_stride, softmax_scale, dq, dk, dv, grad_dtype,
+                      table, workspace, workspace_bytes, stream);
 }
 
 hspmd_status hspmd_attn_estimate_ms(const int32_t* cu_seqlens, int32_t num_seqs, int32_t local_q_heads,
@@ -613,7 +697,7 @@ hspmd_status hspmd_probe_mfma_tflops(int64_t mfma_per_wave, void* scratch_out, s
 
 const char* hspmd_kernel_name(int32_t kernel) {
     static const char* const names[HSPMD_NUM_KERNELS] = {"fwd_kernel", "bwd_dsum_kernel", "bwd_dq_kernel",
-                                                         "bwd_dkv_kernel"};
+                                                         "bwd_dkv_kernel", "rope_qk_kernel"};
     return (kernel >= 0 && kernel < HSPMD_NUM_KERNELS) ? names[kernel] : nullptr;
 }
 

@@ -44,6 +44,8 @@ struct BwdParams {
     int32_t head_dim;              // elements per head in memory (a multiple of 8, at most the kernel's tile width)
     int32_t grad_f32;              // 1: gradients are fp32, 0: bf16
     int32_t dq_accumulate;         // block variant only: dq += this block's share (fp32) instead of dq = ...
+    const float* rope_table;       // packed variant only, may be NULL: (cos, sin) pairs [position][head_dim / 2]; dq and dk
+                                   // then leave as gradients with respect to the q and k BEFORE the rotary embedding
     float scale;                   // softmax_scale
     float scale_log2;              // softmax_scale * log2(e)
 };
@@ -72,6 +74,21 @@ struct MergeParams {
     int32_t q_heads, head_dim;
 };
 hipError_t launch_merge(const MergeParams& p, hipStream_t stream);
+
+// rotary position embedding (RoPE, rotate-half pairing) of the q and k of a pack, walking the forward work list
+struct RopeParams {
+    const uint16_t* q;
+    const uint16_t* k;
+    uint16_t* q_out;
+    uint16_t* k_out;
+    const float* table;            // (cos, sin) pairs [position][head_dim / 2]
+    const hspmd_work_item* items;  // forward list: every (q tile, q head) once
+    int64_t q_stride, kv_stride, q_out_stride, kv_out_stride;   // token strides in elements
+    int32_t group, head_dim;
+    float sin_sign;                // +1: rotate, -1: rotate back
+};
+hipError_t launch_rope_table(float* table, int32_t positions, int32_t head_dim, double base, hipStream_t stream);
+hipError_t launch_rope_qk(const RopeParams& p, int64_t num_items, hipStream_t stream);
 
 // matrix-core rate probe: `grid` workgroups of kProbeThreads threads, each wave issues 16 * rounds MFMAs and
 // every thread writes one float to out[grid * kProbeThreads]

@@ -1,0 +1,102 @@
+// Rotary position embedding of the q and k of a pack (model configuration table of the paper: position encoding
+// RoPE), and the table of cos / sin values that this kernel and the backward epilogues read.
+//
+// Pairing: column i with column i + head_dim/2 ("rotate-half"); a token at position p of its sequence turns the
+// pair by p * theta_i, theta_i = base^(-2i/head_dim).  HBM-bound: every q and k element is read once and written
+// once; the table row of a position is shared by all heads and stays in L2.
+#include "attn_device.hpp"
+#include "kernels.hpp"
+#include "schedule.hpp"
+
+namespace hspmd {
+
+namespace {
+
+constexpr int kRopeThreads = 256;
+
+// table[p][i] = (cos(p theta_i), sin(p theta_i)), evaluated in fp64 and rounded once
+__global__ __launch_bounds__(kRopeThreads) void rope_table_kernel(float* table, int64_t entries, int half, int head_dim,
+                                                                  double base) {
+    const int64_t e = (int64_t)blockIdx.x * kRopeThreads + threadIdx.x;
+    if (e >= entries) return;
+    const int64_t pos = e / half;
+    const int i = (int)(e % half);
+    const double theta = pow(base, -2.0 * (double)i / (double)head_dim);
+    double s, c;
+    sincos((double)pos * theta, &s, &c);
+    *reinterpret_cast<float2*>(table + 2 * e) = make_float2((float)c, (float)s);
+}
+
+// VEC consecutive columns of the low half and their partners of the high half, one token, one head
+template <int VEC>
+__device__ __forceinline__ void rotate_piece(const uint16_t* src, uint16_t* dst, int half, const float* cs, float sin_sign) {
+    using Raw = typename std::conditional<VEC == 8, u32x4, u32x2>::type;
+    const Raw lo = *reinterpret_cast<const Raw*>(src);
+    const Raw hi = *reinterpret_cast<const Raw*>(src + half);
+    f32x4 t[VEC / 2];
+#pragma unroll
+    for (int j = 0; j < VEC / 2; ++j) t[j] = *reinterpret_cast<const f32x4*>(cs + 4 * j);   // (cos, sin) of two columns
+    Raw out_lo, out_hi;
+#pragma unroll
+    for (int j = 0; j < VEC / 2; ++j) {
+        float y_lo[2], y_hi[2];
+#pragma unroll
+        for (int e = 0; e < 2; ++e) {
+            // bf16 -> fp32 is a shift into the high half of the word
+            const float a = __uint_as_float(e == 0 ? lo[j] << 16 : lo[j] & 0xffff0000u);
+            const float b = __uint_as_float(e == 0 ? hi[j] << 16 : hi[j] & 0xffff0000u);
+            const float c = t[j][2 * e], s = t[j][2 * e + 1] * sin_sign;
+            y_lo[e] = a * c - b * s;
+            y_hi[e] = b * c + a * s;
+        }
+        out_lo[j] = pack_bf16(y_lo[0], y_lo[1]);
+        out_hi[j] = pack_bf16(y_hi[0], y_hi[1]);
+    }
+    *reinterpret_cast<Raw*>(dst) = out_lo;
+    *reinterpret_cast<Raw*>(dst + half) = out_hi;
+}
+
+// One workgroup per item of the forward list: the item's 128 rows of one q head, and of the KV head as well when
+// the q head is the first of its group.  In place (q_out == q) is fine: a thread reads what it writes.
+template <int VEC>
+__global__ __launch_bounds__(kRopeThreads) void rope_qk_kernel(RopeParams p) {
+    const hspmd_work_item item = p.items[blockIdx.x];
+    if (item.tile < 0) return;   // padding slot
+    const int hd = p.head_dim, half = hd / 2;
+    const int pieces = half / VEC;   // per row
+    const int row0 = item.tile * kFwdQTile;
+    const int rows = min(kFwdQTile, item.seq_len - row0);
+    const bool with_k = item.head % p.group == 0;
+    const int kv_head = item.head / p.group;
+    for (int e = threadIdx.x; e < rows * pieces; e += kRopeThreads) {
+        const int r = e / pieces, c = (e % pieces) * VEC;
+        const int64_t token = (int64_t)item.token_start + row0 + r;
+        const float* cs = p.table + ((int64_t)(row0 + r) * half + c) * 2;
+        rotate_piece<VEC>(p.q + token * p.q_stride + (int64_t)item.head * hd + c,
+                          p.q_out + token * p.q_out_stride + (int64_t)item.head * hd + c, half, cs, p.sin_sign);
+        if (with_k)
+            rotate_piece<VEC>(p.k + token * p.kv_stride + (int64_t)kv_head * hd + c,
+                              p.k_out + token * p.kv_out_stride + (int64_t)kv_head * hd + c, half, cs, p.sin_sign);
+    }
+}
+
+}  // namespace
+
+hipError_t launch_rope_table(float* table, int32_t positions, int32_t head_dim, double base, hipStream_t stream) {
+    const int64_t entries = (int64_t)positions * (head_dim / 2);
+    if (entries == 0) return hipSuccess;
+    const dim3 grid((unsigned)((entries + kRopeThreads - 1) / kRopeThreads)), threads(kRopeThreads);
+    hipLaunchKernelGGL(rope_table_kernel, grid, threads, 0, stream, table, entries, head_dim / 2, head_dim, base);
+    return hipGetLastError();
+}
+
+hipError_t launch_rope_qk(const RopeParams& p, int64_t num_items, hipStream_t stream) {
+    if (num_items == 0) return hipSuccess;
+    const dim3 grid((unsigned)num_items), threads(kRopeThreads);
+    // 16-byte pieces when half a head is a whole number of them, 8-byte pieces otherwise (head_dim is a multiple of 8)
+    if ((p.head_dim / 2) % 8 == 0) hipLaunchKernelGGL(rope_qk_kernel<8>, grid, threads, 0, stream, p);
+    else hipLaunchKernelGGL(rope_qk_kernel<4>, grid, threads, 0, stream, p);
+    return hipGetLastError();
+}
+
+}  // namespace hspmd

@@ -1,0 +1,237 @@
+"""GPU parity of the rotary-embedding entry points against the fp64 oracle (oracle/rope.py around the packed
+attention oracle): the cos/sin table, the q/k rotation kernel, the backward with the transposed rotation fused
+into its epilogues, the whole chain, and argument validation.  Everything goes through the C ABI."""
+import numpy as np
+import pytest
+
+import hspmd_workloads as w
+import oracle
+from oracle import rope as orope
+
+import gpu_util
+from gpu_util import GpuRun, assert_close, default_scale, f64, make_case, to_dev
+
+pytestmark = pytest.mark.gpu
+
+RAGGED = [17, 300, 1, 129, 0, 64]
+BASE = 10000.0
+
+
+def _torch():
+    import torch
+    return torch
+
+
+def _table(positions, d, base=BASE):
+    import paper_2504_20490_amd as A
+    torch = _torch()
+    t = torch.full((max(positions, 1), d // 2, 2), float("nan"), dtype=torch.float32, device="cuda")
+    A.rope_table(t, positions, d, base)
+    return t
+
+
+def _bits(t):
+    """bf16 device tensor -> uint16 bit patterns on the host."""
+    torch = _torch()
+    return t.contiguous().view(torch.int16).cpu().numpy().view(np.uint16)
+
+
+def _assert_rounded(name, got_bits, ref):
+    """got is the fp32 result rounded once to bf16: half an ulp (2^-9 relative) plus the fp32 arithmetic."""
+    got = f64(got_bits)
+    assert not np.isnan(got).any(), f"{name}: NaN"
+    bound = 2.0 ** -8 * np.abs(ref) + 1e-5
+    worst = float(np.max(np.abs(got - ref) - bound)) if ref.size else -1.0
+    assert worst <= 0.0, f"{name}: {worst:.3e} above the bf16 rounding bound"
+
+
+@pytest.mark.parametrize("d,base", [(128, 10000.0), (104, 10000.0), (64, 500000.0), (8, 10000.0)])
+def test_table_matches_fp64_cos_and_sin(d, base):
+    positions = 5000
+    t = _table(positions, d, base).cpu().numpy().astype(np.float64)
+    a = orope.angles(np.arange(positions), d, base)
+    # fp32 rounding of a value in [-1, 1] is at most 2^-25 away; the fp64 evaluation on the device adds next to nothing
+    assert np.max(np.abs(t[..., 0] - np.cos(a))) <= 6e-8
+    assert np.max(np.abs(t[..., 1] - np.sin(a))) <= 6e-8
+
+
+@pytest.mark.parametrize("hq,hkv,d", [(3, 3, 128), (4, 1, 128), (4, 2, 104), (6, 2, 64), (2, 2, 40), (2, 1, 8)])
+def test_rotation_of_q_and_k(hq, hkv, d):
+    import paper_2504_20490_amd as A
+    torch = _torch()
+    lengths = RAGGED
+    q, k, _, _ = make_case(lengths, hq, hkv, d, seed=300 + d + hq)
+    cu, _, T = A.build_cu_seqlens(lengths)
+    plan = A.Plan(cu, hq, hkv, d)
+    table = _table(max(lengths), d)
+    qd, kd = to_dev(q), to_dev(k)
+    qo = torch.full_like(qd, float("nan")); ko = torch.full_like(kd, float("nan"))
+    A.rope_qk(plan, qd, kd, qo, ko, table, max(lengths))
+    torch.cuda.synchronize()
+    pos = orope.positions_of(lengths)
+    _assert_rounded("rope(q)", _bits(qo), orope.rope(f64(q), pos, BASE))
+    _assert_rounded("rope(k)", _bits(ko), orope.rope(f64(k), pos, BASE))
+    assert np.array_equal(_bits(qd), q) and np.array_equal(_bits(kd), k)       # inputs untouched
+    # in place gives the same bits; the inverse rotation brings the inputs back up to two roundings
+    q2, k2 = qd.clone(), kd.clone()
+    A.rope_qk(plan, q2, k2, q2, k2, table, max(lengths))
+    torch.cuda.synchronize()
+    assert np.array_equal(_bits(q2), _bits(qo)) and np.array_equal(_bits(k2), _bits(ko))
+    A.rope_qk(plan, q2, k2, q2, k2, table, max(lengths), inverse=True)
+    torch.cuda.synchronize()
+    norm = np.sqrt(f64(q)[..., : d // 2] ** 2 + f64(q)[..., d // 2:] ** 2)       # a pair's rounding error scales with its norm
+    err = np.abs(f64(_bits(q2)) - f64(q))
+    assert np.max(err - 2.0 ** -7 * np.concatenate([norm, norm], axis=-1) - 1e-5) <= 0.0
+
+
+def test_rotation_on_views_into_a_fused_projection_output():
+    """q and k as strided views of one [T, (Hq + 2 Hkv) d] buffer, rotated in place; v and the gaps stay untouched."""
+    import paper_2504_20490_amd as A
+    torch = _torch()
+    lengths, hq, hkv, d = [200, 77], 4, 2, 128
+    q, k, v, _ = make_case(lengths, hq, hkv, d, seed=321)
+    T = sum(lengths)
+    fused = torch.zeros(T, (hq + 2 * hkv) * d, dtype=torch.bfloat16, device="cuda")
+    qv = fused[:, : hq * d].view(T, hq, d)
+    kv = fused[:, hq * d: (hq + hkv) * d].view(T, hkv, d)
+    vv = fused[:, (hq + hkv) * d:].view(T, hkv, d)
+    qv.copy_(to_dev(q)); kv.copy_(to_dev(k)); vv.copy_(to_dev(v))
+    cu, _, _ = A.build_cu_seqlens(lengths)
+    plan = A.Plan(cu, hq, hkv, d)
+    table = _table(256, d)
+    A.rope_qk(plan, qv, kv, qv, kv, table, 256)
+    torch.cuda.synchronize()
+    pos = orope.positions_of(lengths)
+    _assert_rounded("rope(q) view", _bits(qv), orope.rope(f64(q), pos, BASE))
+    _assert_rounded("rope(k) view", _bits(kv), orope.rope(f64(k), pos, BASE))
+    assert np.array_equal(_bits(vv), v)
+
+
+def _bwd_rope(run, table, positions, grad_dtype):
+    run.A.attn_varlen_bwd_rope(run.plan, run.q, run.k, run.v, run.o, run.lse, run.do, run.dq, run.dk, run.dv, run.ws,
+                               table, positions, run.scale, grad_dtype)
+    _torch().cuda.synchronize()
+
+
+@pytest.mark.parametrize("hq,hkv,d,grad", [(3, 3, 128, "f32"), (4, 2, 128, "bf16"), (4, 2, 104, "f32"), (6, 2, 64, "f32"),
+                                           (2, 2, 40, "bf16"), (2, 1, 8, "f32")])
+def test_backward_returns_gradients_before_the_rotation(hq, hkv, d, grad):
+    """q, k here are what the forward consumed (any bf16 tensors serve as 'rotated'); the oracle turns the
+    gradients of the attention oracle back.  dV must equal the plain backward's bit for bit."""
+    import paper_2504_20490_amd as A
+    lengths = RAGGED
+    q, k, v, do = make_case(lengths, hq, hkv, d, seed=400 + d + hq)
+    gd = A.GRAD_F32 if grad == "f32" else A.GRAD_BF16
+    run = GpuRun(lengths, q, k, v, do, grad_dtype=gd).run()
+    plain = {n: run.host(n).copy() for n in ("dq", "dk", "dv")}
+    for t in (run.dq, run.dk, run.dv):
+        t.fill_(float("nan"))
+    table = _table(max(lengths), d)
+    _bwd_rope(run, table, max(lengths), gd)
+    s = default_scale(d)
+    rdq, rdk, rdv = oracle.attn_bwd(f64(q), f64(k), f64(v), f64(do), lengths, s)
+    pos = orope.positions_of(lengths)
+    gpu_util.CONTEXT["case"] = f"rope_bwd_h{hq}_{hkv}_d{d}_{grad}"
+    assert_close("dQ before rope", run.host("dq"), orope.rope_transposed(rdq, pos, BASE))
+    assert_close("dK before rope", run.host("dk"), orope.rope_transposed(rdk, pos, BASE))
+    assert_close("dV", run.host("dv"), rdv)
+    assert np.array_equal(run.host("dv"), plain["dv"])
+    if grad == "f32":
+        # the epilogue alone: the plain pass's fp32 gradients, turned back in fp64, differ by fp32 rounding only
+        for name in ("dq", "dk"):
+            want = orope.rope_transposed(plain[name], pos, BASE)
+            assert np.max(np.abs(run.host(name) - want)) <= 2e-6 * max(1.0, float(np.max(np.abs(want))))
+
+
+@pytest.mark.parametrize("hq,hkv,d", [(4, 2, 128), (2, 2, 64)])
+def test_whole_chain_from_unrotated_inputs(hq, hkv, d):
+    """rope_qk -> forward -> backward with fused transposed rotation, against the fp64 chain on the same bf16
+    inputs with no intermediate rounding."""
+    import paper_2504_20490_amd as A
+    torch = _torch()
+    lengths = [700, 45, 260]
+    q, k, v, do = make_case(lengths, hq, hkv, d, seed=500 + d)
+    run = GpuRun(lengths, q, k, v, do)
+    table = _table(1024, d)
+    A.rope_qk(run.plan, run.q, run.k, run.q, run.k, table, 1024)
+    run.forward()
+    _bwd_rope(run, table, 1024, A.GRAD_F32)
+    pos = orope.positions_of(lengths)
+    s = default_scale(d)
+    qr, kr = orope.rope(f64(q), pos, BASE), orope.rope(f64(k), pos, BASE)
+    ro, rlse = oracle.attn_fwd(qr, kr, f64(v), lengths, s)
+    rdq, rdk, rdv = oracle.attn_bwd(qr, kr, f64(v), f64(do), lengths, s)
+    gpu_util.CONTEXT["case"] = f"rope_chain_h{hq}_{hkv}_d{d}"
+    assert_close("O", run.host("o"), ro)
+    assert np.max(np.abs(run.host("lse") - rlse)) <= 5e-3     # the rotated q, k are rounded to bf16 before the scores
+    assert_close("dQ", run.host("dq"), orope.rope_transposed(rdq, pos, BASE))
+    assert_close("dK", run.host("dk"), orope.rope_transposed(rdk, pos, BASE))
+    assert_close("dV", run.host("dv"), rdv)
+
+
+def test_full_size_pack_on_sampled_rows_and_keys():
+    """The 32k-token mixed-length pack with 24 of 40 heads (the configuration the benchmark times): rotation and
+    fused backward checked on sampled rows / keys that the oracle computes one by one."""
+    import paper_2504_20490_amd as A
+    torch = _torch()
+    cfg = w.config_by_name("C4")
+    lengths = w.lengths_for(cfg)
+    hq, hkv, d = cfg.q_heads, cfg.kv_heads, cfg.head_dim
+    q, k, v, do = make_case(lengths, hq, hkv, d, seed=cfg.value_seed, value_scale=cfg.value_scale)
+    run = GpuRun(lengths, q, k, v, do)
+    positions = max(lengths)
+    table = _table(positions, d)
+    A.rope_qk(run.plan, run.q, run.k, run.q, run.k, table, positions)
+    torch.cuda.synchronize()
+    pos = orope.positions_of(lengths)
+    rng = np.random.default_rng(5)
+    ends = np.cumsum(lengths)
+    rows = np.unique(np.concatenate([rng.integers(0, ends[-1], 12), ends - 1, ends[:-1], [0]])).astype(np.int32)[:24]
+    qb, kb = _bits(run.q), _bits(run.k)
+    _assert_rounded("rope(q) rows", qb[rows], orope.rope(f64(q[rows]), pos[rows], BASE))
+    _assert_rounded("rope(k) rows", kb[rows], orope.rope(f64(k[rows]), pos[rows], BASE))
+    run.forward()
+    _bwd_rope(run, table, positions, A.GRAD_F32)
+    s = default_scale(d)
+    heads = rng.integers(0, hq, len(rows)).astype(np.int32)
+    ro, rlse, rdq = oracle.attn_rows(f64(qb), f64(kb), f64(v), f64(do), lengths, s, rows, heads)
+    gpu_util.CONTEXT["case"] = "rope_C4"
+    assert_close("O rows", run.host("o")[rows, heads], ro)
+    dq_rows = orope.rope_transposed(rdq[:, None, :], pos[rows], BASE)[:, 0, :]
+    assert_close("dQ rows", run.host("dq")[rows, heads], dq_rows)
+    kvh = rng.integers(0, hkv, len(rows)).astype(np.int32)
+    rdk, rdv = oracle.attn_keys(f64(qb), f64(kb), f64(v), f64(do), lengths, s, rows, kvh)
+    dk_rows = orope.rope_transposed(rdk[:, None, :], pos[rows], BASE)[:, 0, :]
+    assert_close("dK keys", run.host("dk")[rows, kvh], dk_rows)
+    assert_close("dV keys", run.host("dv")[rows, kvh], rdv)
+    assert not np.isnan(run.host("dq")).any() and not np.isnan(run.host("dk")).any()
+
+
+def test_validation():
+    import paper_2504_20490_amd as A
+    torch = _torch()
+    lengths, hq, hkv, d = [100, 30], 2, 2, 64
+    q, k, v, do = make_case(lengths, hq, hkv, d, seed=1)
+    run = GpuRun(lengths, q, k, v, do).run()
+    table = _table(128, d)
+    with pytest.raises(A.HspmdError, match="fewer positions"):
+        A.rope_qk(run.plan, run.q, run.k, run.q, run.k, table, 99)
+    with pytest.raises(A.HspmdError, match="fewer positions"):
+        A.attn_varlen_bwd_rope(run.plan, run.q, run.k, run.v, run.o, run.lse, run.do, run.dq, run.dk, run.dv, run.ws,
+                               table, 64)
+    with pytest.raises(A.HspmdError, match="aligned"):
+        A.rope_qk(run.plan, run.q, run.k, run.q, run.k, table.view(-1)[1:], 100)
+    with pytest.raises(A.HspmdError, match="base"):
+        A.rope_table(table, 128, d, base=0.0)
+    with pytest.raises(A.HspmdError):
+        A.rope_table(table, 128, 100)
+    assert A.rope_table_bytes(128, 64) == 128 * 32 * 2 * 4 and A.rope_table_bytes(4, 100) == 0
+    cu, _, _ = A.build_cu_seqlens(lengths)
+    bplan = A.BlockPlan(cu, cu, [0, 0], [0, 0], hq, hkv, d)
+    with pytest.raises(A.HspmdError, match="block"):
+        A.rope_qk(bplan, run.q, run.k, run.q, run.k, table, 128)
+    # an empty pack is a no-op
+    cu0, _, _ = A.build_cu_seqlens([0, 0])
+    empty = A.Plan(cu0, hq, hkv, d)
+    z = torch.empty(0, hq, d, dtype=torch.bfloat16, device="cuda")
+    A.rope_qk(empty, z, z, z, z, table, 0)
