@@ -42,9 +42,10 @@ def read_traffic(kernel: str, workload: str):
     return None
 
 
-def cpu_baseline(cfg, lengths, q, k, v, do):
+def cpu_baseline(cfg, lengths, q, k, v, do, rope=False):
     """The fp64 oracle, as it stands, on a bounded sample of the same pack: whole sequences of the
-    pack (shortest first, up to a pair budget) and eight KV groups, forward + backward."""
+    pack (shortest first, up to a pair budget) and eight KV groups, forward + backward (with `rope`:
+    around the rotary-embedding oracle)."""
     import numpy as np
     import hspmd_workloads as w
     import oracle
@@ -67,8 +68,14 @@ def cpu_baseline(cfg, lengths, q, k, v, do):
     sl = [lengths[i] for i in chosen]
     s = 1.0 / math.sqrt(cfg.head_dim)
     t0 = time.perf_counter()
+    if rope:
+        from oracle import rope as orope
+        pos = orope.positions_of(sl)
+        qs, ks = orope.rope(qs, pos), orope.rope(ks, pos)
     oracle.attn_fwd(qs, ks, vs, sl, s)
-    oracle.attn_bwd(qs, ks, vs, dos, sl, s)
+    grads = oracle.attn_bwd(qs, ks, vs, dos, sl, s)
+    if rope:
+        orope.rope_transposed(grads[0], pos), orope.rope_transposed(grads[1], pos)
     dt = time.perf_counter() - t0
     flops = 3.5 * w.fwd_flops(sl, heads, cfg.head_dim)
     return {"value": flops / dt / 1e12, "unit": "TFLOP/s", "cores": oracle.num_threads(), "kind": "oracle",
@@ -165,7 +172,7 @@ def run_ring(args) -> int:
     fwd = 4.0 * d * hq * pairs
     ms_per_step = elapsed / args.steps * 1e3
     tflops = 3.5 * fwd / (ms_per_step * 1e-3) / 1e12
-    kern = {name: (ms / max(args.steps, 1)) for name, (ms, cnt) in prof.items()}     # per step: all blocks of a step
+    kern = {name: (ms / max(args.steps, 1)) for name, (ms, cnt) in prof.items() if cnt}     # per step: all blocks of a step
     dominant = max(GEMMS, key=lambda name: kern.get(name, 0.0))
     achieved = GEMMS[dominant] * (fwd / 2.0) / (kern[dominant] * 1e-3) / 1e12 if kern[dominant] > 0 else 0.0
     out = {
@@ -242,6 +249,9 @@ def main() -> int:
                     help="N > 0: measure the block variant instead: one rank of a context-parallel ring of N chunks "
                          "(see run_ring); the default 0 measures the packed path")
     ap.add_argument("--ring-rank", type=int, default=-1, help="which chunk the rank owns (default: the last, heaviest)")
+    ap.add_argument("--rope", action="store_true",
+                    help="add rotary embedding to the step: q, k rotated by the elementwise kernel before the forward, "
+                         "dQ and dK turned back inside the backward epilogues (side measurement)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU's share of the batch on one GPU; --gpus above 1 is not part of this "
@@ -282,9 +292,21 @@ def main() -> int:
     stream = torch.cuda.current_stream()
     order = {"xcd_cost": A.ORDER_XCD_COST, "natural": A.ORDER_NATURAL, "cost": A.ORDER_COST}[args.order]
 
+    if args.rope:
+        positions = max(lengths)
+        table = torch.empty(positions, d // 2, 2, dtype=torch.float32, device=dev)
+        A.rope_table(table, positions, d, 10000.0, stream=stream)      # per model, not per step
+        tq_rot, tk_rot = torch.empty_like(tq), torch.empty_like(tk)
+
     def step():
         cu, _, _ = A.build_cu_seqlens(lengths)                 # packed offsets
         plan = A.Plan(cu, hq, hkv, d, stream.cuda_stream, order=order)   # cost-sorted work lists
+        if args.rope:
+            A.rope_qk(plan, tq, tk, tq_rot, tk_rot, table, positions, stream=stream)
+            A.attn_varlen_fwd(plan, tq_rot, tk_rot, tv, o, lse, stream=stream)
+            A.attn_varlen_bwd_rope(plan, tq_rot, tk_rot, tv, o, lse, tdo, dq, dk, dv, ws, table, positions,
+                                   grad_dtype=grad, stream=stream)
+            return plan
         A.attn_varlen_fwd(plan, tq, tk, tv, o, lse, stream=stream)
         A.attn_varlen_bwd(plan, tq, tk, tv, o, lse, tdo, dq, dk, dv, ws, grad_dtype=grad, stream=stream)
         return plan
@@ -333,7 +355,7 @@ def main() -> int:
     tflops = useful / (ms_per_step * 1e-3) / 1e12
     pair_flops = fwd / 2.0          # one GEMM over the visible pairs: 2*d flops per pair and head
 
-    kern = {name: (ms / n if n else 0.0) for name, (ms, n) in prof.items()}
+    kern = {name: ms / n for name, (ms, n) in prof.items() if n}
     dominant = max(GEMMS, key=lambda name: kern.get(name, 0.0))
     dom_ms = kern[dominant]
     achieved = GEMMS[dominant] * pair_flops / (dom_ms * 1e-3) / 1e12 if dom_ms > 0 else 0.0
@@ -368,8 +390,18 @@ def main() -> int:
                      "note": f"{GEMMS[dominant]} GEMMs over the visible pairs; avg of {prof[dominant][1]} launches "
                              "timed with HIP events on the launch stream"},
     }
+    if args.rope:
+        # the rotation kernel is an HBM stream: q and k read once and written once
+        rope_bytes = 2.0 * 2.0 * T * (hq + hkv) * d
+        rope_ms = kern.get("rope_qk_kernel", 0.0)
+        gbs = rope_bytes / (rope_ms * 1e-3) / 1e9 if rope_ms > 0 else 0.0
+        out["metric"] = "varlen causal attn fwd+bwd with rotary embedding, attention TFLOP/s, 32k-token mix"
+        out["config"]["step"] = "build_cu_seqlens + work lists + rope(q, k) + fwd + bwd(D, dQ, dK/dV; dQ, dK turned back)"
+        out["rope_roofline"] = {"bound": "hbm", "kernel": "rope_qk_kernel", "achieved": round(gbs, 1), "peak": 8000.0,
+                                "unit": "GB/s", "frac": round(gbs / 8000.0, 4), "traffic": None,
+                                "bytes_per_launch": rope_bytes}
     if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(cfg, lengths, q, k, v, do)
+        out["cpu_baseline"] = cpu_baseline(cfg, lengths, q, k, v, do, rope=args.rope)
     print(json.dumps(out))
     return 0
 

@@ -321,15 +321,31 @@ __device__ __forceinline__ void store_tile_bf16(char* wave_lds, const f32x16 (&a
 // i + head_dim/2 and turns the pair of a token at position p by p * theta_i (model configuration table of the paper:
 // position encoding RoPE; rotate-half pairing); the transposed map turns it back:
 //   x_lo = y_lo cos + y_hi sin,   x_hi = y_hi cos - y_lo sin.
-// The tile is staged as fp32 whatever the destination type, so that a lane can fetch its 4 columns and their 4
-// partner columns (head_dim/2 is a multiple of 4) from LDS; cos and sin come from the caller's table
+// The tile is staged as fp32 whatever the destination type; a lane then fetches 4 columns of the low half and their
+// 4 partner columns (head_dim/2 is a multiple of 4) from LDS and writes both; cos and sin come from the caller's table
 // [position][head_dim/2] of (cos, sin) pairs, `table_row0` pointing at the position of the tile's first row
 // (the 32 rows are consecutive positions).
 template <int D>
 __device__ __forceinline__ void store_tile_rope_transposed(char* wave_lds, const f32x16 (&acc)[D / 32], float mul, void* base,
                                                            int64_t first_elem, bool f32, int64_t row_stride, int valid_rows,
                                                            int head_dim, const float* table_row0, int lane) {
-    constexpr int kChunks = D / 4;
+    constexpr int kChunks = D / 4;             // 16-byte chunks per staged row
+    constexpr int kPairs = D / 8;              // lanes per row: lane c owns chunk c of the low half and its partner
+    constexpr int kRowsPerInstr = 64 / kPairs;
+    constexpr int kIters = 32 / kRowsPerInstr;
+    const int half_chunks = head_dim / 8;
+    const int c = lane % kPairs, sub_row = lane / kPairs;
+    // all table reads first, so that their latency is paid once and overlaps the staging
+    f32x4 t01[kIters], t23[kIters];
+#pragma unroll
+    for (int it = 0; it < kIters; ++it) {
+        const int row = it * kRowsPerInstr + sub_row;
+        if (row < valid_rows && c < half_chunks) {
+            const float* t = table_row0 + ((int64_t)row * (head_dim / 2) + c * 4) * 2;
+            t01[it] = *reinterpret_cast<const f32x4*>(t);
+            t23[it] = *reinterpret_cast<const f32x4*>(t + 4);
+        }
+    }
     const int r = lane & 31, hh = lane >> 5;
 #pragma unroll
     for (int db = 0; db < D / 32; ++db)
@@ -339,22 +355,20 @@ __device__ __forceinline__ void store_tile_rope_transposed(char* wave_lds, const
             *reinterpret_cast<f32x4*>(wave_lds + (r * kChunks + (chunk ^ (r & (kChunks - 1)))) * 16) =
                 f32x4{acc[db][4 * i4 + 0] * mul, acc[db][4 * i4 + 1] * mul, acc[db][4 * i4 + 2] * mul, acc[db][4 * i4 + 3] * mul};
         }
-    constexpr int kRowsPerInstr = 64 / kChunks;
-    const int half_chunks = head_dim / 8;
 #pragma unroll
-    for (int it = 0; it < 32 / kRowsPerInstr; ++it) {
-        const int row = it * kRowsPerInstr + lane / kChunks, chunk = lane % kChunks;
-        if (row < valid_rows && chunk * 4 < head_dim) {
-            const bool lo = chunk < half_chunks;
-            const int other = lo ? chunk + half_chunks : chunk - half_chunks;
-            const f32x4 v = *reinterpret_cast<const f32x4*>(wave_lds + (row * kChunks + (chunk ^ (row & (kChunks - 1)))) * 16);
-            const f32x4 w = *reinterpret_cast<const f32x4*>(wave_lds + (row * kChunks + (other ^ (row & (kChunks - 1)))) * 16);
-            const float* t = table_row0 + ((int64_t)row * (head_dim / 2) + (lo ? chunk : other) * 4) * 2;
-            const f32x4 t01 = *reinterpret_cast<const f32x4*>(t), t23 = *reinterpret_cast<const f32x4*>(t + 4);
-            const float sgn = lo ? 1.f : -1.f;
-            store_grad4(base, first_elem + row * row_stride + chunk * 4, f32, v[0] * t01[0] + sgn * w[0] * t01[1],
-                        v[1] * t01[2] + sgn * w[1] * t01[3], v[2] * t23[0] + sgn * w[2] * t23[1],
-                        v[3] * t23[2] + sgn * w[3] * t23[3]);
+    for (int it = 0; it < kIters; ++it) {
+        const int row = it * kRowsPerInstr + sub_row;
+        if (row < valid_rows && c < half_chunks) {
+            const int sw = row & (kChunks - 1);
+            const f32x4 lo = *reinterpret_cast<const f32x4*>(wave_lds + (row * kChunks + (c ^ sw)) * 16);
+            const f32x4 hi = *reinterpret_cast<const f32x4*>(wave_lds + (row * kChunks + ((c + half_chunks) ^ sw)) * 16);
+            const float cs[4] = {t01[it][0], t01[it][2], t23[it][0], t23[it][2]};
+            const float sn[4] = {t01[it][1], t01[it][3], t23[it][1], t23[it][3]};
+            const int64_t e = first_elem + row * row_stride + c * 4;
+            store_grad4(base, e, f32, lo[0] * cs[0] + hi[0] * sn[0], lo[1] * cs[1] + hi[1] * sn[1],
+                        lo[2] * cs[2] + hi[2] * sn[2], lo[3] * cs[3] + hi[3] * sn[3]);
+            store_grad4(base, e + head_dim / 2, f32, hi[0] * cs[0] - lo[0] * sn[0], hi[1] * cs[1] - lo[1] * sn[1],
+                        hi[2] * cs[2] - lo[2] * sn[2], hi[3] * cs[3] - lo[3] * sn[3]);
         }
     }
 }

@@ -394,6 +394,7 @@ hspmd_status hspmd_rope_qk(const hspmd_attn_plan* plan, const void* q, const voi
     p.kv_stride = kv_token_stride;
     p.q_out_stride = q_out_token_stride;
     p.kv_out_stride = kv_out_token_stride;
+    p.q_heads = plan->q_heads;
     p.group = plan->q_heads / plan->kv_heads;
     p.head_dim = plan->head_dim;
     p.sin_sign = inverse ? -1.f : 1.f;

@@ -84,7 +84,7 @@ struct RopeParams {
     const float* table;            // (cos, sin) pairs [position][head_dim / 2]
     const hspmd_work_item* items;  // forward list: every (q tile, q head) once
     int64_t q_stride, kv_stride, q_out_stride, kv_out_stride;   // token strides in elements
-    int32_t group, head_dim;
+    int32_t q_heads, group, head_dim;
     float sin_sign;                // +1: rotate, -1: rotate back
 };
 hipError_t launch_rope_table(float* table, int32_t positions, int32_t head_dim, double base, hipStream_t stream);

@@ -56,28 +56,43 @@ __device__ __forceinline__ void rotate_piece(const uint16_t* src, uint16_t* dst,
     *reinterpret_cast<Raw*>(dst + half) = out_hi;
 }
 
-// One workgroup per item of the forward list: the item's 128 rows of one q head, and of the KV head as well when
-// the q head is the first of its group.  In place (q_out == q) is fine: a thread reads what it writes.
+// e / n and e % n for 0 <= e < 2^22 and 0 < n through a float reciprocal (the +0.5 keeps the quotient at least
+// 0.5 / n away from an integer, far more than the rounding error of the product)
+__device__ __forceinline__ void divmod(int e, int n, float inv_n, int& quot, int& rem) {
+    quot = (int)(((float)e + 0.5f) * inv_n);
+    rem = e - quot * n;
+}
+
+// One workgroup per item of the forward list.  The items (tile, head) of one tile exist once per q head, so the
+// workgroup of head h takes the h-th share of the tile's rows and rotates ALL heads of those rows: a row of q is
+// q_heads * head_dim contiguous elements, and consecutive lanes walk along it (16 bytes of the low half of a head
+// and 16 bytes of its high half per lane).  In place (q_out == q) is fine: a thread reads what it writes.
 template <int VEC>
 __global__ __launch_bounds__(kRopeThreads) void rope_qk_kernel(RopeParams p) {
     const hspmd_work_item item = p.items[blockIdx.x];
     if (item.tile < 0) return;   // padding slot
     const int hd = p.head_dim, half = hd / 2;
-    const int pieces = half / VEC;   // per row
+    const int pieces = half / VEC;   // per head
     const int row0 = item.tile * kFwdQTile;
     const int rows = min(kFwdQTile, item.seq_len - row0);
-    const bool with_k = item.head % p.group == 0;
-    const int kv_head = item.head / p.group;
-    for (int e = threadIdx.x; e < rows * pieces; e += kRopeThreads) {
-        const int r = e / pieces, c = (e % pieces) * VEC;
-        const int64_t token = (int64_t)item.token_start + row0 + r;
-        const float* cs = p.table + ((int64_t)(row0 + r) * half + c) * 2;
-        rotate_piece<VEC>(p.q + token * p.q_stride + (int64_t)item.head * hd + c,
-                          p.q_out + token * p.q_out_stride + (int64_t)item.head * hd + c, half, cs, p.sin_sign);
-        if (with_k)
-            rotate_piece<VEC>(p.k + token * p.kv_stride + (int64_t)kv_head * hd + c,
-                              p.k_out + token * p.kv_out_stride + (int64_t)kv_head * hd + c, half, cs, p.sin_sign);
-    }
+    const int r_begin = rows * item.head / p.q_heads, r_end = rows * (item.head + 1) / p.q_heads;
+    const int64_t token0 = (int64_t)item.token_start + row0;
+    const float inv_pieces = 1.f / (float)pieces;
+    auto rotate_rows = [&](const uint16_t* src, uint16_t* dst, int64_t stride, int64_t out_stride, int heads) {
+        const int per_row = heads * pieces;
+        const float inv_per_row = 1.f / (float)per_row;
+        for (int e = threadIdx.x; e < (r_end - r_begin) * per_row; e += kRopeThreads) {
+            int r, x, head, piece;
+            divmod(e, per_row, inv_per_row, r, x);
+            divmod(x, pieces, inv_pieces, head, piece);
+            r += r_begin;
+            const int c = piece * VEC;
+            rotate_piece<VEC>(src + (token0 + r) * stride + head * hd + c, dst + (token0 + r) * out_stride + head * hd + c,
+                              half, p.table + ((int64_t)(row0 + r) * half + c) * 2, p.sin_sign);
+        }
+    };
+    rotate_rows(p.q, p.q_out, p.q_stride, p.q_out_stride, p.q_heads);
+    rotate_rows(p.k, p.k_out, p.kv_stride, p.kv_out_stride, p.q_heads / p.group);
 }
 
 }  // namespace
