@@ -34,7 +34,8 @@
  *     are marked "host".
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
  *     Forward and backward only enqueue work; they never synchronise and never
- *     allocate.  Plan creation allocates the plan's small index arrays and
+ *     allocate, so they may be recorded into a HIP graph (with per-kernel timing
+ *     off, see hspmd_profile_enable).  Plan creation allocates the plan's small index arrays and
  *     copies them to the device before returning.
  *   - Every call returns an hspmd_status; no exception crosses this boundary
  *     and nothing aborts.  Arguments are validated on the host before any
