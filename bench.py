@@ -347,6 +347,8 @@ def main() -> int:
     # measured matrix-core rate of this device (register-only MFMA loop): a second denominator beside the nominal peak
     probe = torch.empty(A.probe_scratch_bytes(), dtype=torch.uint8, device=dev)
     mfma_measured = A.probe_mfma_tflops(probe, stream=stream)
+    # the same loop on operands that vary like real data: the chip is power-limited, its clock depends on the toggling
+    mfma_measured_varied = A.probe_mfma_tflops(probe, stream=stream, varied_operands=True)
     del probe
 
     ms_per_step = elapsed / args.steps * 1e3
@@ -387,6 +389,9 @@ def main() -> int:
                      "flops_per_launch": GEMMS[dominant] * pair_flops,
                      "measured_mfma_peak": round(mfma_measured, 1),
                      "frac_of_measured_peak": round(achieved / mfma_measured, 4) if mfma_measured > 0 else None,
+                     "measured_mfma_peak_varied_operands": round(mfma_measured_varied, 1),
+                     "frac_of_measured_peak_varied_operands":
+                         round(achieved / mfma_measured_varied, 4) if mfma_measured_varied > 0 else None,
                      "note": f"{GEMMS[dominant]} GEMMs over the visible pairs; avg of {prof[dominant][1]} launches "
                              "timed with HIP events on the launch stream"},
     }

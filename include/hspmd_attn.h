@@ -364,6 +364,12 @@ const char* hspmd_kernel_name(int32_t kernel);   /* symbol-like name, NULL if ou
 size_t       hspmd_probe_scratch_bytes(void);
 hspmd_status hspmd_probe_mfma_tflops(int64_t mfma_per_wave, void* scratch_out, size_t scratch_bytes,
                                      void* stream, double* tflops);
+/* The same with operands that vary: four pairs of pseudo-random bf16 values in +-[0.5, 2), different in every
+ * lane, used in turn.  The chip limits its power, and the clock it sustains under matrix work depends on how
+ * many bits toggle: this is the rate the matrix cores deliver on data like the attention kernels' (they too
+ * run about a quarter faster on all-zero inputs than on random ones). */
+hspmd_status hspmd_probe_mfma_tflops_varied(int64_t mfma_per_wave, void* scratch_out, size_t scratch_bytes,
+                                     void* stream, double* tflops);
 
 #ifdef __cplusplus
 }

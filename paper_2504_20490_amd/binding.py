@@ -124,6 +124,8 @@ def load_library():
     lib.hspmd_probe_mfma_tflops.restype = ctypes.c_int
     lib.hspmd_probe_mfma_tflops.argtypes = [ctypes.c_int64, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p,
                                             ctypes.POINTER(ctypes.c_double)]
+    lib.hspmd_probe_mfma_tflops_varied.restype = ctypes.c_int
+    lib.hspmd_probe_mfma_tflops_varied.argtypes = lib.hspmd_probe_mfma_tflops.argtypes
     lib.hspmd_profile_read.restype = ctypes.c_int
     lib.hspmd_profile_read.argtypes = [ctypes.POINTER(ctypes.c_double), i64p]
     lib.hspmd_kernel_name.restype = ctypes.c_char_p
@@ -309,13 +311,15 @@ def probe_scratch_bytes() -> int:
     return int(load_library().hspmd_probe_scratch_bytes())
 
 
-def probe_mfma_tflops(scratch, mfma_per_wave: int = 1 << 18, stream=None) -> float:
+def probe_mfma_tflops(scratch, mfma_per_wave: int = 1 << 18, stream=None, varied_operands: bool = False) -> float:
     """Measured dense bf16 MFMA rate (TFLOP/s) of the current device; scratch is a device tensor of at least
-    probe_scratch_bytes() bytes.  Synchronises the stream."""
+    probe_scratch_bytes() bytes.  varied_operands: pseudo-random operand values instead of constants (the clock
+    the chip sustains depends on the switching activity).  Synchronises the stream."""
     out = ctypes.c_double(0.0)
-    _check(load_library().hspmd_probe_mfma_tflops(int(mfma_per_wave), _dev_ptr(scratch),
-                                                  scratch.numel() * scratch.element_size(), _stream_handle(stream),
-                                                  ctypes.byref(out)))
+    lib = load_library()
+    fn = lib.hspmd_probe_mfma_tflops_varied if varied_operands else lib.hspmd_probe_mfma_tflops
+    _check(fn(int(mfma_per_wave), _dev_ptr(scratch), scratch.numel() * scratch.element_size(), _stream_handle(stream),
+              ctypes.byref(out)))
     return float(out.value)
 
 

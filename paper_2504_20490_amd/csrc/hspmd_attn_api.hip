@@ -664,8 +664,8 @@ hspmd_status hspmd_profile_read(double* ms, int64_t* launches) {
 
 size_t hspmd_probe_scratch_bytes(void) { return (size_t)hspmd::kProbeMaxGrid * hspmd::kProbeThreads * sizeof(float); }
 
-hspmd_status hspmd_probe_mfma_tflops(int64_t mfma_per_wave, void* scratch_out, size_t scratch_bytes, void* stream,
-                                     double* tflops) {
+static hspmd_status probe_mfma(int64_t mfma_per_wave, bool varied_operands, void* scratch_out, size_t scratch_bytes,
+                               void* stream, double* tflops) {
     if (!scratch_out || !tflops) return fail(HSPMD_ERR_INVALID_ARG, "null pointer");
     if (mfma_per_wave <= 0) return fail(HSPMD_ERR_INVALID_ARG, "mfma_per_wave must be positive");
     if (scratch_bytes < hspmd_probe_scratch_bytes()) return fail(HSPMD_ERR_WORKSPACE_TOO_SMALL, "probe scratch too small");
@@ -680,9 +680,9 @@ hspmd_status hspmd_probe_mfma_tflops(int64_t mfma_per_wave, void* scratch_out, s
     hipEvent_t start = nullptr, stop = nullptr;
     e = hipEventCreate(&start);
     if (e == hipSuccess) e = hipEventCreate(&stop);
-    if (e == hipSuccess) e = hspmd::launch_mfma_probe((float*)scratch_out, rounds, grid, s);   // untimed
+    if (e == hipSuccess) e = hspmd::launch_mfma_probe((float*)scratch_out, rounds, grid, varied_operands, s);   // untimed
     if (e == hipSuccess) e = hipEventRecord(start, s);
-    if (e == hipSuccess) e = hspmd::launch_mfma_probe((float*)scratch_out, rounds, grid, s);
+    if (e == hipSuccess) e = hspmd::launch_mfma_probe((float*)scratch_out, rounds, grid, varied_operands, s);
     if (e == hipSuccess) e = hipEventRecord(stop, s);
     if (e == hipSuccess) e = hipEventSynchronize(stop);
     float ms = 0.f;
@@ -694,6 +694,16 @@ hspmd_status hspmd_probe_mfma_tflops(int64_t mfma_per_wave, void* scratch_out, s
     const double flops = (double)grid * 4.0 * (double)(rounds * 16) * 32768.0;
     *tflops = ms > 0.f ? flops / ((double)ms * 1e-3) / 1e12 : 0.0;
     return HSPMD_OK;
+}
+
+hspmd_status hspmd_probe_mfma_tflops(int64_t mfma_per_wave, void* scratch_out, size_t scratch_bytes, void* stream,
+                                     double* tflops) {
+    return probe_mfma(mfma_per_wave, false, scratch_out, scratch_bytes, stream, tflops);
+}
+
+hspmd_status hspmd_probe_mfma_tflops_varied(int64_t mfma_per_wave, void* scratch_out, size_t scratch_bytes, void* stream,
+                                            double* tflops) {
+    return probe_mfma(mfma_per_wave, true, scratch_out, scratch_bytes, stream, tflops);
 }
 
 const char* hspmd_kernel_name(int32_t kernel) {

@@ -95,6 +95,6 @@ hipError_t launch_rope_qk(const RopeParams& p, int64_t num_items, hipStream_t st
 constexpr int kProbeMaxGrid = 4096;
 constexpr int kProbeThreads = 256;
 int probe_grid(int compute_units);
-hipError_t launch_mfma_probe(float* out, int64_t rounds, int grid, hipStream_t stream);
+hipError_t launch_mfma_probe(float* out, int64_t rounds, int grid, bool varied_operands, hipStream_t stream);
 
 }  // namespace hspmd

@@ -210,6 +210,10 @@ def test_mfma_rate_probe_is_plausible():
     scratch = torch.empty(A.probe_scratch_bytes(), dtype=torch.uint8, device="cuda")
     rate = A.probe_mfma_tflops(scratch, mfma_per_wave=1 << 16)
     assert 800.0 < rate < 2700.0, rate
+    # operands that vary like real data: the power-limited clock is lower, never higher
+    varied = A.probe_mfma_tflops(scratch, mfma_per_wave=1 << 16, varied_operands=True)
+    assert 600.0 < varied < 1.05 * rate, (varied, rate)
+    assert torch.isfinite(scratch.view(torch.float32)).all()      # the checksums of the varied run
     with pytest.raises(A.HspmdError):
         A.probe_mfma_tflops(scratch[:16])
     with pytest.raises(A.HspmdError):
