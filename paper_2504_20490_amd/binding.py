@@ -299,12 +299,12 @@ def profile_enable(on: bool) -> None:
 
 
 def profile_read():
-    """Returns {kernel name: (total ms, launches)} for the launches recorded since the last read."""
+    """Returns {kernel name: (total ms, launches)} for the kernels launched since the last read."""
     lib = load_library()
     ms = (ctypes.c_double * NUM_KERNELS)()
     n = (ctypes.c_int64 * NUM_KERNELS)()
     _check(lib.hspmd_profile_read(ms, n))
-    return {lib.hspmd_kernel_name(i).decode(): (float(ms[i]), int(n[i])) for i in range(NUM_KERNELS)}
+    return {lib.hspmd_kernel_name(i).decode(): (float(ms[i]), int(n[i])) for i in range(NUM_KERNELS) if n[i] > 0}
 
 
 def probe_scratch_bytes() -> int:
