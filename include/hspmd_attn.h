@@ -193,9 +193,9 @@ hspmd_status hspmd_attn_varlen_fwd(const hspmd_attn_plan* plan, const void* q, c
                                    void* o, float* lse, void* stream);
 
 /*
- * Backward (AttentionBwd): three launches on `stream` -- D = rowsum(dO * O); the dQ
- * pass; the dK/dV pass.  Both passes recompute P from the stored lse.  No atomics:
- * results are run-to-run bit-identical.
+ * Backward (AttentionBwd): two launches on `stream` -- the dQ pass, which also computes the
+ * row statistic D = rowsum(dO * O) of its rows and leaves it in the workspace; the dK/dV pass.
+ * Both passes recompute P from the stored lse.  No atomics: results are run-to-run bit-identical.
  *   o, d_o  bf16 [T, local_q_heads, head_dim], contiguous
  *   lse     fp32 [local_q_heads, T] as written by the forward
  *   dq      [T, local_q_heads, head_dim]; dk, dv [T, local_kv_heads, head_dim]; contiguous,
@@ -254,8 +254,8 @@ hspmd_status hspmd_attn_varlen_bwd_rope(const hspmd_attn_plan* plan, const void*
  * mixed-length case).  Host only, no GPU needed; costs about as much as building the work lists.
  * Model: each pass walks its work list; an item weighs (inner steps x a step time + a fixed time per
  * item), a pass takes a launch time plus the weight of its heaviest XCD queue divided by the
- * workgroups resident per XCD, and not less than its heaviest item; backward = D pass (an HBM
- * stream) + dQ pass + dK/dV pass.  The coefficients are fitted to measured kernel times
+ * workgroups resident per XCD, and not less than its heaviest item; backward = dQ pass + dK/dV
+ * pass.  The coefficients are fitted to measured kernel times
  * (paper_2504_20490_amd/fit_cost_model.py refits them): mean error 5-8 % at head_dim 128, up to
  * 25-35 % on packs that take only a few hundred microseconds.  Host-side plan creation is not included.
  */
@@ -340,7 +340,8 @@ hspmd_status hspmd_attn_block_bwd(const hspmd_attn_plan* plan, const void* q, co
  * calling process is bracketed by a pair of HIP events recorded on the launch stream.
  * hspmd_profile_read waits for the recorded events, adds each kernel's elapsed time and launch
  * count to the caller's arrays and forgets the records.
- *   kernel index: 0 forward, 1 backward D = rowsum(dO*O), 2 backward dQ pass, 3 backward dK/dV pass,
+ *   kernel index: 0 forward, 1 backward D = rowsum(dO*O) (block variant only: the packed dQ pass computes D
+ *                 itself), 2 backward dQ pass, 3 backward dK/dV pass,
  *                 4 rotary embedding of q and k
  *   ms, launches  host, [HSPMD_NUM_KERNELS] each, accumulated into (the caller zeroes them)
  * Not thread-safe: enable, launch and read from one thread.  Events are created on first use and

@@ -56,6 +56,8 @@ __global__ __launch_bounds__(kThreads, 2) void bwd_dq_kernel(BwdParams p) {
     constexpr int kTileBytes = BK * D * 2;
     __shared__ __attribute__((aligned(1024))) char lds[2 * 2 * kTileBytes];   // {K, V} x 2 stages
 
+    // packed variant: this pass also produces the row statistics (see below); the constants that go with them
+    if (!BLOCK && blockIdx.x == 0 && threadIdx.x < 16) p.ninf_pad[threadIdx.x] = -INFINITY;
     const ItemGeom item = load_item<BLOCK>(p.items, p.block_items, blockIdx.x);
     if (item.tile < 0) return;
     const int tid = threadIdx.x, lane = tid & 63;
@@ -98,23 +100,46 @@ __global__ __launch_bounds__(kThreads, 2) void bwd_dq_kernel(BwdParams p) {
     kvcopy.issue(lds0, kbase, p.kv_stride, 0, L, wave, lane);
     kvcopy.issue(lds0 + kTileBytes, vbase, p.kv_stride, 0, L, wave, lane);
 
+    // Q and dO rows of this lane.  The packed variant owns every (row, head) exactly once in this pass, so it
+    // also computes the row statistic D = <dO, O> here (no separate pass over O and dO) and leaves -D and
+    // -LSE / scale in the workspace for the dK/dV pass that follows on the stream; the block variant reads
+    // what bwd_dsum_kernel wrote (the statistics of the merged rows are shared by all blocks of a row).
     bf16x8 qf[KK], dof[KK];
+    float d_part = 0.f;
 #pragma unroll
     for (int kk = 0; kk < KK; ++kk) {
         union { u32x4 u; bf16x8 v; } a, b;
         a.u = u32x4{0u, 0u, 0u, 0u};
         b.u = u32x4{0u, 0u, 0u, 0u};
         if (valid && kk * 16 + hh * 8 < hd) {
+            const int64_t row_elem = (int64_t)my_row * p.q_heads * hd + kk * 16 + hh * 8;
             a.u = *reinterpret_cast<const u32x4*>(qbase + (int64_t)my_row * p.q_stride + kk * 16 + hh * 8);
-            b.u = *reinterpret_cast<const u32x4*>(dobase + (int64_t)my_row * p.q_heads * hd + kk * 16 + hh * 8);
+            b.u = *reinterpret_cast<const u32x4*>(dobase + row_elem);
+            if constexpr (!BLOCK) {
+                union { u32x4 u; bf16x8 v; } o;
+                o.u = *reinterpret_cast<const u32x4*>(p.o + ((int64_t)item.q_start * p.q_heads + h) * hd + row_elem);
+#pragma unroll
+                for (int i = 0; i < 8; ++i) d_part += (float)b.v[i] * (float)o.v[i];
+            }
         }
         qf[kk] = a.v;
         dof[kk] = b.v;
     }
     const int64_t stat = (int64_t)h * p.total_tokens + item.q_start + my_row;
     const float c = p.scale_log2;
-    const float nlse2 = valid ? p.nlse[stat] * c : -INFINITY;   // -LSE log2(e); rows past the end get P = 0
-    const float negd = valid ? p.negd[stat] : 0.f;
+    float nlse2, negd;
+    if constexpr (BLOCK) {
+        nlse2 = valid ? p.nlse[stat] * c : -INFINITY;   // -LSE log2(e); rows past the end get P = 0
+        negd = valid ? p.negd[stat] : 0.f;
+    } else {
+        negd = -(d_part + partner32(d_part));            // the two half rows of lanes l and l + 32
+        const float nlse = valid ? -p.lse[stat] / p.scale : -INFINITY;   // rows past the end get P = 0
+        nlse2 = nlse * c;                                                // -LSE log2(e)
+        if (valid && hh == 0) {
+            p.negd[stat] = negd;
+            p.nlse[stat] = nlse;
+        }
+    }
 
     f32x16 acc[DB];
 #pragma unroll

@@ -322,10 +322,9 @@ static hspmd_status varlen_bwd(const hspmd_attn_plan* plan, const void* q, const
     p.scale = scale;
     p.scale_log2 = scale * 1.4426950408889634f;
     hipStream_t s = static_cast<hipStream_t>(stream);
-    hipError_t e = timed_launch(1, s, [&] { return hspmd::launch_bwd_dsum(p, plan->head_dim, s); });
-    if (e != hipSuccess) return fail_hip(e, "backward D launch");
+    // D = rowsum(dO * O) is computed by the dQ pass itself (every (row, head) belongs to exactly one of its items)
     p.items = plan->items[HSPMD_LIST_DQ];
-    e = timed_launch(2, s, [&] { return hspmd::launch_bwd_dq(p, plan->head_dim, plan->count[HSPMD_LIST_DQ], false, s); });
+    hipError_t e = timed_launch(2, s, [&] { return hspmd::launch_bwd_dq(p, plan->head_dim, plan->count[HSPMD_LIST_DQ], false, s); });
     if (e != hipSuccess) return fail_hip(e, "backward dQ launch");
     p.items = plan->items[HSPMD_LIST_DKV];
     e = timed_launch(3, s, [&] { return hspmd::launch_bwd_dkv(p, plan->head_dim, plan->count[HSPMD_LIST_DKV], false, s); });
@@ -423,8 +422,7 @@ hspmd_status hspmd_attn_estimate_ms(const int32_t* cu_seqlens, int32_t num_seqs,
     try {
         head_dim = hspmd::tile_width(head_dim);   // a narrower head runs on the next tile width up
         *fwd_ms = hspmd::estimate_pass_us(HSPMD_LIST_FWD, cu_seqlens, num_seqs, local_q_heads, local_kv_heads, head_dim) * 1e-3;
-        *bwd_ms = (hspmd::estimate_dsum_us(cu_seqlens[num_seqs], local_q_heads, head_dim) +
-                   hspmd::estimate_pass_us(HSPMD_LIST_DQ, cu_seqlens, num_seqs, local_q_heads, local_kv_heads, head_dim) +
+        *bwd_ms = (hspmd::estimate_pass_us(HSPMD_LIST_DQ, cu_seqlens, num_seqs, local_q_heads, local_kv_heads, head_dim) +
                    hspmd::estimate_pass_us(HSPMD_LIST_DKV, cu_seqlens, num_seqs, local_q_heads, local_kv_heads, head_dim)) * 1e-3;
     } catch (const std::bad_alloc&) {
         return fail(HSPMD_ERR_INVALID_ARG, "out of host memory while building the work lists");

@@ -205,12 +205,6 @@ double estimate_pass_us(hspmd_list_kind kind, const int32_t* cu, int32_t num_seq
     return c.launch_us + std::max(worst / slots, heaviest);
 }
 
-double estimate_dsum_us(int64_t total_tokens, int32_t hq, int32_t head_dim) {
-    if (total_tokens <= 0) return 0.0;
-    const double bytes = 2.0 * (double)total_tokens * hq * head_dim * 2.0;   // O and dO, bf16
-    return 5.0 + bytes / 5.0e6;                                              // ~5 TB/s sustained for this stream
-}
-
 // ------------------------------------------------------------------------------ block variant
 std::string check_block_pack(const int32_t* cu_q, const int32_t* cu_k, const int32_t* q_pos, const int32_t* k_pos,
                              int32_t num_seqs, int32_t hq, int32_t hkv) {

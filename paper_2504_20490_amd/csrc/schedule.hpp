@@ -35,8 +35,6 @@ struct PassCost {
 // coefficients fitted to measurements on MI355X (fit_cost_model.py refits them); head_dim = the tile width, 64 or 128
 PassCost pass_cost_coefficients(hspmd_list_kind kind, int32_t head_dim);
 double estimate_pass_us(hspmd_list_kind kind, const int32_t* cu, int32_t num_seqs, int32_t hq, int32_t hkv, int32_t head_dim);
-// the D pass of the backward (an HBM stream over O and dO)
-double estimate_dsum_us(int64_t total_tokens, int32_t hq, int32_t head_dim);
 
 // ---- block variant (one step of context-parallel attention): per sequence a query chunk and a key chunk
 // with positions inside the sequence; key j is visible to row r iff j <= r + (q_pos - k_pos).

@@ -184,7 +184,8 @@ def gpu_util_cu(lengths):
 
 def test_block_equals_packed_kernels_when_there_is_no_shift():
     """Query chunk = key chunk = whole sequence: the block path must reproduce the packed path (O after rounding,
-    LSE and gradients to the parity tolerance, since the two instantiations differ only in index arithmetic)."""
+    LSE and dV bit for bit, dQ and dK up to the rounding of the row statistic D: the two instantiations differ only
+    in index arithmetic and in where D is computed)."""
     import torch
     import paper_2504_20490_amd as A
     lengths = [200, 0, 513, 64]
@@ -208,7 +209,11 @@ def test_block_equals_packed_kernels_when_there_is_no_shift():
     A.attn_varlen_bwd(plan, q, k, v, o, lse, do, dq, dk, dv, ws, grad_dtype=A.GRAD_F32)
     A.attn_block_bwd(bplan, q, k, v, o, lse, do, dq2, dk2, dv2, ws)
     torch.cuda.synchronize()
-    assert torch.equal(dq2, dq) and torch.equal(dk2, dk) and torch.equal(dv2, dv)
+    # dV does not depend on the row statistic D; dQ and dK do, and the two paths add D up in different orders
+    # (the packed dQ pass computes it per lane, the block path in a kernel of its own): fp32 rounding apart
+    assert torch.equal(dv2, dv)
+    for a, b in ((dq2, dq), (dk2, dk)):
+        assert float((a - b).abs().max()) <= 1e-5 * float(b.abs().max())
 
 
 def test_block_validation():
