@@ -433,35 +433,24 @@ __global__ __launch_bounds__(kThreads, 1) void bwd_dkv_kernel(BwdParams p) {
 
     // whole rows per store instruction, staged through LDS (free once every wave has left the tile loop)
     const bool rope = !BLOCK && p.rope_table != nullptr;
-    if (p.grad_f32 != 0 || rope) __syncthreads();
+    __syncthreads();
     char* wave_lds = lds + wave * (32 * D * 4);
     const int64_t row0_elem = ((int64_t)(item.k_start + wave_key0) * p.kv_heads + g) * hd;
+    const int64_t row_stride = (int64_t)p.kv_heads * hd;
     const int rows = min(32, Lk - wave_key0);
     if (rope) {
         // dK with respect to the keys before their rotary embedding; key positions = index in the sequence
-        store_tile_rope_transposed<D>(wave_lds, st.dk, p.scale, p.dk, row0_elem, p.grad_f32 != 0, (int64_t)p.kv_heads * hd, rows,
-                                      hd, p.rope_table + (int64_t)wave_key0 * hd, lane);
+        store_tile_rope_transposed<D>(wave_lds, st.dk, p.scale, p.dk, row0_elem, p.grad_f32 != 0, row_stride, rows, hd,
+                                      p.rope_table + (int64_t)wave_key0 * hd, lane);
     } else if (p.grad_f32 != 0) {
-        store_tile_f32<D, false>(wave_lds, st.dk, p.scale, static_cast<float*>(p.dk) + row0_elem, (int64_t)p.kv_heads * hd,
-                                 rows, hd, lane);
+        store_tile_f32<D, false>(wave_lds, st.dk, p.scale, static_cast<float*>(p.dk) + row0_elem, row_stride, rows, hd, lane);
+    } else {
+        store_tile_bf16<D>(wave_lds, st.dk, p.scale, static_cast<uint16_t*>(p.dk) + row0_elem, row_stride, rows, hd, lane);
     }
     if (p.grad_f32 != 0) {
-        store_tile_f32<D, false>(wave_lds, st.dv, 1.f, static_cast<float*>(p.dv) + row0_elem, (int64_t)p.kv_heads * hd,
-                                 rows, hd, lane);
-    } else if (valid) {
-        const int64_t row_elem = ((int64_t)(item.k_start + my_key) * p.kv_heads + g) * hd;
-#pragma unroll
-        for (int db = 0; db < DB; ++db)
-#pragma unroll
-            for (int i4 = 0; i4 < 4; ++i4) {
-                if (db * 32 + i4 * 8 + hh * 4 >= hd) continue;
-                const int64_t e = row_elem + db * 32 + i4 * 8 + hh * 4;
-                if (!rope)
-                    store_grad4(p.dk, e, false, st.dk[db][4 * i4 + 0] * p.scale, st.dk[db][4 * i4 + 1] * p.scale,
-                                st.dk[db][4 * i4 + 2] * p.scale, st.dk[db][4 * i4 + 3] * p.scale);
-                store_grad4(p.dv, e, false, st.dv[db][4 * i4 + 0], st.dv[db][4 * i4 + 1], st.dv[db][4 * i4 + 2],
-                            st.dv[db][4 * i4 + 3]);
-            }
+        store_tile_f32<D, false>(wave_lds, st.dv, 1.f, static_cast<float*>(p.dv) + row0_elem, row_stride, rows, hd, lane);
+    } else {
+        store_tile_bf16<D>(wave_lds, st.dv, 1.f, static_cast<uint16_t*>(p.dv) + row0_elem, row_stride, rows, hd, lane);
     }
 }
 

@@ -285,16 +285,11 @@ __global__ __launch_bounds__(kThreads, 2) void bwd_dq_kernel(BwdParams p) {
             store_tile_f32<D, true>(wave_lds, acc, p.scale, first_row, (int64_t)p.q_heads * hd, rows, hd, lane);
         else
             store_tile_f32<D, false>(wave_lds, acc, p.scale, first_row, (int64_t)p.q_heads * hd, rows, hd, lane);
-    } else if (valid) {
-        const int64_t row_elem = ((int64_t)(item.q_start + my_row) * p.q_heads + h) * hd;
-#pragma unroll
-        for (int db = 0; db < DB; ++db)
-#pragma unroll
-            for (int i4 = 0; i4 < 4; ++i4)
-                if (db * 32 + i4 * 8 + hh * 4 < hd)
-                    store_grad4(p.dq, row_elem + db * 32 + i4 * 8 + hh * 4, false,
-                                acc[db][4 * i4 + 0] * p.scale, acc[db][4 * i4 + 1] * p.scale,
-                                acc[db][4 * i4 + 2] * p.scale, acc[db][4 * i4 + 3] * p.scale);
+    } else {
+        __syncthreads();
+        store_tile_bf16<D>(lds + wave * (32 * D * 2), acc, p.scale,
+                           static_cast<uint16_t*>(p.dq) + ((int64_t)(item.q_start + wave_row0) * p.q_heads + h) * hd,
+                           (int64_t)p.q_heads * hd, min(32, Lq - wave_row0), hd, lane);
     }
 }
 
