@@ -232,12 +232,14 @@ __global__ __launch_bounds__(kThreads, 2) void fwd_kernel(FwdParams p) {
     // key j is visible to row r iff j <= r + off: the tile's last row sees keys 0 .. kv_end-1
     const int kv_end = max(0, min(L, min(Lq, q_row0 + BQ) + off));
     const int n_tiles = (kv_end + BK - 1) / BK;
-    // tiles whose every key exists and is visible to every row of this q tile: (kt + 1) BK - 1 <= q_row0 + off
-    // (without the shift, keys past the end of the sequence lie above every row's diagonal; with it they need the
-    // mask, so the chunk's last, partial tile is never an interior one)
-    const int n_interior = BLOCK ? max(0, min(min(n_tiles, (q_row0 + off + 1) / BK), L / BK)) : min(n_tiles, 2 * item.tile);
     // last key this lane's row may see, as an index into the chunk
     const int my_limit = BLOCK ? min(my_row + off, L - 1) : my_row;
+    // this wave's own share: the tiles that hold a key visible to one of its 32 rows, and those among them that
+    // are visible to all of them (a wave whose rows lie past the end of the chunk computes nothing).  On the
+    // diagonal the upper waves of a workgroup see fewer tiles than the lower ones.
+    const int kv_end_w = wave_row0 < Lq ? max(0, min(L, min(Lq, wave_row0 + 32) + off)) : 0;
+    const int n_tiles_w = (kv_end_w + BK - 1) / BK;
+    const int n_interior_w = max(0, min(min(n_tiles_w, (wave_row0 + off + 1) / BK), L / BK));
     if (BLOCK && n_tiles == 0) {
         // no key of the chunk is visible to any row of the tile: O = 0, LSE = -inf
         if (my_row < Lq) {
@@ -290,6 +292,7 @@ __global__ __launch_bounds__(kThreads, 2) void fwd_kernel(FwdParams p) {
     wait_tile_loads();
     __syncthreads();
     // S^T(0), not pipelined
+    if (n_tiles_w > 0)
 #pragma unroll
     for (int jb = 0; jb < 2; ++jb) {
 #pragma unroll
@@ -329,16 +332,30 @@ __global__ __launch_bounds__(kThreads, 2) void fwd_kernel(FwdParams p) {
         fwd_iteration<D, false, false, true, BLOCK>(st, kbuf0 + ((kt + 1) & 1) * kTileBytes, vbuf0 + (kt & 1) * kTileBytes, c,
                                                     my_limit - kt * BK - 4 * hh, load);
     };
+    // a tile past this wave's own diagonal: the barrier and the wave's share of the copies, nothing else
+    auto idle = [&](int kt) {
+        if (kt > 0) {
+            wait_tile_loads();
+            __syncthreads();
+        }
+        if (kt + 2 < n_tiles) kvcopy.issue(kdst0 + (kt & 1) * kTileBytes, kbase, p.kv_stride, (kt + 2) * BK, L, wave, lane);
+        if (kt + 1 < n_tiles) kvcopy.issue(vdst0 + ((kt + 1) & 1) * kTileBytes, vbase, p.kv_stride, (kt + 1) * BK, L, wave, lane);
+    };
     // separate loops instead of branches inside one: unmasked tiles (with and without whole successors), masked
-    // tiles, and the final tile (which has no successor to compute scores for); the large register state then
-    // meets at a join once per loop, not per tile
-    const int n_plain = min(n_interior, n_tiles - 1);
+    // tiles, and the wave's final tile (which has no successor to compute scores for); the large register state
+    // then meets at a join once per loop, not per tile.  Every wave passes the barrier of every tile of the
+    // workgroup, in whichever loop it happens to be.
+    const int n_plain = min(n_interior_w, n_tiles_w - 1);
     const int n_spread = max(0, min(n_plain, L / BK - 2));   // tile kt+2 exists and is whole
     int kt = 0;
     for (; kt < n_spread; ++kt) step_spread(kt);
     for (; kt < n_plain; ++kt) step(kt, std::false_type{}, std::false_type{});
-    for (; kt < n_tiles - 1; ++kt) step(kt, std::true_type{}, std::false_type{});
-    step(kt, std::true_type{}, std::true_type{});   // the final tile touches the diagonal (always, when !BLOCK)
+    for (; kt < n_tiles_w - 1; ++kt) step(kt, std::true_type{}, std::false_type{});
+    if (n_tiles_w > 0) {
+        step(kt, std::true_type{}, std::true_type{});   // the wave's final tile touches its diagonal (always, when !BLOCK)
+        ++kt;
+    }
+    for (; kt < n_tiles; ++kt) idle(kt);
 
     const float l_row = st.l + partner32(st.l);
     // O leaves through LDS (free once every wave has left the tile loop) so that every store instruction writes
