@@ -153,6 +153,36 @@ def test_strided_views_into_a_fused_qkv_buffer():
         assert torch.equal(getattr(a, name), getattr(b, name)), name
 
 
+def test_many_tiny_sequences():
+    """3000 sequences of 1 .. 12 tokens: one work item per (sequence, head), most of every tile empty."""
+    rng = np.random.default_rng(8)
+    lengths = [int(x) for x in rng.integers(1, 13, size=3000)]
+    _full_check(lengths, 4, 2, 64, seed=61, magnitude_slack=True)   # 3000 x 8 heads of outliers: the bound follows max|ref|
+
+
+def test_one_very_long_sequence_on_sampled_rows_and_keys():
+    """A single 50000-token sequence, one head: 782 key tiles in the longest forward item, 782 q tiles in the
+    longest dK/dV item; rows and keys at the ends, at tile edges and in the middle against the oracle."""
+    L, d = 50000, 64
+    lengths = [L]
+    q, k, v, do = make_case(lengths, 1, 1, d, seed=62)
+    gpu_util.CONTEXT["case"] = "long50k"
+    run = GpuRun(lengths, q, k, v, do).run()
+    s = default_scale(d)
+    rows = np.array([0, 1, 63, 64, 127, 128, 24999, 25000, 32767, 32768, L - 2, L - 1], dtype=np.int32)
+    heads = np.zeros(len(rows), dtype=np.int32)
+    ro, rlse, rdq = oracle.attn_rows(f64(q), f64(k), f64(v), f64(do), lengths, s, rows, heads)
+    assert_close("O rows", run.host("o")[rows, heads], ro)
+    assert np.max(np.abs(run.host("lse")[heads, rows] - rlse)) <= LSE_ABS
+    assert_close("dQ rows", run.host("dq")[rows, heads], rdq)
+    rdk, rdv = oracle.attn_keys(f64(q), f64(k), f64(v), f64(do), lengths, s, rows, heads)
+    # the first keys collect a contribution from every one of the 50000 rows: the bound scales with the magnitude
+    for name, got, ref in (("dK keys", run.host("dk")[rows, heads], rdk), ("dV keys", run.host("dv")[rows, heads], rdv)):
+        assert_close(name, got, ref, max_abs=2e-2 + 2.0 ** -9 * float(np.max(np.abs(ref))))
+    for name in ("o", "dq", "dk", "dv"):
+        assert not np.isnan(run.host(name)).any()
+
+
 def test_run_to_run_bit_identical_and_plan_reuse():
     import torch
     lengths = [300, 41, 1000, 7]
