@@ -99,7 +99,7 @@ typedef struct {
     int32_t offset;    /* q_pos - k_pos: key j of the chunk is visible to row r of the chunk iff j <= r + offset */
     int32_t tile;      /* q tile index (FWD, DQ) or k tile index (DKV) within the chunk; < 0: padding slot  */
     int32_t head;      /* local q head (FWD, DQ) or local kv head (DKV)                                     */
-    int32_t reserved;  /* 0 */
+    int32_t q_pos;     /* position of the query chunk's first row inside its sequence (the key chunk's is q_pos - offset) */
 } hspmd_block_item;
 
 /* Never NULL.  Thread-local. */
@@ -227,13 +227,21 @@ hspmd_status hspmd_attn_varlen_bwd(const hspmd_attn_plan* plan, const void* q, c
  * hspmd_rope_qk: q_out, k_out = rope(q), rope(k) (inverse != 0: the rotation by the opposite angle).
  *   q, k, q_out, k_out  bf16, layouts and stride rules as in hspmd_attn_varlen_fwd, each with its own token
  *                       stride; q_out == q and k_out == k (in place) are allowed, other overlaps are not
- *   table_positions     positions the table holds; must be >= the longest sequence of the plan
- *   Arithmetic in fp32, one rounding to bf16.  Packed plans only (not the block variant).
+ *   table_positions     positions the table holds; must cover every position a token of the plan has (packed
+ *                       plans: the longest sequence; block plans: the largest q_pos + chunk length and
+ *                       k_pos + chunk length)
+ *   Arithmetic in fp32, one rounding to bf16.  With a block plan (hspmd_attn_block_plan_create) q is the
+ *   plan's query chunks and k its key chunks, each token rotated by its position inside its sequence
+ *   (q_pos / k_pos of the chunk + index in the chunk): a device rotates its own chunks once, and the rotated
+ *   key chunk travels around the ring.
  * hspmd_attn_varlen_bwd_rope: hspmd_attn_varlen_bwd where q and k are the ROTATED tensors the forward consumed
  *   and dq, dk are returned with respect to the unrotated ones (dv is unaffected).  Other arguments, workspace and
  *   errors as hspmd_attn_varlen_bwd.
- * Errors: INVALID_ARG for NULL / misaligned pointers, bad strides, a table that is too short, a block plan;
- * UNSUPPORTED for a head_dim outside the supported set.  Nothing is launched on error.
+ * hspmd_attn_block_bwd_rope: the same for hspmd_attn_block_bwd; the rotation is linear, so the accumulated dq
+ *   (dq_accumulate) is the sum of the blocks' turned-back shares, and each block's dk is turned back before it
+ *   travels on.
+ * Errors: INVALID_ARG for NULL / misaligned pointers, bad strides, a table that is too short, the wrong kind of
+ * plan; UNSUPPORTED for a head_dim outside the supported set.  Nothing is launched on error.
  */
 size_t hspmd_rope_table_bytes(int32_t positions, int32_t head_dim);   /* 0 on bad arguments */
 hspmd_status hspmd_rope_table(float* table, int32_t positions, int32_t head_dim, double base, void* stream);
@@ -246,6 +254,11 @@ hspmd_status hspmd_attn_varlen_bwd_rope(const hspmd_attn_plan* plan, const void*
                                         int64_t kv_token_stride, float softmax_scale, void* dq, void* dk, void* dv,
                                         hspmd_grad_dtype grad_dtype, const float* table, int32_t table_positions,
                                         void* workspace, size_t workspace_bytes, void* stream);
+hspmd_status hspmd_attn_block_bwd_rope(const hspmd_attn_plan* plan, const void* q, const void* k, const void* v,
+                                       const void* o, const float* lse, const void* d_o, int64_t q_token_stride,
+                                       int64_t kv_token_stride, float softmax_scale, float* dq, int32_t dq_accumulate,
+                                       float* dk, float* dv, int32_t reuse_statistics, const float* table,
+                                       int32_t table_positions, void* workspace, size_t workspace_bytes, void* stream);
 
 /*
  * Predicted kernel time (milliseconds, MI355X) of forward and backward of a pack on this library's

@@ -31,7 +31,7 @@ class WorkItem(ctypes.Structure):
 class BlockItem(ctypes.Structure):
     _fields_ = [("q_start", ctypes.c_int32), ("q_len", ctypes.c_int32), ("k_start", ctypes.c_int32),
                 ("k_len", ctypes.c_int32), ("offset", ctypes.c_int32), ("tile", ctypes.c_int32),
-                ("head", ctypes.c_int32), ("reserved", ctypes.c_int32)]
+                ("head", ctypes.c_int32), ("q_pos", ctypes.c_int32)]
 
 
 _lib = None
@@ -100,6 +100,10 @@ def load_library():
     lib.hspmd_attn_varlen_bwd_rope.argtypes = [vp, vp, vp, vp, vp, vp, vp, ctypes.c_int64, ctypes.c_int64,
                                                ctypes.c_float, vp, vp, vp, ctypes.c_int, vp, ctypes.c_int32, vp,
                                                ctypes.c_size_t, vp]
+    lib.hspmd_attn_block_bwd_rope.restype = ctypes.c_int
+    lib.hspmd_attn_block_bwd_rope.argtypes = [vp, vp, vp, vp, vp, vp, vp, ctypes.c_int64, ctypes.c_int64, ctypes.c_float,
+                                              vp, ctypes.c_int32, vp, vp, ctypes.c_int32, vp, ctypes.c_int32, vp,
+                                              ctypes.c_size_t, vp]
     lib.hspmd_attn_estimate_ms.restype = ctypes.c_int
     lib.hspmd_attn_estimate_ms.argtypes = [i32p, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32,
                                            ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_double)]
@@ -327,7 +331,7 @@ def probe_mfma_tflops(scratch, mfma_per_wave: int = 1 << 18, stream=None, varied
 def block_schedule(kind: int, cu_q: Sequence[int], cu_k: Sequence[int], q_pos: Sequence[int], k_pos: Sequence[int],
                    q_heads: int, kv_heads: int, num_queues: int = 8) -> np.ndarray:
     """Host-only: the launch-ordered block work list as an int32 array [slots, 8]
-    (q_start, q_len, k_start, k_len, offset, tile, head, 0); padding slots have tile == -1."""
+    (q_start, q_len, k_start, k_len, offset, tile, head, q_pos); padding slots have tile == -1."""
     lib = load_library()
     cq, ck, qp, kp = _i32(cu_q), _i32(cu_k), _i32(q_pos), _i32(k_pos)
     if not (len(cq) == len(ck) == len(qp) + 1 == len(kp) + 1):
@@ -393,6 +397,18 @@ def attn_block_bwd(plan: BlockPlan, q, k, v, o, lse, d_o, dq, dk, dv, workspace,
                                                _dev_ptr(dq), 1 if dq_accumulate else 0, _dev_ptr(dk), _dev_ptr(dv),
                                                1 if reuse_statistics else 0, _dev_ptr(workspace),
                                                workspace.numel() * workspace.element_size(), _stream_handle(stream)))
+
+
+def attn_block_bwd_rope(plan: BlockPlan, q, k, v, o, lse, d_o, dq, dk, dv, workspace, table, table_positions: int,
+                        softmax_scale: float = 0.0, dq_accumulate: bool = False, reuse_statistics: bool = False,
+                        stream=None) -> None:
+    """attn_block_bwd for rotated q, k chunks; dq and dk come back with respect to the unrotated tensors."""
+    _check(load_library().hspmd_attn_block_bwd_rope(
+        plan.handle, _dev_ptr(q), _dev_ptr(k), _dev_ptr(v), _opt_ptr(o), _opt_ptr(lse), _dev_ptr(d_o),
+        _token_stride(q, plan.q_heads, plan.head_dim), _token_stride(k, plan.kv_heads, plan.head_dim),
+        float(softmax_scale), _dev_ptr(dq), 1 if dq_accumulate else 0, _dev_ptr(dk), _dev_ptr(dv),
+        1 if reuse_statistics else 0, _dev_ptr(table), int(table_positions), _dev_ptr(workspace),
+        workspace.numel() * workspace.element_size(), _stream_handle(stream)))
 
 
 def estimate_ms(cu_seqlens: Sequence[int], q_heads: int, kv_heads: int, head_dim: int) -> Tuple[float, float]:

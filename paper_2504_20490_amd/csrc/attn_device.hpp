@@ -325,7 +325,9 @@ __device__ __forceinline__ void store_tile_bf16(char* wave_lds, const f32x16 (&a
 // 4 partner columns (head_dim/2 is a multiple of 4) from LDS and writes both; cos and sin come from the caller's table
 // [position][head_dim/2] of (cos, sin) pairs, `table_row0` pointing at the position of the tile's first row
 // (the 32 rows are consecutive positions).
-template <int D>
+//   ACCUM: add to what the destination holds (fp32 only; the rotation is linear, so a sum of rotated shares is the
+//   rotated sum)
+template <int D, bool ACCUM = false>
 __device__ __forceinline__ void store_tile_rope_transposed(char* wave_lds, const f32x16 (&acc)[D / 32], float mul, void* base,
                                                            int64_t first_elem, bool f32, int64_t row_stride, int valid_rows,
                                                            int head_dim, const float* table_row0, int lane) {
@@ -365,10 +367,21 @@ __device__ __forceinline__ void store_tile_rope_transposed(char* wave_lds, const
             const float cs[4] = {t01[it][0], t01[it][2], t23[it][0], t23[it][2]};
             const float sn[4] = {t01[it][1], t01[it][3], t23[it][1], t23[it][3]};
             const int64_t e = first_elem + row * row_stride + c * 4;
-            store_grad4(base, e, f32, lo[0] * cs[0] + hi[0] * sn[0], lo[1] * cs[1] + hi[1] * sn[1],
-                        lo[2] * cs[2] + hi[2] * sn[2], lo[3] * cs[3] + hi[3] * sn[3]);
-            store_grad4(base, e + head_dim / 2, f32, hi[0] * cs[0] - lo[0] * sn[0], hi[1] * cs[1] - lo[1] * sn[1],
-                        hi[2] * cs[2] - lo[2] * sn[2], hi[3] * cs[3] - lo[3] * sn[3]);
+            f32x4 x_lo, x_hi;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                x_lo[j] = lo[j] * cs[j] + hi[j] * sn[j];
+                x_hi[j] = hi[j] * cs[j] - lo[j] * sn[j];
+            }
+            if constexpr (ACCUM) {
+                float* dst = static_cast<float*>(base) + e;
+                const f32x4 old_lo = *reinterpret_cast<const f32x4*>(dst);
+                const f32x4 old_hi = *reinterpret_cast<const f32x4*>(dst + head_dim / 2);
+#pragma unroll
+                for (int j = 0; j < 4; ++j) { x_lo[j] += old_lo[j]; x_hi[j] += old_hi[j]; }
+            }
+            store_grad4(base, e, f32, x_lo[0], x_lo[1], x_lo[2], x_lo[3]);
+            store_grad4(base, e + head_dim / 2, f32, x_hi[0], x_hi[1], x_hi[2], x_hi[3]);
         }
     }
 }
@@ -394,15 +407,16 @@ struct InterleaveHint {
 // are copies and offset is the constant 0, so the general index arithmetic folds back to the plain one.
 struct ItemGeom {
     int q_start, q_len, k_start, k_len, offset, tile, head;
+    int q_pos;   // position of the chunk's first row inside its sequence (0 when !BLOCK); the key chunk's is q_pos - offset
 };
 template <bool BLOCK>
 __device__ __forceinline__ ItemGeom load_item(const hspmd_work_item* items, const hspmd_block_item* block_items, int idx) {
     if constexpr (BLOCK) {
         const hspmd_block_item it = block_items[idx];
-        return ItemGeom{it.q_start, it.q_len, it.k_start, it.k_len, it.offset, it.tile, it.head};
+        return ItemGeom{it.q_start, it.q_len, it.k_start, it.k_len, it.offset, it.tile, it.head, it.q_pos};
     } else {
         const hspmd_work_item it = items[idx];
-        return ItemGeom{it.token_start, it.seq_len, it.token_start, it.seq_len, 0, it.tile, it.head};
+        return ItemGeom{it.token_start, it.seq_len, it.token_start, it.seq_len, 0, it.tile, it.head, 0};
     }
 }
 

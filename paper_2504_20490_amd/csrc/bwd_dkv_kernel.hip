@@ -432,16 +432,16 @@ __global__ __launch_bounds__(kThreads, 1) void bwd_dkv_kernel(BwdParams p) {
     }
 
     // whole rows per store instruction, staged through LDS (free once every wave has left the tile loop)
-    const bool rope = !BLOCK && p.rope_table != nullptr;
+    const bool rope = p.rope_table != nullptr;
     __syncthreads();
     char* wave_lds = lds + wave * (32 * D * 4);
     const int64_t row0_elem = ((int64_t)(item.k_start + wave_key0) * p.kv_heads + g) * hd;
     const int64_t row_stride = (int64_t)p.kv_heads * hd;
     const int rows = min(32, Lk - wave_key0);
     if (rope) {
-        // dK with respect to the keys before their rotary embedding; key positions = index in the sequence
+        // dK with respect to the keys before their rotary embedding; key positions inside the sequence
         store_tile_rope_transposed<D>(wave_lds, st.dk, p.scale, p.dk, row0_elem, p.grad_f32 != 0, row_stride, rows, hd,
-                                      p.rope_table + (int64_t)wave_key0 * hd, lane);
+                                      p.rope_table + (int64_t)(item.q_pos - item.offset + wave_key0) * hd, lane);
     } else if (p.grad_f32 != 0) {
         store_tile_f32<D, false>(wave_lds, st.dk, p.scale, static_cast<float*>(p.dk) + row0_elem, row_stride, rows, hd, lane);
     } else {

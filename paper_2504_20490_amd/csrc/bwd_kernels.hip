@@ -268,13 +268,18 @@ __global__ __launch_bounds__(kThreads, 2) void bwd_dq_kernel(BwdParams p) {
     for (; kt < n_interior; ++kt) step(kt, std::false_type{});
     for (; kt < n_tiles; ++kt) step(kt, std::true_type{});
 
-    if (!BLOCK && p.rope_table != nullptr) {
-        // dQ with respect to the queries before their rotary embedding; row positions = index in the sequence
+    if (p.rope_table != nullptr) {
+        // dQ with respect to the queries before their rotary embedding; row positions inside the sequence
         __syncthreads();
-        store_tile_rope_transposed<D>(lds + wave * (32 * D * 4), acc, p.scale, p.dq,
-                                      ((int64_t)(item.q_start + wave_row0) * p.q_heads + h) * hd, p.grad_f32 != 0,
-                                      (int64_t)p.q_heads * hd, min(32, Lq - wave_row0), hd,
-                                      p.rope_table + (int64_t)wave_row0 * hd, lane);
+        char* wave_lds = lds + wave * (32 * D * 4);
+        const int64_t first_elem = ((int64_t)(item.q_start + wave_row0) * p.q_heads + h) * hd;
+        const float* table_row0 = p.rope_table + (int64_t)(item.q_pos + wave_row0) * hd;
+        if (BLOCK && p.dq_accumulate)
+            store_tile_rope_transposed<D, true>(wave_lds, acc, p.scale, p.dq, first_elem, true, (int64_t)p.q_heads * hd,
+                                                min(32, Lq - wave_row0), hd, table_row0, lane);
+        else
+            store_tile_rope_transposed<D, false>(wave_lds, acc, p.scale, p.dq, first_elem, p.grad_f32 != 0,
+                                                 (int64_t)p.q_heads * hd, min(32, Lq - wave_row0), hd, table_row0, lane);
     } else if (p.grad_f32 != 0) {
         // whole rows per store instruction, staged through LDS (free once every wave has left the tile loop)
         __syncthreads();

@@ -75,7 +75,7 @@ struct hspmd_attn_plan {
     int32_t num_seqs = 0;
     int32_t q_heads = 0, kv_heads = 0, head_dim = 0;
     int64_t total_tokens = 0;
-    int32_t max_seq_len = 0;
+    int32_t max_position = 0;      // positions inside a sequence that the plan's tokens occupy: 0 .. max_position-1
     int64_t count[3] = {0, 0, 0};
     hspmd_work_item* items[3] = {nullptr, nullptr, nullptr};   // device; three views into one allocation
     void* device_block = nullptr;
@@ -163,7 +163,7 @@ hspmd_status hspmd_attn_plan_create_ordered(const int32_t* cu_seqlens_host, int3
     plan->head_dim = head_dim;
     plan->total_tokens = cu_seqlens_host[num_seqs];
     for (int32_t i = 0; i < num_seqs; ++i)
-        plan->max_seq_len = std::max(plan->max_seq_len, cu_seqlens_host[i + 1] - cu_seqlens_host[i]);
+        plan->max_position = std::max(plan->max_position, cu_seqlens_host[i + 1] - cu_seqlens_host[i]);
     // the three lists back to back in one host vector -> one allocation, one copy, one synchronisation
     std::vector<hspmd_work_item> all;
     size_t offset[3] = {0, 0, 0};
@@ -345,12 +345,11 @@ hspmd_status hspmd_attn_varlen_bwd(const hspmd_attn_plan* plan, const void* q, c
 
 static hspmd_status check_rope_table(const hspmd_attn_plan* plan, const float* table, int32_t table_positions) {
     if (!plan) return fail(HSPMD_ERR_INVALID_ARG, "plan is NULL");
-    if (plan->is_block) return fail(HSPMD_ERR_INVALID_ARG, "plan was made by hspmd_attn_block_plan_create");
-    if (plan->total_tokens == 0) return HSPMD_OK;
+    if (plan->total_tokens == 0 && plan->total_kv_tokens == 0) return HSPMD_OK;
     if (!table) return fail(HSPMD_ERR_INVALID_ARG, "rope table is NULL");
     if (!aligned16(table)) return fail(HSPMD_ERR_INVALID_ARG, "rope table must be 16-byte aligned");
-    if (table_positions < plan->max_seq_len)
-        return fail(HSPMD_ERR_INVALID_ARG, "rope table has fewer positions than the longest sequence of the plan");
+    if (table_positions < plan->max_position)
+        return fail(HSPMD_ERR_INVALID_ARG, "rope table has fewer positions than the plan's tokens occupy");
     return HSPMD_OK;
 }
 
@@ -376,8 +375,9 @@ hspmd_status hspmd_rope_qk(const hspmd_attn_plan* plan, const void* q, const voi
                            int64_t kv_out_token_stride, const float* table, int32_t table_positions, int32_t inverse,
                            void* stream) {
     if (hspmd_status rc = check_rope_table(plan, table, table_positions)) return rc;
-    if (plan->total_tokens == 0) return HSPMD_OK;
-    if (!q || !k || !q_out || !k_out) return fail(HSPMD_ERR_INVALID_ARG, "null tensor pointer");
+    if (plan->total_tokens == 0 && plan->total_kv_tokens == 0) return HSPMD_OK;
+    if ((plan->total_tokens > 0 && (!q || !q_out)) || ((plan->is_block ? plan->total_kv_tokens : plan->total_tokens) > 0 && (!k || !k_out)))
+        return fail(HSPMD_ERR_INVALID_ARG, "null tensor pointer");
     if (!aligned16(q) || !aligned16(k) || !aligned16(q_out) || !aligned16(k_out))
         return fail(HSPMD_ERR_INVALID_ARG, "q, k, q_out, k_out must be 16-byte aligned");
     if (hspmd_status rc = check_strides(plan, q_token_stride, kv_token_stride)) return rc;
@@ -398,6 +398,16 @@ hspmd_status hspmd_rope_qk(const hspmd_attn_plan* plan, const void* q, const voi
     p.head_dim = plan->head_dim;
     p.sin_sign = inverse ? -1.f : 1.f;
     hipStream_t s = static_cast<hipStream_t>(stream);
+    if (plan->is_block) {
+        // query chunks through the forward list, key chunks through the dK/dV list
+        p.block_items = plan->block_items[HSPMD_LIST_FWD];
+        hipError_t e = timed_launch(4, s, [&] { return hspmd::launch_rope_block(p, plan->count[HSPMD_LIST_FWD], false, s); });
+        if (e != hipSuccess) return fail_hip(e, "rope launch (query chunks)");
+        p.block_items = plan->block_items[HSPMD_LIST_DKV];
+        e = timed_launch(4, s, [&] { return hspmd::launch_rope_block(p, plan->count[HSPMD_LIST_DKV], true, s); });
+        if (e != hipSuccess) return fail_hip(e, "rope launch (key chunks)");
+        return HSPMD_OK;
+    }
     const hipError_t e = timed_launch(4, s, [&] { return hspmd::launch_rope_qk(p, plan->count[HSPMD_LIST_FWD], s); });
     if (e != hipSuccess) return fail_hip(e, "rope launch");
     return HSPMD_OK;
@@ -408,6 +418,7 @@ hspmd_status hspmd_attn_varlen_bwd_rope(const hspmd_attn_plan* plan, const void*
                                         int64_t kv_token_stride, float softmax_scale, void* dq, void* dk, void* dv,
                                         hspmd_grad_dtype grad_dtype, const float* table, int32_t table_positions,
                                         void* workspace, size_t workspace_bytes, void* stream) {
+    if (plan && plan->is_block) return fail(HSPMD_ERR_INVALID_ARG, "plan was made by hspmd_attn_block_plan_create");
     if (hspmd_status rc = check_rope_table(plan, table, table_positions)) return rc;
     return varlen_bwd(plan, q, k, v, o, lse, d_o, q_token_stride, kv_token_stride, softmax_scale, dq, dk, dv, grad_dtype,
                       table, workspace, workspace_bytes, stream);
@@ -473,6 +484,9 @@ hspmd_status hspmd_attn_block_plan_create(const int32_t* cu_q_host, const int32_
     plan->head_dim = head_dim;
     plan->total_tokens = cu_q_host[num_seqs];
     plan->total_kv_tokens = cu_k_host[num_seqs];
+    for (int32_t i = 0; i < num_seqs; ++i)
+        plan->max_position = std::max(plan->max_position, std::max(q_pos_host[i] + (cu_q_host[i + 1] - cu_q_host[i]),
+                                                                   k_pos_host[i] + (cu_k_host[i + 1] - cu_k_host[i])));
     std::vector<hspmd_block_item> all;
     size_t offset[3] = {0, 0, 0};
     try {
@@ -576,11 +590,12 @@ hspmd_status hspmd_attn_merge(int64_t total_tokens, int32_t local_q_heads, int32
     return HSPMD_OK;
 }
 
-hspmd_status hspmd_attn_block_bwd(const hspmd_attn_plan* plan, const void* q, const void* k, const void* v,
-                                  const void* o, const float* lse, const void* d_o,
-                                  int64_t q_token_stride, int64_t kv_token_stride, float softmax_scale,
-                                  float* dq, int32_t dq_accumulate, float* dk, float* dv, int32_t reuse_statistics,
-                                  void* workspace, size_t workspace_bytes, void* stream) {
+// rope_table == NULL: plain block backward
+static hspmd_status block_bwd(const hspmd_attn_plan* plan, const void* q, const void* k, const void* v, const void* o,
+                              const float* lse, const void* d_o, int64_t q_token_stride, int64_t kv_token_stride,
+                              float softmax_scale, float* dq, int32_t dq_accumulate, float* dk, float* dv,
+                              int32_t reuse_statistics, const float* rope_table, void* workspace, size_t workspace_bytes,
+                              void* stream) {
     if (!plan) return fail(HSPMD_ERR_INVALID_ARG, "plan is NULL");
     if (!plan->is_block) return fail(HSPMD_ERR_INVALID_ARG, "plan was not made by hspmd_attn_block_plan_create");
     if (plan->total_tokens == 0 && plan->total_kv_tokens == 0) return HSPMD_OK;
@@ -618,6 +633,7 @@ hspmd_status hspmd_attn_block_bwd(const hspmd_attn_plan* plan, const void* q, co
     p.head_dim = plan->head_dim;
     p.grad_f32 = 1;
     p.dq_accumulate = dq_accumulate ? 1 : 0;
+    p.rope_table = rope_table;
     p.scale = scale;
     p.scale_log2 = scale * 1.4426950408889634f;
     hipStream_t s = static_cast<hipStream_t>(stream);
@@ -633,6 +649,26 @@ hspmd_status hspmd_attn_block_bwd(const hspmd_attn_plan* plan, const void* q, co
     e = timed_launch(3, s, [&] { return hspmd::launch_bwd_dkv(p, plan->head_dim, plan->count[HSPMD_LIST_DKV], true, s); });
     if (e != hipSuccess) return fail_hip(e, "block backward dK/dV launch");
     return HSPMD_OK;
+}
+
+hspmd_status hspmd_attn_block_bwd(const hspmd_attn_plan* plan, const void* q, const void* k, const void* v,
+                                  const void* o, const float* lse, const void* d_o,
+                                  int64_t q_token_stride, int64_t kv_token_stride, float softmax_scale,
+                                  float* dq, int32_t dq_accumulate, float* dk, float* dv, int32_t reuse_statistics,
+                                  void* workspace, size_t workspace_bytes, void* stream) {
+    return block_bwd(plan, q, k, v, o, lse, d_o, q_token_stride, kv_token_stride, softmax_scale, dq, dq_accumulate, dk, dv,
+                     reuse_statistics, nullptr, workspace, workspace_bytes, stream);
+}
+
+hspmd_status hspmd_attn_block_bwd_rope(const hspmd_attn_plan* plan, const void* q, const void* k, const void* v,
+                                       const void* o, const float* lse, const void* d_o, int64_t q_token_stride,
+                                       int64_t kv_token_stride, float softmax_scale, float* dq, int32_t dq_accumulate,
+                                       float* dk, float* dv, int32_t reuse_statistics, const float* table,
+                                       int32_t table_positions, void* workspace, size_t workspace_bytes, void* stream) {
+    if (plan && !plan->is_block) return fail(HSPMD_ERR_INVALID_ARG, "plan was not made by hspmd_attn_block_plan_create");
+    if (hspmd_status rc = check_rope_table(plan, table, table_positions)) return rc;
+    return block_bwd(plan, q, k, v, o, lse, d_o, q_token_stride, kv_token_stride, softmax_scale, dq, dq_accumulate, dk, dv,
+                     reuse_statistics, table, workspace, workspace_bytes, stream);
 }
 
 hspmd_status hspmd_profile_enable(int32_t on) {

@@ -44,7 +44,7 @@ struct BwdParams {
     int32_t head_dim;              // elements per head in memory (a multiple of 8, at most the kernel's tile width)
     int32_t grad_f32;              // 1: gradients are fp32, 0: bf16
     int32_t dq_accumulate;         // block variant only: dq += this block's share (fp32) instead of dq = ...
-    const float* rope_table;       // packed variant only, may be NULL: (cos, sin) pairs [position][head_dim / 2]; dq and dk
+    const float* rope_table;       // may be NULL: (cos, sin) pairs [position][head_dim / 2]; dq and dk
                                    // then leave as gradients with respect to the q and k BEFORE the rotary embedding
     float scale;                   // softmax_scale
     float scale_log2;              // softmax_scale * log2(e)
@@ -82,13 +82,16 @@ struct RopeParams {
     uint16_t* q_out;
     uint16_t* k_out;
     const float* table;            // (cos, sin) pairs [position][head_dim / 2]
-    const hspmd_work_item* items;  // forward list: every (q tile, q head) once
+    const hspmd_work_item* items;  // packed plans: forward list, every (q tile, q head) once
+    const hspmd_block_item* block_items;   // block plans: forward list (query chunks) or dK/dV list (key chunks)
     int64_t q_stride, kv_stride, q_out_stride, kv_out_stride;   // token strides in elements
     int32_t q_heads, group, head_dim;
     float sin_sign;                // +1: rotate, -1: rotate back
 };
 hipError_t launch_rope_table(float* table, int32_t positions, int32_t head_dim, double base, hipStream_t stream);
 hipError_t launch_rope_qk(const RopeParams& p, int64_t num_items, hipStream_t stream);
+// block plans: `keys` selects the key chunks (p.block_items = dK/dV list) or the query chunks (forward list)
+hipError_t launch_rope_block(const RopeParams& p, int64_t num_items, bool keys, hipStream_t stream);
 
 // matrix-core rate probe: `grid` workgroups of kProbeThreads threads, each wave issues 16 * rounds MFMAs and
 // every thread writes one float to out[grid * kProbeThreads]

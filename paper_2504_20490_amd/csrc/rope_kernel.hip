@@ -63,36 +63,63 @@ __device__ __forceinline__ void divmod(int e, int n, float inv_n, int& quot, int
     rem = e - quot * n;
 }
 
-// One workgroup per item of the forward list.  The items (tile, head) of one tile exist once per q head, so the
-// workgroup of head h takes the h-th share of the tile's rows and rotates ALL heads of those rows: a row of q is
-// q_heads * head_dim contiguous elements, and consecutive lanes walk along it (16 bytes of the low half of a head
-// and 16 bytes of its high half per lane).  In place (q_out == q) is fine: a thread reads what it writes.
+// rows r_begin .. r_end-1 (counted from token0, which sits at position pos0 of its sequence) of a [tokens, heads,
+// head_dim] tensor, all heads: consecutive lanes walk along the contiguous token rows (16 or 8 bytes of the low
+// half of a head and as many of its high half per lane).  In place is fine: a thread reads what it writes.
+template <int VEC>
+__device__ __forceinline__ void rotate_rows(const uint16_t* src, uint16_t* dst, int64_t stride, int64_t out_stride,
+                                            int64_t token0, int pos0, int r_begin, int r_end, int heads, int hd,
+                                            const float* table, float sin_sign) {
+    const int half = hd / 2, pieces = half / VEC;   // pieces per head
+    const int per_row = heads * pieces;
+    const float inv_per_row = 1.f / (float)per_row, inv_pieces = 1.f / (float)pieces;
+    for (int e = threadIdx.x; e < (r_end - r_begin) * per_row; e += kRopeThreads) {
+        int r, x, head, piece;
+        divmod(e, per_row, inv_per_row, r, x);
+        divmod(x, pieces, inv_pieces, head, piece);
+        r += r_begin;
+        const int c = piece * VEC;
+        rotate_piece<VEC>(src + (token0 + r) * stride + head * hd + c, dst + (token0 + r) * out_stride + head * hd + c, half,
+                          table + ((int64_t)(pos0 + r) * half + c) * 2, sin_sign);
+    }
+}
+
+// Packed plans: one workgroup per item of the forward list.  The items (tile, head) of one tile exist once per q
+// head, so the workgroup of head h takes the h-th share of the tile's rows and rotates ALL heads of those rows,
+// of q and of k.
 template <int VEC>
 __global__ __launch_bounds__(kRopeThreads) void rope_qk_kernel(RopeParams p) {
     const hspmd_work_item item = p.items[blockIdx.x];
     if (item.tile < 0) return;   // padding slot
-    const int hd = p.head_dim, half = hd / 2;
-    const int pieces = half / VEC;   // per head
     const int row0 = item.tile * kFwdQTile;
     const int rows = min(kFwdQTile, item.seq_len - row0);
     const int r_begin = rows * item.head / p.q_heads, r_end = rows * (item.head + 1) / p.q_heads;
     const int64_t token0 = (int64_t)item.token_start + row0;
-    const float inv_pieces = 1.f / (float)pieces;
-    auto rotate_rows = [&](const uint16_t* src, uint16_t* dst, int64_t stride, int64_t out_stride, int heads) {
-        const int per_row = heads * pieces;
-        const float inv_per_row = 1.f / (float)per_row;
-        for (int e = threadIdx.x; e < (r_end - r_begin) * per_row; e += kRopeThreads) {
-            int r, x, head, piece;
-            divmod(e, per_row, inv_per_row, r, x);
-            divmod(x, pieces, inv_pieces, head, piece);
-            r += r_begin;
-            const int c = piece * VEC;
-            rotate_piece<VEC>(src + (token0 + r) * stride + head * hd + c, dst + (token0 + r) * out_stride + head * hd + c,
-                              half, p.table + ((int64_t)(row0 + r) * half + c) * 2, p.sin_sign);
-        }
-    };
-    rotate_rows(p.q, p.q_out, p.q_stride, p.q_out_stride, p.q_heads);
-    rotate_rows(p.k, p.k_out, p.kv_stride, p.kv_out_stride, p.q_heads / p.group);
+    rotate_rows<VEC>(p.q, p.q_out, p.q_stride, p.q_out_stride, token0, row0, r_begin, r_end, p.q_heads, p.head_dim, p.table,
+                     p.sin_sign);
+    rotate_rows<VEC>(p.k, p.k_out, p.kv_stride, p.kv_out_stride, token0, row0, r_begin, r_end, p.q_heads / p.group,
+                     p.head_dim, p.table, p.sin_sign);
+}
+
+// Block plans: the query chunks are walked through the forward list (items (q tile, q head)), the key chunks through
+// the dK/dV list (items (k tile, kv head)); positions are those of the chunks inside their sequences.
+template <int VEC, bool KEYS>
+__global__ __launch_bounds__(kRopeThreads) void rope_block_kernel(RopeParams p) {
+    const hspmd_block_item item = p.block_items[blockIdx.x];
+    if (item.tile < 0) return;   // padding slot
+    const int tile_rows = KEYS ? kDkvKTile : kFwdQTile;
+    const int heads = KEYS ? p.q_heads / p.group : p.q_heads;
+    const int len = KEYS ? item.k_len : item.q_len;
+    const int row0 = item.tile * tile_rows;
+    const int rows = min(tile_rows, len - row0);
+    if (rows <= 0) return;
+    const int r_begin = rows * item.head / heads, r_end = rows * (item.head + 1) / heads;
+    if constexpr (KEYS)
+        rotate_rows<VEC>(p.k, p.k_out, p.kv_stride, p.kv_out_stride, (int64_t)item.k_start + row0,
+                         item.q_pos - item.offset + row0, r_begin, r_end, heads, p.head_dim, p.table, p.sin_sign);
+    else
+        rotate_rows<VEC>(p.q, p.q_out, p.q_stride, p.q_out_stride, (int64_t)item.q_start + row0, item.q_pos + row0, r_begin,
+                         r_end, heads, p.head_dim, p.table, p.sin_sign);
 }
 
 }  // namespace
@@ -111,6 +138,20 @@ hipError_t launch_rope_qk(const RopeParams& p, int64_t num_items, hipStream_t st
     // 16-byte pieces when half a head is a whole number of them, 8-byte pieces otherwise (head_dim is a multiple of 8)
     if ((p.head_dim / 2) % 8 == 0) hipLaunchKernelGGL(rope_qk_kernel<8>, grid, threads, 0, stream, p);
     else hipLaunchKernelGGL(rope_qk_kernel<4>, grid, threads, 0, stream, p);
+    return hipGetLastError();
+}
+
+hipError_t launch_rope_block(const RopeParams& p, int64_t num_items, bool keys, hipStream_t stream) {
+    if (num_items == 0) return hipSuccess;
+    const dim3 grid((unsigned)num_items), threads(kRopeThreads);
+    const bool wide = (p.head_dim / 2) % 8 == 0;
+    if (keys) {
+        if (wide) hipLaunchKernelGGL((rope_block_kernel<8, true>), grid, threads, 0, stream, p);
+        else hipLaunchKernelGGL((rope_block_kernel<4, true>), grid, threads, 0, stream, p);
+    } else {
+        if (wide) hipLaunchKernelGGL((rope_block_kernel<8, false>), grid, threads, 0, stream, p);
+        else hipLaunchKernelGGL((rope_block_kernel<4, false>), grid, threads, 0, stream, p);
+    }
     return hipGetLastError();
 }
 

@@ -252,7 +252,7 @@ std::vector<hspmd_block_item> build_block_list(hspmd_list_kind kind, const int32
         if (rows <= 0) continue;
         const int tile_rows = (kind == HSPMD_LIST_DKV) ? kDkvKTile : kFwdQTile;
         const int32_t n_tiles = (int32_t)ceil_div(rows, tile_rows);
-        const hspmd_block_item proto{cu_q[s], q_len, cu_k[s], k_len, q_pos[s] - k_pos[s], 0, 0, 0};
+        const hspmd_block_item proto{cu_q[s], q_len, cu_k[s], k_len, q_pos[s] - k_pos[s], 0, 0, q_pos[s]};
         for (int32_t g = 0; g < hkv; ++g) {
             std::vector<hspmd_block_item> chain;
             auto add = [&](int32_t tile, int32_t head) {

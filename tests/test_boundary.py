@@ -207,7 +207,9 @@ def test_block_work_list_invariants(kind):
     items = A.block_schedule(kind, cq, ck, qp, kp, hq, hkv)
     assert items.shape[1] == 8 and items.shape[0] % 8 == 0
     real = items[items[:, 5] >= 0]
-    assert np.all(items[items[:, 5] < 0][:, 5] == -1) and np.all(real[:, 7] == 0)
+    assert np.all(items[items[:, 5] < 0][:, 5] == -1)
+    q_pos_of = {(int(cq[i]), ql[i], int(ck[i]), kl[i]): qp[i] for i in range(len(ql))}     # the chunk's position travels with the item
+    assert all(int(r[7]) == q_pos_of[(int(r[0]), int(r[1]), int(r[2]), int(r[3]))] for r in real)
     # every tile that owns output rows appears exactly once per head, with its sequence's geometry
     expected = set()
     for i in range(len(ql)):

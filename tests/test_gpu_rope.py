@@ -227,11 +227,93 @@ def test_validation():
         A.rope_table(table, 128, 100)
     assert A.rope_table_bytes(128, 64) == 128 * 32 * 2 * 4 and A.rope_table_bytes(4, 100) == 0
     cu, _, _ = A.build_cu_seqlens(lengths)
-    bplan = A.BlockPlan(cu, cu, [0, 0], [0, 0], hq, hkv, d)
+    bplan = A.BlockPlan(cu, cu, [0, 28], [0, 0], hq, hkv, d)      # the second query chunk sits at positions 28 .. 57
     with pytest.raises(A.HspmdError, match="block"):
-        A.rope_qk(bplan, run.q, run.k, run.q, run.k, table, 128)
+        A.attn_varlen_bwd_rope(bplan, run.q, run.k, run.v, run.o, run.lse, run.do, run.dq, run.dk, run.dv, run.ws,
+                               table, 128)
+    with pytest.raises(A.HspmdError, match="block"):
+        A.attn_block_bwd_rope(run.plan, run.q, run.k, run.v, run.o, run.lse, run.do, run.dq, run.dk, run.dv, run.ws,
+                              table, 128)
+    with pytest.raises(A.HspmdError, match="fewer positions"):
+        A.rope_qk(bplan, run.q, run.k, run.q, run.k, table, 99)      # chunk 0 alone occupies positions 0 .. 99
+    far = A.BlockPlan(cu, cu, [0, 99], [0, 0], hq, hkv, d)           # the second query chunk ends at position 128
+    with pytest.raises(A.HspmdError, match="fewer positions"):
+        A.rope_qk(far, run.q, run.k, run.q, run.k, table, 128)       # 99 + 30 = 129 positions are needed
     # an empty pack is a no-op
     cu0, _, _ = A.build_cu_seqlens([0, 0])
     empty = A.Plan(cu0, hq, hkv, d)
     z = torch.empty(0, hq, d, dtype=torch.bfloat16, device="cuda")
     A.rope_qk(empty, z, z, z, z, table, 0)
+
+
+@pytest.mark.parametrize("hq,hkv,d", [(4, 2, 128), (2, 2, 64), (2, 1, 104)])
+def test_emulated_ring_with_rotary_embedding(hq, hkv, d):
+    """Every sequence cut into 3 chunks by position; 'device' c rotates its own query and key chunks once (positions
+    inside the sequences), meets the rotated key chunks one after the other (block forward + merge), and runs the
+    block backward with the transposed rotation fused: the accumulated dQ and the per-chunk dK summed over the devices
+    equal the fp64 chain rope -> whole-sequence attention -> transposed rope."""
+    import paper_2504_20490_amd as A
+    torch = _torch()
+    gpu_util.CONTEXT["case"] = f"rope_ring_d{d}"
+    lengths = [700, 1500, 260, 97]
+    n_dev, T = 3, sum(lengths)
+    q, k, v, do = make_case(lengths, hq, hkv, d, seed=600 + d)
+    s = default_scale(d)
+    pos_all = orope.positions_of(lengths)
+    qr, kr = orope.rope(f64(q), pos_all, BASE), orope.rope(f64(k), pos_all, BASE)
+    ro, rl = oracle.attn_fwd(qr, kr, f64(v), lengths, s)
+    rdq, rdk, rdv = oracle.attn_bwd(qr, kr, f64(v), f64(do), lengths, s)
+    rdq, rdk = orope.rope_transposed(rdq, pos_all, BASE), orope.rope_transposed(rdk, pos_all, BASE)
+    cu = np.concatenate([[0], np.cumsum(lengths)])
+    edges = [[0, L // 4, (2 * L) // 3, L] for L in lengths]
+    edges[3] = [0, 0, 50, 97]                                   # one empty chunk
+    tok = lambda c: np.concatenate([np.arange(cu[i] + edges[i][c], cu[i] + edges[i][c + 1]) for i in range(len(lengths))])
+    lens = lambda c: [edges[i][c + 1] - edges[i][c] for i in range(len(lengths))]
+    pos = lambda c: [edges[i][c] for i in range(len(lengths))]
+    cuof = lambda ls: np.concatenate([[0], np.cumsum(ls)]).astype(np.int32)
+    table = _table(max(lengths), d)
+    # every device rotates its own chunks (q and k of chunk c) with the plan of its diagonal block
+    rot_q, rot_k = {}, {}
+    for c in range(n_dev):
+        own = A.BlockPlan(cuof(lens(c)), cuof(lens(c)), pos(c), pos(c), hq, hkv, d)
+        qc, kc = to_dev(q[tok(c)]), to_dev(k[tok(c)])
+        A.rope_qk(own, qc, kc, qc, kc, table, max(lengths))
+        rot_q[c], rot_k[c] = qc, kc
+    torch.cuda.synchronize()
+    for c in range(n_dev):
+        _assert_rounded(f"rope(q) chunk {c}", _bits(rot_q[c]), qr[tok(c)])
+        _assert_rounded(f"rope(k) chunk {c}", _bits(rot_k[c]), kr[tok(c)])
+    dk_total = np.zeros((T, hkv, d)); dv_total = np.zeros((T, hkv, d))
+    for c in range(n_dev):
+        tq = tok(c)
+        Tq = len(tq)
+        dod = to_dev(do[tq])
+        o_acc = torch.zeros(Tq, hq, d, dtype=torch.float32, device="cuda")
+        lse_acc = torch.full((hq, Tq), float("-inf"), dtype=torch.float32, device="cuda")
+        o_part = torch.empty_like(o_acc); lse_part = torch.empty_like(lse_acc)
+        o_bf16 = torch.full((Tq, hq, d), float("nan"), dtype=torch.bfloat16, device="cuda")
+        plans = []
+        for kc in range(n_dev):
+            plan = A.BlockPlan(cuof(lens(c)), cuof(lens(kc)), pos(c), pos(kc), hq, hkv, d)
+            A.attn_block_fwd(plan, rot_q[c], rot_k[kc], to_dev(v[tok(kc)]), o_part, lse_part)
+            A.attn_merge(o_acc, lse_acc, o_part, lse_part, o_acc, lse_acc, o_bf16 if kc == n_dev - 1 else None)
+            plans.append(plan)
+        torch.cuda.synchronize()
+        assert_close(f"O merged, device {c}", o_bf16.float().cpu().numpy().astype(np.float64), ro[tq])
+        assert np.max(np.abs(lse_acc.cpu().numpy().astype(np.float64) - rl[:, tq])) <= 5e-3
+        dq = torch.full((Tq, hq, d), float("nan"), dtype=torch.float32, device="cuda")
+        ws = torch.empty(max(plans[0].bwd_workspace_bytes(), 16), dtype=torch.uint8, device="cuda")
+        for kc, plan in enumerate(plans):
+            tk = tok(kc)
+            dk = torch.full((len(tk), hkv, d), float("nan"), dtype=torch.float32, device="cuda")
+            dv = torch.full_like(dk, float("nan"))
+            A.attn_block_bwd_rope(plan, rot_q[c], rot_k[kc], to_dev(v[tk]), o_bf16, lse_acc, dod, dq, dk, dv, ws, table,
+                                  max(lengths), dq_accumulate=kc > 0, reuse_statistics=kc > 0)
+            torch.cuda.synchronize()
+            got_dk, got_dv = dk.cpu().numpy().astype(np.float64), dv.cpu().numpy().astype(np.float64)
+            assert not np.isnan(got_dk).any() and not np.isnan(got_dv).any()
+            dk_total[tk] += got_dk
+            dv_total[tk] += got_dv
+        assert_close(f"dQ summed over blocks, device {c}", dq.cpu().numpy().astype(np.float64), rdq[tq])
+    assert_close("dK summed over devices", dk_total, rdk)
+    assert_close("dV summed over devices", dv_total, rdv)
