@@ -154,7 +154,10 @@ hspmd_status hspmd_attn_schedule_ordered(hspmd_list_kind kind, hspmd_order order
  * Plan: the three device-resident work lists for one pack and one local head
  * configuration.  One plan serves every layer and both passes of a micro-batch.
  * Opaque, library-owned; destroy it with hspmd_attn_plan_destroy.  Creating a
- * plan needs a GPU; it synchronises `stream` before returning.
+ * plan needs a GPU: the lists are uploaded through a copy stream that the library owns (one per
+ * device, created on first use) and the call waits for that upload only, never for `stream` or any
+ * other work of the caller, so the plan of the next micro-batch can be built while the kernels of the
+ * current one run.  The lists are in place when the call returns (`stream` is accepted and unused).
  *   local_q_heads   query heads held by this GPU (any positive count: an uneven share is fine)
  *   local_kv_heads  KV heads held by this GPU; local_q_heads % local_kv_heads must be 0
  *   head_dim        a multiple of 8 in 8..128 (rows move in 16-byte chunks).  The kernels are built for

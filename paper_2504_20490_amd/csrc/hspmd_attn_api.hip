@@ -6,6 +6,8 @@
 #include <cstring>
 #include <limits>
 #include <new>
+#include <map>
+#include <mutex>
 #include <string>
 #include <vector>
 
@@ -67,6 +69,34 @@ hipError_t timed_launch(int kernel, hipStream_t stream, F&& launch) {
     if (e != hipSuccess) return e;
     g_records.push_back(r);
     return hipSuccess;
+}
+
+// Upload of a plan's work lists.  It goes through a copy stream of the library's own (one per device, created on
+// first use, default priority, not synchronising with the NULL stream) and waits for that stream only: the
+// caller's compute stream is never waited on, so building the plan of the next micro-batch overlaps the kernels
+// of the current one.  The copy has completed when this returns; kernels launched afterwards on any stream see it.
+std::mutex g_copy_stream_mutex;
+std::map<int, hipStream_t> g_copy_streams;
+
+hipError_t upload_blocking(void* dst, const void* src, size_t bytes) {
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    hipStream_t copy = nullptr;
+    {
+        std::lock_guard<std::mutex> lock(g_copy_stream_mutex);
+        auto it = g_copy_streams.find(dev);
+        if (it == g_copy_streams.end()) {
+            e = hipStreamCreateWithFlags(&copy, hipStreamNonBlocking);
+            if (e != hipSuccess) return e;
+            g_copy_streams[dev] = copy;
+        } else {
+            copy = it->second;
+        }
+    }
+    e = hipMemcpyAsync(dst, src, bytes, hipMemcpyHostToDevice, copy);
+    if (e == hipSuccess) e = hipStreamSynchronize(copy);
+    return e;
 }
 
 }  // namespace
@@ -185,16 +215,15 @@ hspmd_status hspmd_attn_plan_create_ordered(const int32_t* cu_seqlens_host, int3
         delete plan;
         return fail(HSPMD_ERR_INVALID_ARG, "out of host memory while building the work lists");
     }
+    (void)stream;   // kept in the signature; the upload uses the library's copy stream
     if (!all.empty()) {
-        hipStream_t s = static_cast<hipStream_t>(stream);
         const size_t bytes = all.size() * sizeof(hspmd_work_item);
         hipError_t e = hipMalloc(&plan->device_block, bytes);
         if (e != hipSuccess) {
             delete plan;
             return fail_hip(e, "hipMalloc(work lists)");
         }
-        e = hipMemcpyAsync(plan->device_block, all.data(), bytes, hipMemcpyHostToDevice, s);
-        if (e == hipSuccess) e = hipStreamSynchronize(s);   // `all` dies at the end of this scope
+        e = upload_blocking(plan->device_block, all.data(), bytes);   // `all` dies at the end of this scope
         if (e != hipSuccess) {
             hspmd_attn_plan_destroy(plan);
             return fail_hip(e, "hipMemcpyAsync(work lists)");
@@ -508,16 +537,15 @@ hspmd_status hspmd_attn_block_plan_create(const int32_t* cu_q_host, const int32_
         delete plan;
         return fail(HSPMD_ERR_INVALID_ARG, "out of host memory while building the work lists");
     }
+    (void)stream;   // kept in the signature; the upload uses the library's copy stream
     if (!all.empty()) {
-        hipStream_t s = static_cast<hipStream_t>(stream);
         const size_t bytes = all.size() * sizeof(hspmd_block_item);
         hipError_t e = hipMalloc(&plan->device_block, bytes);
         if (e != hipSuccess) {
             delete plan;
             return fail_hip(e, "hipMalloc(work lists)");
         }
-        e = hipMemcpyAsync(plan->device_block, all.data(), bytes, hipMemcpyHostToDevice, s);
-        if (e == hipSuccess) e = hipStreamSynchronize(s);
+        e = upload_blocking(plan->device_block, all.data(), bytes);
         if (e != hipSuccess) {
             hspmd_attn_plan_destroy(plan);
             return fail_hip(e, "hipMemcpyAsync(work lists)");
