@@ -177,11 +177,11 @@ std::vector<hspmd_work_item> build_work_list(hspmd_list_kind kind, const int32_t
 // ------------------------------------------------------------------------------ cost model
 // The paper's planner dispatches mixed-length sequences with a cost model evaluated on the CPU (Appendix
 // "Scenario-specific Planning", mixed-length case); this is the per-operator predictor for the attention
-// kernels of this library.  Fitted by relative least squares to 40 (head_dim 128) and 33 (head_dim 64) packs:
-// mean absolute error 5-8 % (128) and 8-12 % (64), at most 25-35 % on packs of a few hundred microseconds.
+// kernels of this library.  Fitted by relative least squares to 40 packs per head_dim: mean absolute error
+// 6-9 %, at most 15-29 % (on packs that take about a hundred microseconds).
 PassCost pass_cost_coefficients(hspmd_list_kind kind, int32_t head_dim) {
-    static const PassCost k128[3] = {{9.9, 1.937, 10.49}, {3.1, 2.366, 14.09}, {0.0, 1.694, 15.64}};
-    static const PassCost k64[3] = {{3.8, 1.195, 4.30}, {0.0, 1.376, 6.66}, {3.5, 1.137, 7.91}};
+    static const PassCost k128[3] = {{8.1, 1.910, 8.17}, {8.0, 2.353, 17.61}, {26.2, 1.653, 11.36}};
+    static const PassCost k64[3] = {{7.4, 1.190, 4.20}, {8.6, 1.312, 8.69}, {18.6, 1.024, 6.44}};
     return (head_dim == 64 ? k64 : k128)[(int)kind];
 }
 
