@@ -272,8 +272,8 @@ hspmd_status hspmd_attn_block_bwd_rope(const hspmd_attn_plan* plan, const void* 
  * item), a pass takes a launch time plus the weight of its heaviest XCD queue divided by the
  * workgroups resident per XCD, and not less than its heaviest item; backward = dQ pass + dK/dV
  * pass.  The coefficients are fitted to measured kernel times
- * (paper_2504_20490_amd/fit_cost_model.py refits them): mean error 5-8 % at head_dim 128, up to
- * 25-35 % on packs that take only a few hundred microseconds.  Host-side plan creation is not included.
+ * (paper_2504_20490_amd/fit_cost_model.py refits them): mean error 6-9 %, up to 15-29 % on packs
+ * that take only about a hundred microseconds.  Host-side plan creation is not included.
  */
 hspmd_status hspmd_attn_estimate_ms(const int32_t* cu_seqlens, int32_t num_seqs, int32_t local_q_heads,
                                     int32_t local_kv_heads, int32_t head_dim, double* fwd_ms, double* bwd_ms);
