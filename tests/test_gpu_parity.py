@@ -26,7 +26,7 @@ def _full_check(lengths, hq, hkv, d, seed, value_scale=1.0, grad_dtype=None, sca
     # hundreds of rows push |dK|, |dV| above 10; scaled inputs push |O| above 8, where half a bf16 ulp is 0.03) add the
     # bf16 rounding of P / dS / O at that magnitude to the max-abs bound
     # (slack_roundings: how many such roundings, P, dS and the bf16 operands among them, may line up in one element)
-    slack = (lambda ref: slack_roundings * 2.0 ** -9 * float(np.max(np.abs(ref)))) if magnitude_slack else (lambda ref: 0.0)
+    slack = (lambda ref: slack_roundings * 2.0 ** -9 * float(np.max(np.abs(ref))) if ref.size else 0.0) if magnitude_slack else (lambda ref: 0.0)
     assert_close("O", run.host("o"), ro, max_abs=gpu_util.MAX_ABS + slack(ro))
     assert np.max(np.abs(run.host("lse") - rlse)) <= LSE_ABS * max(1.0, float(np.max(np.abs(rlse))) / 8.0 if magnitude_slack else 1.0)
     assert_close("dQ", run.host("dq"), rdq, max_abs=gpu_util.MAX_ABS + slack(rdq))
