@@ -317,3 +317,51 @@ def test_emulated_ring_with_rotary_embedding(hq, hkv, d):
         assert_close(f"dQ summed over blocks, device {c}", dq.cpu().numpy().astype(np.float64), rdq[tq])
     assert_close("dK summed over devices", dk_total, rdk)
     assert_close("dV summed over devices", dv_total, rdv)
+
+
+def test_random_block_geometries_with_rotary_embedding():
+    """Twenty random single blocks (chunk lengths and positions, head dims 64 / 104 / 128, MHA and GQA): rotation of the
+    chunks by their positions inside the sequences, then the block backward with the transposed rotation, the block's
+    own (O, LSE) serving as the statistics of the rows."""
+    import paper_2504_20490_amd as A
+    from oracle import block as ob
+    from test_gpu_block import BlockRun
+    torch = _torch()
+    rng = np.random.default_rng(77)
+    for case in range(20):
+        n = int(rng.integers(1, 5))
+        ql = [int(x) for x in rng.integers(0, 330, n)]; kl = [int(x) for x in rng.integers(0, 330, n)]
+        qp = [int(x) for x in rng.integers(0, 400, n)]; kp = [int(x) for x in rng.integers(0, 400, n)]
+        if sum(ql) == 0:
+            ql[0] = 5
+        if sum(kl) == 0:
+            kl[0] = 7
+        d = int(rng.choice([64, 128, 104]))
+        hq, hkv = [(2, 2), (4, 2), (3, 1)][int(rng.integers(0, 3))]
+        gpu_util.CONTEXT["case"] = f"rope_block_random_{case}"
+        r = BlockRun(ql, kl, qp, kp, hq, hkv, d, 2000 + case)
+        positions = max(max(p + l for p, l in zip(qp, ql)), max(p + l for p, l in zip(kp, kl)))
+        table = _table(positions, d)
+        A.rope_qk(r.plan, r.q, r.k, r.q, r.k, table, positions)
+        torch.cuda.synchronize()
+        pos_q = np.concatenate([p + np.arange(l) for p, l in zip(qp, ql)]).astype(np.int64)
+        pos_k = np.concatenate([p + np.arange(l) for p, l in zip(kp, kl)]).astype(np.int64)
+        qb, kb = _bits(r.q), _bits(r.k)
+        _assert_rounded("rope(q chunks)", qb, orope.rope(f64(r.qb), pos_q, BASE))
+        _assert_rounded("rope(k chunks)", kb, orope.rope(f64(r.kb), pos_k, BASE))
+        A.attn_block_fwd(r.plan, r.q, r.k, r.v, r.o, r.lse)
+        torch.cuda.synchronize()
+        ro, rl = ob.block_fwd(f64(qb), f64(kb), f64(r.vb), *r.geom, r.s)
+        assert_close("O partial", r.host("o"), ro)
+        o_bits = w.bf16_bits(ro.astype(np.float32))
+        lse_dev = torch.from_numpy(rl.astype(np.float32)).cuda()
+        A.attn_block_bwd_rope(r.plan, r.q, r.k, r.v, to_dev(o_bits), lse_dev, r.do, r.dq, r.dk, r.dv, r.ws, table, positions)
+        torch.cuda.synchronize()
+        lse_ref = np.where(np.isneginf(rl), np.inf, lse_dev.cpu().numpy().astype(np.float64))
+        rdq, rdk, rdv = ob.block_bwd(f64(qb), f64(kb), f64(r.vb), f64(r.dob), lse_ref, ob.row_dot(f64(o_bits), f64(r.dob)),
+                                     *r.geom, r.s)
+        rdq, rdk = orope.rope_transposed(rdq, pos_q, BASE), orope.rope_transposed(rdk, pos_k, BASE)
+        slack = lambda ref: 2.0 ** -9 * float(np.max(np.abs(ref))) if ref.size else 0.0
+        assert_close("dQ share before rope", r.host("dq"), rdq, max_abs=gpu_util.MAX_ABS + slack(rdq))
+        assert_close("dK block before rope", r.host("dk"), rdk, max_abs=gpu_util.MAX_ABS + slack(rdk))
+        assert_close("dV block", r.host("dv"), rdv, max_abs=gpu_util.MAX_ABS + slack(rdv))
