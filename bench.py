@@ -249,6 +249,9 @@ def main() -> int:
                     help="N > 0: measure the block variant instead: one rank of a context-parallel ring of N chunks "
                          "(see run_ring); the default 0 measures the packed path")
     ap.add_argument("--ring-rank", type=int, default=-1, help="which chunk the rank owns (default: the last, heaviest)")
+    ap.add_argument("--inputs", default="workload", choices=["workload", "zeros"],
+                    help="zeros: all-zero q, k, v, dO (same instruction stream, almost no switching activity): shows how "
+                         "much of the kernel time is the power-limited clock.  A side measurement, not a benchmark result")
     ap.add_argument("--rope", action="store_true",
                     help="add rotary embedding to the step: q, k rotated by the elementwise kernel before the forward, "
                          "dQ and dK turned back inside the backward epilogues (side measurement)")
@@ -281,6 +284,9 @@ def main() -> int:
         return torch.from_numpy(bits.view(np.int16)).view(torch.bfloat16).to(dev)
 
     tq, tk, tv, tdo = bf(q), bf(k), bf(v), bf(do)
+    if args.inputs == "zeros":
+        for t in (tq, tk, tv, tdo):
+            t.zero_()
     o = torch.empty_like(tq)
     lse = torch.empty(hq, T, dtype=torch.float32, device=dev)
     grad = A.GRAD_F32 if args.grad_dtype == "f32" else A.GRAD_BF16
@@ -395,6 +401,9 @@ def main() -> int:
                      "note": f"{GEMMS[dominant]} GEMMs over the visible pairs; avg of {prof[dominant][1]} launches "
                              "timed with HIP events on the launch stream"},
     }
+    if args.inputs == "zeros":
+        out["metric"] = "varlen causal attn fwd+bwd on ALL-ZERO inputs (clock-dependence probe, not a benchmark result)"
+        out["data"] = "zeros"
     if args.rope:
         # the rotation kernel is an HBM stream: q and k read once and written once
         rope_bytes = 2.0 * 2.0 * T * (hq + hkv) * d
