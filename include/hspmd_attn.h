@@ -366,6 +366,9 @@ hspmd_status hspmd_attn_block_bwd(const hspmd_attn_plan* plan, const void* q, co
 #define HSPMD_NUM_KERNELS 5
 hspmd_status hspmd_profile_enable(int32_t on);
 hspmd_status hspmd_profile_read(double* ms, int64_t* launches);
+/* The same records as per-kernel statistics: sum, number of launches, minimum and median of the launches' elapsed
+ * times (all four arrays host, [HSPMD_NUM_KERNELS], overwritten; 0 for a kernel without launches). */
+hspmd_status hspmd_profile_read_stats(double* sum_ms, int64_t* launches, double* min_ms, double* median_ms);
 const char* hspmd_kernel_name(int32_t kernel);   /* symbol-like name, NULL if out of range */
 
 /*

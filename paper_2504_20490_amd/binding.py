@@ -132,6 +132,9 @@ def load_library():
     lib.hspmd_probe_mfma_tflops_varied.argtypes = lib.hspmd_probe_mfma_tflops.argtypes
     lib.hspmd_profile_read.restype = ctypes.c_int
     lib.hspmd_profile_read.argtypes = [ctypes.POINTER(ctypes.c_double), i64p]
+    lib.hspmd_profile_read_stats.restype = ctypes.c_int
+    lib.hspmd_profile_read_stats.argtypes = [ctypes.POINTER(ctypes.c_double), i64p, ctypes.POINTER(ctypes.c_double),
+                                             ctypes.POINTER(ctypes.c_double)]
     lib.hspmd_kernel_name.restype = ctypes.c_char_p
     lib.hspmd_kernel_name.argtypes = [ctypes.c_int32]
     _lib = lib
@@ -309,6 +312,18 @@ def profile_read():
     n = (ctypes.c_int64 * NUM_KERNELS)()
     _check(lib.hspmd_profile_read(ms, n))
     return {lib.hspmd_kernel_name(i).decode(): (float(ms[i]), int(n[i])) for i in range(NUM_KERNELS) if n[i] > 0}
+
+
+def profile_read_stats():
+    """Returns {kernel name: {"mean", "min", "median" (ms per launch), "launches"}} for the kernels launched since the
+    last read."""
+    lib = load_library()
+    total, mn, med = ((ctypes.c_double * NUM_KERNELS)() for _ in range(3))
+    n = (ctypes.c_int64 * NUM_KERNELS)()
+    _check(lib.hspmd_profile_read_stats(total, n, mn, med))
+    return {lib.hspmd_kernel_name(i).decode(): {"mean": float(total[i]) / int(n[i]), "min": float(mn[i]),
+                                                "median": float(med[i]), "launches": int(n[i])}
+            for i in range(NUM_KERNELS) if n[i] > 0}
 
 
 def probe_scratch_bytes() -> int:

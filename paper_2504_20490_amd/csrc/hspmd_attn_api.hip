@@ -1,6 +1,7 @@
 // C-ABI entry points of libhspmd_attn: argument validation, plan management, launches.
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
 #include <cmath>
 #include <cstdio>
 #include <cstring>
@@ -97,6 +98,23 @@ hipError_t upload_blocking(void* dst, const void* src, size_t bytes) {
     e = hipMemcpyAsync(dst, src, bytes, hipMemcpyHostToDevice, copy);
     if (e == hipSuccess) e = hipStreamSynchronize(copy);
     return e;
+}
+
+// waits for the recorded events, hands every launch's elapsed time to `sink(kernel, ms)` and forgets the records
+template <typename Sink>
+hspmd_status drain_profile_records(Sink&& sink) {
+    hspmd_status rc = HSPMD_OK;
+    for (const ProfileRecord& r : g_records) {
+        hipError_t e = hipEventSynchronize(r.stop);
+        float t = 0.f;
+        if (e == hipSuccess) e = hipEventElapsedTime(&t, r.start, r.stop);
+        if (e == hipSuccess) sink(r.kernel, (double)t);
+        else rc = fail_hip(e, "profile read");
+        g_event_pool.push_back(r.start);
+        g_event_pool.push_back(r.stop);
+    }
+    g_records.clear();
+    return rc;
 }
 
 }  // namespace
@@ -706,21 +724,27 @@ hspmd_status hspmd_profile_enable(int32_t on) {
 
 hspmd_status hspmd_profile_read(double* ms, int64_t* launches) {
     if (!ms || !launches) return fail(HSPMD_ERR_INVALID_ARG, "null pointer");
-    hspmd_status rc = HSPMD_OK;
-    for (const ProfileRecord& r : g_records) {
-        hipError_t e = hipEventSynchronize(r.stop);
-        float t = 0.f;
-        if (e == hipSuccess) e = hipEventElapsedTime(&t, r.start, r.stop);
-        if (e == hipSuccess) {
-            ms[r.kernel] += (double)t;
-            launches[r.kernel] += 1;
-        } else {
-            rc = fail_hip(e, "profile read");
-        }
-        g_event_pool.push_back(r.start);
-        g_event_pool.push_back(r.stop);
+    return drain_profile_records([&](int kernel, double t) {
+        ms[kernel] += t;
+        launches[kernel] += 1;
+    });
+}
+
+hspmd_status hspmd_profile_read_stats(double* sum_ms, int64_t* launches, double* min_ms, double* median_ms) {
+    if (!sum_ms || !launches || !min_ms || !median_ms) return fail(HSPMD_ERR_INVALID_ARG, "null pointer");
+    std::vector<double> samples[HSPMD_NUM_KERNELS];
+    const hspmd_status rc = drain_profile_records([&](int kernel, double t) { samples[kernel].push_back(t); });
+    for (int k = 0; k < HSPMD_NUM_KERNELS; ++k) {
+        std::vector<double>& v = samples[k];
+        sum_ms[k] = 0.0;
+        launches[k] = (int64_t)v.size();
+        min_ms[k] = median_ms[k] = 0.0;
+        if (v.empty()) continue;
+        std::sort(v.begin(), v.end());
+        for (double t : v) sum_ms[k] += t;
+        min_ms[k] = v.front();
+        median_ms[k] = v.size() % 2 ? v[v.size() / 2] : 0.5 * (v[v.size() / 2 - 1] + v[v.size() / 2]);
     }
-    g_records.clear();
     return rc;
 }
 
