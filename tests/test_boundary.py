@@ -270,3 +270,12 @@ def test_forward_and_dq_lists_are_the_same_list():
         assert np.array_equal(A.schedule(A.LIST_FWD, cu, 6, 2, order=order), A.schedule(A.LIST_DQ, cu, 6, 2, order=order))
     assert np.array_equal(A.block_schedule(A.LIST_FWD, cu, cu[::-1].cumsum() * 0 + cu, [5, 0, 100, 0, 7], [0, 0, 0, 9, 7], 6, 2),
                           A.block_schedule(A.LIST_DQ, cu, cu, [5, 0, 100, 0, 7], [0, 0, 0, 9, 7], 6, 2))
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """bench.py measures one GPU's share on one GPU; asked for more it exits with a message and no JSON line."""
+    import subprocess
+    import sys
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True, timeout=120)
+    assert r.returncode != 0
+    assert "one GPU" in r.stderr and r.stdout.strip() == ""
