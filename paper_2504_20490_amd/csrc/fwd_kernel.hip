@@ -115,6 +115,9 @@ __device__ __forceinline__ void fwd_iteration(FwdState<D>& st, const char* kbuf,
     st.m = m_new;
     __builtin_amdgcn_sched_barrier(0);
 
+    // The two waves of a SIMD (one of each resident workgroup) compete for its issue slots: the one that is in its
+    // MFMA phases goes first, so that the matrix pipe does not wait behind the other's VALU-only stretch.
+    __builtin_amdgcn_s_setprio(1);
     // ---------------- phase A: S^T(kt+1) on the MFMA, exp2 / row sum / bf16 pack of tile kt on the VALU.
     // Written out step by step with a scheduling barrier after each: step n issues the K fragment read of
     // MFMA n + kAheadK, MFMA n, and the softmax work on two scores.
@@ -192,6 +195,7 @@ __device__ __forceinline__ void fwd_iteration(FwdState<D>& st, const char* kbuf,
             __builtin_amdgcn_sched_barrier(0);
         }
     }
+    __builtin_amdgcn_s_setprio(0);
     st.l = st.l * alpha + psum;
     if constexpr (!LAST) {
         st.s[0] = sn[0];
