@@ -102,7 +102,13 @@ __device__ __forceinline__ void fwd_iteration(FwdState<D>& st, const char* kbuf,
 #pragma unroll
         for (int i = (jb == 0 ? 2 : 0); i < 16; ++i) tmax = fmaxf(tmax, st.s[jb][i]);
     tmax = pair_max(tmax);
-    const float m_new = fmaxf(st.m, tmax);
+    // st.m is the reference that the exponentials are taken against, not the exact running maximum: it moves only
+    // when the maximum has risen by more than kMaxSlack in the exponent (base-2) domain.  Weights then lie in
+    // (0, 2^kMaxSlack] instead of (0, 1] -- the same relative precision in bf16 and fp32, and O and LSE do not depend on
+    // the reference -- while the accumulator rescale, which a moving maximum of ANY of the wave's 32 rows triggers,
+    // becomes rare after the first tiles.  (-inf - -inf = NaN compares false: a row without a visible key keeps -inf.)
+    constexpr float kMaxSlack = 8.f;
+    const float m_new = (tmax - st.m) * c > kMaxSlack ? tmax : st.m;
     const float m_ref = (BLOCK && m_new == -INFINITY) ? 0.f : m_new;
     const float alpha = fast_exp2((st.m - m_ref) * c);
     const float mc = m_ref * c;
