@@ -146,6 +146,9 @@ __global__ __launch_bounds__(kThreads, 2) void bwd_dq_kernel(BwdParams p) {
     for (int db = 0; db < DB; ++db)
 #pragma unroll
         for (int i = 0; i < 16; ++i) acc[db][i] = 0.f;
+    f32x16 negd_frag;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) negd_frag[i] = negd;
 
     // per-lane LDS offsets of the operand fragments inside a tile
     int rm[KK], tr[DB][2];
@@ -185,9 +188,11 @@ __global__ __launch_bounds__(kThreads, 2) void bwd_dq_kernel(BwdParams p) {
             u.s.b = lds_transpose_read(ktile + tr[n % DB][1] + off);
             return u.v;
         };
-        f32x16 sacc, dp;
+        // dP^T starts from -D (a fragment that holds the lane's -D in every element, kept for the whole item): the
+        // matrix core then delivers dP^T - D and the VALU step needs no subtraction
+        f32x16 sacc, dp = negd_frag;
 #pragma unroll
-        for (int i = 0; i < 16; ++i) { sacc[i] = 0.f; dp[i] = 0.f; }
+        for (int i = 0; i < 16; ++i) sacc[i] = 0.f;
         bf16x8 q1[kAhead + 1];
 #pragma unroll
         for (int n = 0; n < kAhead; ++n) q1[n] = frag1(n);
@@ -208,7 +213,7 @@ __global__ __launch_bounds__(kThreads, 2) void bwd_dq_kernel(BwdParams p) {
         for (int i = 0; i < 16; ++i) {
             float pr = fast_exp2(fmaf(sacc[i], c, nlse2));
             if (kMask && kb + acc_row(i, lane) > my_limit) pr = 0.f;
-            sacc[i] = pr * (dp[i] + negd);   // dS^T
+            sacc[i] = pr * dp[i];   // dS^T = P (dP^T - D)
         }
         const bf16x8 dsf[2] = {frag_to_bf16(sacc, 0), frag_to_bf16(sacc, 1)};
         __builtin_amdgcn_sched_barrier(0);
