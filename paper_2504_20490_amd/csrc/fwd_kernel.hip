@@ -327,7 +327,10 @@ __global__ __launch_bounds__(kThreads, 2) void fwd_kernel(FwdParams p) {
     };
     // the same for an unmasked tile whose successors kt+1 and kt+2 are whole tiles: their copies need no case
     // distinction and are issued from inside the iteration
-    auto step_spread = [&](int kt) {
+    // `parity` = kt & 1, as a run-time value or as a std::integral_constant: with a constant the LDS buffers of the
+    // iteration are compile-time offsets and the operand reads need no address arithmetic
+    auto step_spread = [&](int kt, auto parity) {
+        const int par = parity;
         if (kt > 0) {
             wait_tile_loads();
             __syncthreads();
@@ -336,10 +339,10 @@ __global__ __launch_bounds__(kThreads, 2) void fwd_kernel(FwdParams p) {
         load.copy = &kvcopy;
         load.k_row = kbase + (int64_t)(kt + 2) * BK * p.kv_stride;
         load.v_row = vbase + (int64_t)(kt + 1) * BK * p.kv_stride;
-        load.k_dst = kdst0 + (kt & 1) * kTileBytes;
-        load.v_dst = vdst0 + ((kt + 1) & 1) * kTileBytes;
+        load.k_dst = kdst0 + par * kTileBytes;
+        load.v_dst = vdst0 + (1 - par) * kTileBytes;
         load.wave = wave;
-        fwd_iteration<D, false, false, true, BLOCK>(st, kbuf0 + ((kt + 1) & 1) * kTileBytes, vbuf0 + (kt & 1) * kTileBytes, c,
+        fwd_iteration<D, false, false, true, BLOCK>(st, kbuf0 + (1 - par) * kTileBytes, vbuf0 + par * kTileBytes, c,
                                                     my_limit - kt * BK - 4 * hh, load);
     };
     // a tile past this wave's own diagonal: the barrier and the wave's share of the copies, nothing else
@@ -358,7 +361,12 @@ __global__ __launch_bounds__(kThreads, 2) void fwd_kernel(FwdParams p) {
     const int n_plain = min(n_interior_w, n_tiles_w - 1);
     const int n_spread = max(0, min(n_plain, L / BK - 2));   // tile kt+2 exists and is whole
     int kt = 0;
-    for (; kt < n_spread; ++kt) step_spread(kt);
+    // the long loop of a long sequence runs in pairs (even tile, odd tile) with constant buffer offsets
+    for (; kt + 1 < n_spread; kt += 2) {
+        step_spread(kt, std::integral_constant<int, 0>{});
+        step_spread(kt + 1, std::integral_constant<int, 1>{});
+    }
+    for (; kt < n_spread; ++kt) step_spread(kt, kt & 1);
     for (; kt < n_plain; ++kt) step(kt, std::false_type{}, std::false_type{});
     for (; kt < n_tiles_w - 1; ++kt) step(kt, std::true_type{}, std::false_type{});
     if (n_tiles_w > 0) {
