@@ -247,12 +247,15 @@ __global__ __launch_bounds__(kThreads, 2) void bwd_dq_kernel(BwdParams p) {
     };
     // An unmasked tile whose successor is a whole tile: the successor's copies are issued from inside the blocks,
     // one instruction at a time (all waves' copies issued together queue up in front of the CU's address unit).
-    auto step_spread = [&](int kt) {
+    // `parity` = kt & 1, as a run-time value or as a std::integral_constant: with a constant the stage of the tile
+    // is a compile-time offset and the operand reads need no address arithmetic
+    auto step_spread = [&](int kt, auto parity) {
+        const int par = parity;
         wait_tile_loads();
         __syncthreads();
-        const char* ktile = lds + (kt & 1) * (2 * kTileBytes);
+        const char* ktile = lds + par * (2 * kTileBytes);
         const char* vtile = ktile + kTileBytes;
-        const uint32_t next = lds0 + ((kt + 1) & 1) * (2 * kTileBytes);
+        const uint32_t next = lds0 + (1 - par) * (2 * kTileBytes);
         const uint16_t* k_row = kbase + (int64_t)(kt + 1) * BK * p.kv_stride;
         const uint16_t* v_row = vbase + (int64_t)(kt + 1) * BK * p.kv_stride;
         auto piece = [&](int jb, int i) {
@@ -269,7 +272,12 @@ __global__ __launch_bounds__(kThreads, 2) void bwd_dq_kernel(BwdParams p) {
     const int n_interior = BLOCK ? max(0, min(min(n_tiles, (q_row0 + off + 1) / BK), L / BK)) : min(n_tiles, 2 * item.tile);
     const int n_spread = max(0, min(min(n_interior, n_tiles - 1), L / BK - 1));
     int kt = 0;
-    for (; kt < n_spread; ++kt) step_spread(kt);
+    // the long loop of a long sequence runs in pairs (even tile, odd tile) with constant stage offsets
+    for (; kt + 1 < n_spread; kt += 2) {
+        step_spread(kt, std::integral_constant<int, 0>{});
+        step_spread(kt + 1, std::integral_constant<int, 1>{});
+    }
+    for (; kt < n_spread; ++kt) step_spread(kt, kt & 1);
     for (; kt < n_interior; ++kt) step(kt, std::false_type{});
     for (; kt < n_tiles; ++kt) step(kt, std::true_type{});
 
