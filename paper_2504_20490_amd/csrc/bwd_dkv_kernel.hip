@@ -181,10 +181,12 @@ __device__ __forceinline__ void dkv_iteration(DkvState<D>& st, const char* lds, 
             }
         }
     // G1(i+1) on top of the statistics
+    // the two accumulation chains alternate: an MFMA that continues a chain does not follow its predecessor directly
 #pragma unroll
-    for (int kk = 0; kk < KK; ++kk) st.s[NRB] = mfma(st.qf[kk], st.kf[kk], st.s[NRB]);
-#pragma unroll
-    for (int kk = 0; kk < KK; ++kk) st.dp[NRB] = mfma(st.dof[kk], st.vf[kk], st.dp[NRB]);
+    for (int kk = 0; kk < KK; ++kk) {
+        st.s[NRB] = mfma(st.qf[kk], st.kf[kk], st.s[NRB]);
+        st.dp[NRB] = mfma(st.dof[kk], st.vf[kk], st.dp[NRB]);
+    }
     u32x4 pw1, dw1;
     softmax_half(1, pw1, dw1);
     cv.u = pw1; st.pprev[1] = cv.v;
