@@ -260,9 +260,12 @@ __device__ __forceinline__ void store_grad4(void* base, int64_t elem, bool f32, 
 // wave, and LDS accesses of one wave complete in order, so no barrier is needed between its writes and reads.
 //   valid_rows: rows 0 .. valid_rows-1 exist; head_dim: columns that exist in memory (<= D, a multiple of 8)
 //   ACCUM: add to what the destination holds (fp32 only)
-template <int D, bool ACCUM>
-__device__ __forceinline__ void store_tile_f32(char* wave_lds, const f32x16 (&acc)[D / 32], float mul, float* first_row,
-                                               int64_t row_stride, int valid_rows, int head_dim, int lane) {
+// FULL: all 32 rows and all D columns exist (decided per wave by the callers below).  Without the per-row test the
+// second loop is straight-line code: the LDS reads are issued together and the stores follow as the data arrives,
+// instead of one LDS round trip per store.
+template <int D, bool ACCUM, bool FULL>
+__device__ __forceinline__ void store_tile_f32_rows(char* wave_lds, const f32x16 (&acc)[D / 32], float mul, float* first_row,
+                                                    int64_t row_stride, int valid_rows, int head_dim, int lane) {
     constexpr int kChunks = D / 4;                // 16-byte chunks per row
     const int r = lane & 31, hh = lane >> 5;
 #pragma unroll
@@ -274,12 +277,14 @@ __device__ __forceinline__ void store_tile_f32(char* wave_lds, const f32x16 (&ac
                 f32x4{acc[db][4 * i4 + 0] * mul, acc[db][4 * i4 + 1] * mul, acc[db][4 * i4 + 2] * mul, acc[db][4 * i4 + 3] * mul};
         }
     constexpr int kRowsPerInstr = 64 / kChunks;
+    const int chunk = lane % kChunks;
+    float* const lane_dst = first_row + (lane / kChunks) * row_stride + chunk * 4;   // this lane's piece of rows 0 .. kRowsPerInstr-1
 #pragma unroll
     for (int it = 0; it < 32 / kRowsPerInstr; ++it) {
-        const int row = it * kRowsPerInstr + lane / kChunks, chunk = lane % kChunks;
-        if (row < valid_rows && chunk * 4 < head_dim) {
+        const int row = it * kRowsPerInstr + lane / kChunks;
+        if (FULL || (row < valid_rows && chunk * 4 < head_dim)) {
             f32x4 v = *reinterpret_cast<const f32x4*>(wave_lds + (row * kChunks + (chunk ^ (row & (kChunks - 1)))) * 16);
-            f32x4* dst = reinterpret_cast<f32x4*>(first_row + row * row_stride + chunk * 4);
+            f32x4* dst = reinterpret_cast<f32x4*>(lane_dst + it * kRowsPerInstr * row_stride);
             if constexpr (ACCUM) {
                 const f32x4 old = *dst;
 #pragma unroll
@@ -290,10 +295,19 @@ __device__ __forceinline__ void store_tile_f32(char* wave_lds, const f32x16 (&ac
     }
 }
 
+template <int D, bool ACCUM>
+__device__ __forceinline__ void store_tile_f32(char* wave_lds, const f32x16 (&acc)[D / 32], float mul, float* first_row,
+                                               int64_t row_stride, int valid_rows, int head_dim, int lane) {
+    if (valid_rows >= 32 && head_dim == D)
+        store_tile_f32_rows<D, ACCUM, true>(wave_lds, acc, mul, first_row, row_stride, valid_rows, head_dim, lane);
+    else
+        store_tile_f32_rows<D, ACCUM, false>(wave_lds, acc, mul, first_row, row_stride, valid_rows, head_dim, lane);
+}
+
 // The same for a bf16 destination: rows of D bf16 in LDS (8-byte pieces in, 16-byte chunks out).
-template <int D>
-__device__ __forceinline__ void store_tile_bf16(char* wave_lds, const f32x16 (&acc)[D / 32], float mul, uint16_t* first_row,
-                                                int64_t row_stride, int valid_rows, int head_dim, int lane) {
+template <int D, bool FULL>
+__device__ __forceinline__ void store_tile_bf16_rows(char* wave_lds, const f32x16 (&acc)[D / 32], float mul, uint16_t* first_row,
+                                                     int64_t row_stride, int valid_rows, int head_dim, int lane) {
     constexpr int kChunks = D / 8;                // 16-byte chunks (8 bf16) per row
     const int r = lane & 31, hh = lane >> 5;
 #pragma unroll
@@ -307,13 +321,24 @@ __device__ __forceinline__ void store_tile_bf16(char* wave_lds, const f32x16 (&a
             *reinterpret_cast<u32x2*>(wave_lds + (r * kChunks + ((col / 8) ^ (r & (kChunks - 1)))) * 16 + (col & 4) * 2) = w;
         }
     constexpr int kRowsPerInstr = 64 / kChunks;
+    const int chunk = lane % kChunks;
+    uint16_t* const lane_dst = first_row + (lane / kChunks) * row_stride + chunk * 8;
 #pragma unroll
     for (int it = 0; it < 32 / kRowsPerInstr; ++it) {
-        const int row = it * kRowsPerInstr + lane / kChunks, chunk = lane % kChunks;
-        if (row < valid_rows && chunk * 8 < head_dim)
-            *reinterpret_cast<u32x4*>(first_row + row * row_stride + chunk * 8) =
+        const int row = it * kRowsPerInstr + lane / kChunks;
+        if (FULL || (row < valid_rows && chunk * 8 < head_dim))
+            *reinterpret_cast<u32x4*>(lane_dst + it * kRowsPerInstr * row_stride) =
                 *reinterpret_cast<const u32x4*>(wave_lds + (row * kChunks + (chunk ^ (row & (kChunks - 1)))) * 16);
     }
+}
+
+template <int D>
+__device__ __forceinline__ void store_tile_bf16(char* wave_lds, const f32x16 (&acc)[D / 32], float mul, uint16_t* first_row,
+                                                int64_t row_stride, int valid_rows, int head_dim, int lane) {
+    if (valid_rows >= 32 && head_dim == D)
+        store_tile_bf16_rows<D, true>(wave_lds, acc, mul, first_row, row_stride, valid_rows, head_dim, lane);
+    else
+        store_tile_bf16_rows<D, false>(wave_lds, acc, mul, first_row, row_stride, valid_rows, head_dim, lane);
 }
 
 // The same with the transposed rotary-embedding rotation applied on the way out (the gradient with respect to the
@@ -327,10 +352,11 @@ __device__ __forceinline__ void store_tile_bf16(char* wave_lds, const f32x16 (&a
 // (the 32 rows are consecutive positions).
 //   ACCUM: add to what the destination holds (fp32 only; the rotation is linear, so a sum of rotated shares is the
 //   rotated sum)
-template <int D, bool ACCUM = false>
-__device__ __forceinline__ void store_tile_rope_transposed(char* wave_lds, const f32x16 (&acc)[D / 32], float mul, void* base,
-                                                           int64_t first_elem, bool f32, int64_t row_stride, int valid_rows,
-                                                           int head_dim, const float* table_row0, int lane) {
+//   FULL: all 32 rows and all D columns exist (straight-line code, see store_tile_f32_rows)
+template <int D, bool ACCUM, bool FULL>
+__device__ __forceinline__ void store_tile_rope_transposed_rows(char* wave_lds, const f32x16 (&acc)[D / 32], float mul, void* base,
+                                                                int64_t first_elem, bool f32, int64_t row_stride, int valid_rows,
+                                                                int head_dim, const float* table_row0, int lane) {
     constexpr int kChunks = D / 4;             // 16-byte chunks per staged row
     constexpr int kPairs = D / 8;              // lanes per row: lane c owns chunk c of the low half and its partner
     constexpr int kRowsPerInstr = 64 / kPairs;
@@ -342,7 +368,7 @@ __device__ __forceinline__ void store_tile_rope_transposed(char* wave_lds, const
 #pragma unroll
     for (int it = 0; it < kIters; ++it) {
         const int row = it * kRowsPerInstr + sub_row;
-        if (row < valid_rows && c < half_chunks) {
+        if (FULL || (row < valid_rows && c < half_chunks)) {
             const float* t = table_row0 + ((int64_t)row * (head_dim / 2) + c * 4) * 2;
             t01[it] = *reinterpret_cast<const f32x4*>(t);
             t23[it] = *reinterpret_cast<const f32x4*>(t + 4);
@@ -360,7 +386,7 @@ __device__ __forceinline__ void store_tile_rope_transposed(char* wave_lds, const
 #pragma unroll
     for (int it = 0; it < kIters; ++it) {
         const int row = it * kRowsPerInstr + sub_row;
-        if (row < valid_rows && c < half_chunks) {
+        if (FULL || (row < valid_rows && c < half_chunks)) {
             const int sw = row & (kChunks - 1);
             const f32x4 lo = *reinterpret_cast<const f32x4*>(wave_lds + (row * kChunks + (c ^ sw)) * 16);
             const f32x4 hi = *reinterpret_cast<const f32x4*>(wave_lds + (row * kChunks + ((c + half_chunks) ^ sw)) * 16);
@@ -384,6 +410,18 @@ __device__ __forceinline__ void store_tile_rope_transposed(char* wave_lds, const
             store_grad4(base, e + head_dim / 2, f32, x_hi[0], x_hi[1], x_hi[2], x_hi[3]);
         }
     }
+}
+
+template <int D, bool ACCUM = false>
+__device__ __forceinline__ void store_tile_rope_transposed(char* wave_lds, const f32x16 (&acc)[D / 32], float mul, void* base,
+                                                           int64_t first_elem, bool f32, int64_t row_stride, int valid_rows,
+                                                           int head_dim, const float* table_row0, int lane) {
+    if (valid_rows >= 32 && head_dim == D)
+        store_tile_rope_transposed_rows<D, ACCUM, true>(wave_lds, acc, mul, base, first_elem, f32, row_stride, valid_rows, head_dim,
+                                                        table_row0, lane);
+    else
+        store_tile_rope_transposed_rows<D, ACCUM, false>(wave_lds, acc, mul, base, first_elem, f32, row_stride, valid_rows, head_dim,
+                                                         table_row0, lane);
 }
 
 // Scheduling hint for one basic block: N times {1 MFMA, DS LDS reads, VA VALU instructions}, in that
