@@ -135,6 +135,10 @@ __device__ __forceinline__ void fwd_iteration(FwdState<D>& st, const char* kbuf,
         const float e0 = fast_exp2(fmaf(st.s[jb][i], c, -mc));
         const float e1 = fast_exp2(fmaf(st.s[jb][i + 1], c, -mc));
         psum += e0 + e1;
+        // the sum is needed only at the end of the iteration, and left alone the compiler keeps all 32 weights in
+        // registers and adds them up there, in one stretch of 32 VALU instructions with no MFMA to run under;
+        // an (empty) statement that reads and writes the sum keeps each pair's two additions in this step
+        asm volatile("" : "+v"(psum));
         pw[jb * 2 + (i >> 3)].u[(i >> 1) & 3] = pack_bf16(e0, e1);
     };
     if constexpr (!LAST) {
