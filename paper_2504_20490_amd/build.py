@@ -23,21 +23,42 @@ def _stale() -> bool:
     return any(os.path.getmtime(d) > built for d in deps)
 
 
+# Per-source flags (none at present; every source is compiled on its own, in parallel, and the objects are linked).
+EXTRA_FLAGS: dict = {}
+BUILD_DIR = os.path.join(HERE, "_build")
+
+
+def _compile(hipcc: str, source: str) -> tuple:
+    path = os.path.join(CSRC, source)
+    obj = os.path.join(BUILD_DIR, os.path.splitext(source)[0] + ".o")
+    cmd = [hipcc, *HIPCC_FLAGS, *EXTRA_FLAGS.get(source, []), "-c", "-o", obj]
+    cmd += (["-x", "hip", path] if source.endswith(".cpp") else [path])
+    proc = subprocess.run(cmd, capture_output=True, text=True)
+    return obj, proc.returncode, proc.stderr
+
+
 def build(force: bool = True, verbose: bool = False) -> str:
     if not force and not _stale():
         return LIBRARY
+    from concurrent.futures import ThreadPoolExecutor
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    cmd = [hipcc, *HIPCC_FLAGS, "-shared", "-o", LIBRARY]
-    for s in SOURCES:
-        path = os.path.join(CSRC, s)
-        cmd += (["-x", "hip", path] if s.endswith(".cpp") else [path])
-    proc = subprocess.run(cmd, capture_output=True, text=True)
+    os.makedirs(BUILD_DIR, exist_ok=True)
     noise = "is not a recognized feature for this target"
-    err = "\n".join(l for l in proc.stderr.splitlines() if noise not in l)
+    with ThreadPoolExecutor(max_workers=min(8, len(SOURCES))) as pool:
+        results = list(pool.map(lambda s: _compile(hipcc, s), SOURCES))
+    errors = []
+    for (obj, rc, stderr), source in zip(results, SOURCES):
+        err = "\n".join(l for l in stderr.splitlines() if noise not in l)
+        if rc != 0:
+            raise RuntimeError(f"hipcc failed on {source}:\n" + err)
+        if err.strip():
+            errors.append(err)
+    proc = subprocess.run([hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIBRARY, *[r[0] for r in results]],
+                          capture_output=True, text=True)
     if proc.returncode != 0:
-        raise RuntimeError("hipcc failed:\n" + err)
-    if verbose and err.strip():
-        print(err)
+        raise RuntimeError("link failed:\n" + proc.stderr)
+    if verbose and errors:
+        print("\n".join(errors))
     return LIBRARY
 
 
