@@ -41,6 +41,10 @@
  *     and nothing aborts.  Arguments are validated on the host before any
  *     launch.  hspmd_last_error() returns a thread-local description of the
  *     last failure on the calling thread.
+ *   - Threads: every entry point except the per-kernel timing calls may be used by several host
+ *     threads at once, on plans, streams and workspaces of their own; a plan may be shared by
+ *     threads that only launch with it.  Two launches that share a workspace must be ordered
+ *     (same stream, or an event between them).
  *   - bf16 tensors are raw 16-bit bfloat16 values.
  */
 #ifndef HSPMD_ATTN_H
