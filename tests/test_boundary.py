@@ -94,6 +94,44 @@ def test_work_list_invariants(name, kind):
             assert np.all(tiles[pad[0]:] < 0)
 
 
+def test_work_list_invariants_on_random_packs():
+    """The same invariants on packs nobody chose: lengths from 0 up, any number of queues, MHA and GQA."""
+    from hypothesis import given, settings, strategies as st
+
+    @settings(max_examples=60, deadline=None)
+    @given(lengths=st.lists(st.one_of(st.integers(0, 300), st.integers(0, 5000)), min_size=0, max_size=12),
+           hkv=st.integers(1, 4), group=st.sampled_from([1, 2, 4]), queues=st.sampled_from([1, 3, 8]),
+           kind=st.sampled_from([A.LIST_FWD, A.LIST_DKV]))
+    def check(lengths, hkv, group, queues, kind):
+        hq = hkv * group
+        cu, _, _ = A.build_cu_seqlens(lengths)
+        items = A.schedule(kind, cu, hq, hkv, queues)
+        assert items.shape[0] % queues == 0
+        real = items[items[:, 2] >= 0]
+        rows = A.tile_rows(kind)
+        heads = hkv if kind == A.LIST_DKV else hq
+        want = {(int(cu[s]), L, t, h) for s, L in enumerate(lengths) for t in range(-(-L // rows)) for h in range(heads)}
+        got = [tuple(int(x) for x in r) for r in real]
+        assert len(got) == len(want) and set(got) == want
+        if not got:
+            return
+        loads = np.zeros(queues)
+        for p, r in enumerate(items):
+            if r[2] >= 0:
+                loads[p % queues] += max(1, _cost(kind, int(r[1]), int(r[2]), group))
+        costs = [max(1, _cost(kind, int(r[1]), int(r[2]), group)) for r in real]
+        # longest-processing-time placement of segments no heavier than total / (4 queues) (or one item, if heavier)
+        cap = max(max(costs), sum(costs) // (4 * queues) + 1)
+        assert loads.max() - loads.min() <= cap, (loads, cap)
+        for x in range(queues):
+            tiles = items[x::queues, 2]
+            pad = np.flatnonzero(tiles < 0)
+            if pad.size:
+                assert np.all(tiles[pad[0]:] < 0)
+
+    check()
+
+
 @pytest.mark.parametrize("order", [A.ORDER_NATURAL, A.ORDER_COST])
 @pytest.mark.parametrize("kind", [A.LIST_FWD, A.LIST_DKV])
 def test_alternative_orders_hold_every_item_once(order, kind):
