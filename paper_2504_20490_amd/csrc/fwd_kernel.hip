@@ -36,6 +36,7 @@ struct FwdState {
     f32x16 acc[G::DB];     // O^T accumulator
     f32x16 s[2];           // S^T of the current tile (two 32-key blocks)
     float m, l;            // running row max of the raw scores; this lane's share of the running row sum
+    float tnext;           // this lane's maximum over s[] as it stands (all keys taken as visible)
     int rm[G::KK];         // per-lane LDS offsets of the K fragments (row-major read), block 0 of a tile
     int tr[G::DB][2];      // per-lane LDS offsets of the V^T fragments (transpose read), k-step 0 of a tile
 };
@@ -61,6 +62,14 @@ struct FwdTileLoad {
             if (n == i) copy->issue_full_one_at(n, v_dst, v_row, wave);
     }
 };
+
+// this lane's maximum over the 32 scores of a tile (v_max3: two scores per instruction)
+__device__ __forceinline__ float lane_max(const f32x16 (&s)[2]) {
+    float t = fmaxf(s[0][0], s[0][1]);
+#pragma unroll
+    for (int e = 2; e < 32; ++e) t = fmaxf(t, s[e >> 4][e & 15]);   // a chain: pairs of steps become one v_max3
+    return t;
+}
 
 __device__ __forceinline__ float pair_max(float x) {
     // v_permlane32_swap: first result = the value held by lane l % 32, second = the value of lane l % 32 + 32
@@ -96,11 +105,10 @@ __device__ __forceinline__ void fwd_iteration(FwdState<D>& st, const char* kbuf,
             for (int i = 0; i < 16; ++i)
                 if (32 * jb + 8 * (i >> 2) + (i & 3) > dkey) st.s[jb][i] = -INFINITY;
     }
-    float tmax = fmaxf(st.s[0][0], st.s[0][1]);
-#pragma unroll
-    for (int jb = 0; jb < 2; ++jb)
-#pragma unroll
-        for (int i = (jb == 0 ? 2 : 0); i < 16; ++i) tmax = fmaxf(tmax, st.s[jb][i]);
+    // An unmasked tile's maximum was taken while the scores were still warm: under the last MFMAs of the iteration
+    // that produced them, which have no other VALU work to run beside them (st.tnext).
+    float tmax = st.tnext;
+    if constexpr (MASK) tmax = lane_max(st.s);
     tmax = pair_max(tmax);
     // st.m is the reference that the exponentials are taken against, not the exact running maximum: it moves only
     // when the maximum has risen by more than kMaxSlack in the exponent (base-2) domain.  Weights then lie in
@@ -192,6 +200,15 @@ __device__ __forceinline__ void fwd_iteration(FwdState<D>& st, const char* kbuf,
         bf16x8 vq[kAheadV + 1];
 #pragma unroll
         for (int n = 0; n < kAheadV; ++n) vq[n] = v_frag(n);
+        // the next tile's maximum, a share of its 32 scores per step (the scores are complete since phase A)
+        float tnext = -INFINITY;
+        auto max_share = [&](int e0, int count) {
+#pragma unroll
+            for (int e = e0; e < e0 + count; ++e) tnext = fmaxf(tnext, sn[e >> 4][e & 15]);   // a chain: v_max3 per pair
+            // (an empty statement on the running value keeps the share in its step: nothing else needs the value
+            // before the end of the iteration, and the compiler would collect all 32 there)
+            asm volatile("" : "+v"(tnext));
+        };
 #pragma unroll
         for (int n = 0; n < NM; ++n) {
             if (n + kAheadV < NM) vq[(n + kAheadV) % (kAheadV + 1)] = v_frag(n + kAheadV);
@@ -199,11 +216,14 @@ __device__ __forceinline__ void fwd_iteration(FwdState<D>& st, const char* kbuf,
             // score pairs 8 .. 15 (key block 1, P fragments 2 and 3) under the MFMAs of fragments 0 and 1
             if constexpr (DB == 4) {
                 if (n < 8) softmax_pair(8 + n);
+                else if (!LAST) max_share((n - 8) * 4, 4);
             } else {
                 if (n < 4) { softmax_pair(8 + 2 * n); softmax_pair(9 + 2 * n); }
+                else if (!LAST) max_share((n - 4) * 8, 8);
             }
             __builtin_amdgcn_sched_barrier(0);
         }
+        if constexpr (!LAST) st.tnext = tnext;
     }
     __builtin_amdgcn_s_setprio(0);
     st.l = st.l * alpha + psum;
@@ -315,6 +335,7 @@ __global__ __launch_bounds__(kThreads, 2) void fwd_kernel(FwdParams p) {
         for (int kk = 0; kk < KK; ++kk)
             st.s[jb] = mfma(*reinterpret_cast<const bf16x8*>(kbuf0 + st.rm[kk] + jb * 32 * D * 2), st.qf[kk], st.s[jb]);
     }
+    st.tnext = n_tiles_w > 0 ? lane_max(st.s) : -INFINITY;
 
     // iteration kt: K(kt+1) in kbuf[(kt+1) & 1], V(kt) in vbuf[kt & 1]; issues K(kt+2) -> kbuf[kt & 1] and
     // V(kt+1) -> vbuf[(kt+1) & 1], both free since the barrier at the top
