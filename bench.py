@@ -30,16 +30,26 @@ GEMMS = {"fwd_kernel": 2, "bwd_dq_kernel": 3, "bwd_dkv_kernel": 4}
 
 
 def read_traffic(kernel: str, workload: str):
-    """HBM bytes per launch from the committed rocprofv3 counter summary, if there is one."""
-    path = os.path.join(ROOT, "profiles", f"{kernel}_{workload}_hbm_traffic.txt")
+    """HBM bytes per launch from the committed rocprofv3 counter summary (a --pmc run cannot share a process with
+    the timing run), and where it comes from.  The summary names the digest of the kernel sources it was measured
+    with; when the library has changed since, the figure is withheld (None) rather than shown beside fresh timings."""
+    from paper_2504_20490_amd.build import sources_digest
+    rel = os.path.join("profiles", f"{kernel}_{workload}_hbm_traffic.txt")
+    value, digest = None, None
     try:
-        with open(path) as f:
+        with open(os.path.join(ROOT, rel)) as f:
             for line in f:
                 if line.startswith("traffic_bytes_per_launch:"):
-                    return float(line.split(":", 1)[1])
+                    value = float(line.split(":", 1)[1])
+                elif line.startswith("kernel_sources_sha256_16:"):
+                    digest = line.split(":", 1)[1].strip()
     except OSError:
-        pass
-    return None
+        return None, "no committed counter summary for this kernel and workload"
+    if value is None:
+        return None, f"{rel} holds no figure"
+    if digest != sources_digest():
+        return None, f"{rel} was measured with other kernel sources ({digest}); withheld"
+    return value, f"{rel} (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of these kernel sources, not this run)"
 
 
 def cpu_baseline(cfg, lengths, q, k, v, do, rope=False):
@@ -130,9 +140,13 @@ def run_ring(args) -> int:
     ws = torch.empty(2 * hq * Tq * 4 + 256, dtype=torch.uint8, device=dev)
     stream = torch.cuda.current_stream()
 
+    # one block plan per ring step, made once and refilled with its chunks every step (no allocation per step)
+    plans = [A.BlockPlan(cuof(lens(rank)), cuof(lens(c)), pos(rank), pos(c), hq, hkv, d, stream.cuda_stream)
+             for c in range(n)]
+
     def step():
-        plans = [A.BlockPlan(cuof(lens(rank)), cuof(lens(c)), pos(rank), pos(c), hq, hkv, d, stream.cuda_stream)
-                 for c in range(n)]
+        for c, plan in enumerate(plans):
+            plan.update(cuof(lens(rank)), cuof(lens(c)), pos(rank), pos(c))
         for c, plan in enumerate(plans):
             if c == 0:
                 A.attn_block_fwd(plan, tq, kv[c][0], kv[c][1], o_acc, lse_acc, stream=stream)
@@ -144,25 +158,20 @@ def run_ring(args) -> int:
         for c, plan in enumerate(plans):
             A.attn_block_bwd(plan, tq, kv[c][0], kv[c][1], o_bf16, lse_acc, tdo, dq, dkv[c][0], dkv[c][1], ws,
                              dq_accumulate=c > 0, reuse_statistics=c > 0, stream=stream)
-        return plans
 
-    keep = []
     for _ in range(args.warmup):
-        keep.extend(step())
+        step()
     torch.cuda.synchronize()
-    for p in keep:
-        p.destroy()
-    keep = []
     A.profile_enable(True)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for _ in range(args.steps):
-        keep.extend(step())
+        step()
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
     A.profile_enable(False)
     prof = A.profile_read()
-    for p in keep:
+    for p in plans:
         p.destroy()
     probe = torch.empty(A.probe_scratch_bytes(), dtype=torch.uint8, device=dev)
     mfma_measured = A.probe_mfma_tflops(probe, stream=stream)
@@ -183,7 +192,7 @@ def run_ring(args) -> int:
         "config": {"workload": f"{cfg.name} cut into {n} chunks by position, rank {rank} (queries: chunk {rank} of every "
                                f"sequence; keys: all {n} chunks in turn)", "query_tokens": Tq, "q_heads": hq, "kv_heads": hkv,
                    "head_dim": d, "lengths": lengths, "visible_pairs_per_head": pairs, "fwd_useful_flops": fwd,
-                   "step": f"{n} block plans + {n} block fwd + merges + {n} block bwd (D once, dQ accumulated)"},
+                   "step": f"{n} block plan refills + {n} block fwd + merges + {n} block bwd (D once, dQ accumulated)"},
         "pct_of_bf16_mfma_peak": round(100.0 * tflops / PEAK_BF16_TFLOPS, 2),
         "kernel_ms_per_step": {name: round(ms, 4) for name, ms in kern.items()},
         "roofline": {"bound": "mfma", "kernel": dominant, "achieved": round(achieved, 2), "peak": PEAK_BF16_TFLOPS,
@@ -304,18 +313,23 @@ def main() -> int:
         A.rope_table(table, positions, d, 10000.0, stream=stream)      # per model, not per step
         tq_rot, tk_rot = torch.empty_like(tq), torch.empty_like(tk)
 
+    # One plan for the whole run, made before the first step as a training loop would; every step refills it with
+    # its pack (hspmd_attn_plan_update: the work lists are rebuilt on the host and uploaded into storage the plan
+    # owns, while the previous step's kernels run): no device allocation, no free and no device-wide wait per step.
+    cu0, _, _ = A.build_cu_seqlens(lengths)
+    plan = A.Plan(cu0, hq, hkv, d, stream.cuda_stream, order=order)
+
     def step():
         cu, _, _ = A.build_cu_seqlens(lengths)                 # packed offsets
-        plan = A.Plan(cu, hq, hkv, d, stream.cuda_stream, order=order)   # cost-sorted work lists
+        plan.update(cu)                                        # cost-sorted work lists of this step's pack
         if args.rope:
             A.rope_qk(plan, tq, tk, tq_rot, tk_rot, table, positions, stream=stream)
             A.attn_varlen_fwd(plan, tq_rot, tk_rot, tv, o, lse, stream=stream)
             A.attn_varlen_bwd_rope(plan, tq_rot, tk_rot, tv, o, lse, tdo, dq, dk, dv, ws, table, positions,
                                    grad_dtype=grad, stream=stream)
-            return plan
+            return
         A.attn_varlen_fwd(plan, tq, tk, tv, o, lse, stream=stream)
         A.attn_varlen_bwd(plan, tq, tk, tv, o, lse, tdo, dq, dk, dv, ws, grad_dtype=grad, stream=stream)
-        return plan
 
     if args.calibrate_copy:
         src = torch.empty(1 << 30, dtype=torch.uint8, device=dev).fill_(1)
@@ -324,32 +338,27 @@ def main() -> int:
         torch.cuda.synchronize()
         del src, dst
 
-    plans = []
     for _ in range(args.warmup):
-        plans.append(step())
+        step()
     torch.cuda.synchronize()
-    for p in plans:
-        p.destroy()
-    plans = []
     A.profile_enable(True)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for _ in range(args.steps):
-        plans.append(step())
+        step()
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
     A.profile_enable(False)
     stats = A.profile_read_stats()
     prof = {name: (st["mean"] * st["launches"], st["launches"]) for name, st in stats.items()}
-    for p in plans:
-        p.destroy()
 
-    # host-only share of a step (offsets + work lists + upload), timed separately for the record
+    # host-only share of a step (offsets + work lists + upload into the plan), timed separately for the record
     t1 = time.perf_counter()
     for _ in range(5):
         cu, _, _ = A.build_cu_seqlens(lengths)
-        A.Plan(cu, hq, hkv, d, stream.cuda_stream, order=order).destroy()
+        plan.update(cu)
     plan_ms = (time.perf_counter() - t1) / 5 * 1e3
+    plan.destroy()
 
     # measured matrix-core rate of this device (register-only MFMA loop): a second denominator beside the nominal peak
     probe = torch.empty(A.probe_scratch_bytes(), dtype=torch.uint8, device=dev)
@@ -369,6 +378,7 @@ def main() -> int:
     dom_ms = kern[dominant]
     achieved = GEMMS[dominant] * pair_flops / (dom_ms * 1e-3) / 1e12 if dom_ms > 0 else 0.0
 
+    traffic, traffic_source = read_traffic(dominant, cfg.name.split("_")[0])
     out = {
         "metric": "varlen causal attn fwd+bwd TFLOP/s and % bf16 MFMA peak, 32k-token mix",
         "value": round(tflops, 2),
@@ -386,7 +396,8 @@ def main() -> int:
                    "head_dim": d, "num_seqs": len(lengths), "lengths": lengths,
                    "sum_L_Lplus1": 2 * w.causal_pairs(lengths), "fwd_useful_flops": fwd,
                    "grad_dtype": args.grad_dtype, "order": args.order,
-                   "step": "build_cu_seqlens + work lists + fwd + bwd(dQ pass with the row statistic D, dK/dV pass)"},
+                   "step": "build_cu_seqlens + work lists (plan refill, no device allocation) + fwd + "
+                           "bwd(dQ pass with the row statistic D, dK/dV pass)"},
         "pct_of_bf16_mfma_peak": round(100.0 * tflops / PEAK_BF16_TFLOPS, 2),
         "kernel_ms": {name: round(ms, 4) for name, ms in kern.items()},
         "kernel_ms_median": {name: round(st["median"], 4) for name, st in stats.items()},
@@ -394,7 +405,7 @@ def main() -> int:
         "host_plan_ms": round(plan_ms, 4),
         "roofline": {"bound": "mfma", "kernel": dominant, "achieved": round(achieved, 2), "peak": PEAK_BF16_TFLOPS,
                      "unit": "TFLOP/s", "frac": round(achieved / PEAK_BF16_TFLOPS, 4),
-                     "traffic": read_traffic(dominant, cfg.name.split("_")[0]),
+                     "traffic": traffic, "traffic_source": traffic_source,
                      "flops_per_launch": GEMMS[dominant] * pair_flops,
                      "measured_mfma_peak": round(mfma_measured, 1),
                      "frac_of_measured_peak": round(achieved / mfma_measured, 4) if mfma_measured > 0 else None,
@@ -413,7 +424,8 @@ def main() -> int:
         rope_ms = kern.get("rope_qk_kernel", 0.0)
         gbs = rope_bytes / (rope_ms * 1e-3) / 1e9 if rope_ms > 0 else 0.0
         out["metric"] = "varlen causal attn fwd+bwd with rotary embedding, attention TFLOP/s, 32k-token mix"
-        out["config"]["step"] = "build_cu_seqlens + work lists + rope(q, k) + fwd + bwd(dQ pass with D, dK/dV pass; dQ, dK turned back)"
+        out["config"]["step"] = ("build_cu_seqlens + work lists (plan refill) + rope(q, k) + fwd + "
+                                 "bwd(dQ pass with D, dK/dV pass; dQ, dK turned back)")
         out["rope_roofline"] = {"bound": "hbm", "kernel": "rope_qk_kernel", "achieved": round(gbs, 1), "peak": 8000.0,
                                 "unit": "GB/s", "frac": round(gbs / 8000.0, 4), "traffic": None,
                                 "bytes_per_launch": rope_bytes}

@@ -36,14 +36,15 @@
  *     Forward and backward only enqueue work; they never synchronise and never
  *     allocate, so they may be recorded into a HIP graph (with per-kernel timing
  *     off, see hspmd_profile_enable).  Plan creation allocates the plan's small index arrays and
- *     copies them to the device before returning.
+ *     copies them to the device before returning; hspmd_attn_plan_update refills them without
+ *     allocating.
  *   - Every call returns an hspmd_status; no exception crosses this boundary
  *     and nothing aborts.  Arguments are validated on the host before any
  *     launch.  hspmd_last_error() returns a thread-local description of the
  *     last failure on the calling thread.
- *   - Threads: every entry point except the per-kernel timing calls may be used by several host
- *     threads at once, on plans, streams and workspaces of their own; a plan may be shared by
- *     threads that only launch with it.  Two launches that share a workspace must be ordered
+ *   - Threads: every entry point may be used by several host threads at once, on plans, streams
+ *     and workspaces of their own; a plan may be shared by threads that only launch with it
+ *     (hspmd_attn_plan_update and hspmd_attn_plan_destroy need the plan to themselves).  Two launches that share a workspace must be ordered
  *     (same stream, or an event between them).
  *   - bf16 tensors are raw 16-bit bfloat16 values.
  */
@@ -176,7 +177,25 @@ hspmd_status hspmd_attn_plan_create(const int32_t* cu_seqlens_host, int32_t num_
 hspmd_status hspmd_attn_plan_create_ordered(const int32_t* cu_seqlens_host, int32_t num_seqs, int32_t local_q_heads,
                                             int32_t local_kv_heads, int32_t head_dim, hspmd_order order,
                                             void* stream, hspmd_attn_plan** out);
-hspmd_status hspmd_attn_plan_destroy(hspmd_attn_plan* plan);      /* NULL is accepted */
+/*
+ * Refill of a plan with the next pack (same local head counts, head_dim and launch order): the work lists are rebuilt
+ * on the host and uploaded into device storage the plan already owns.  The paper plans every mixed-length batch on the
+ * CPU while the GPU works on the previous one (Appendix "Scenario-specific Planning", mixed-length case); this is that
+ * step for the attention operator, and it is what a training loop calls once per micro-batch.
+ *   A plan holds three copies ("slots") of its lists and a refill writes the one used longest ago, so launches that
+ *   read the current lists may still be running.  Each forward / backward / rotary call records an event on its stream
+ *   for the slot it reads; the refill waits on the host for the event of the slot it is about to overwrite (finished
+ *   long ago once the ring has gone round), never for the device as a whole.  A slot that is too small is replaced
+ *   by a larger one (hipFree + hipMalloc, with a quarter of headroom); packs of similar size therefore stop
+ *   allocating after the first few refills.
+ *   Not for concurrent use: no other thread may launch with the plan during the call.  A launch recorded into a HIP
+ *   graph records no event (events cannot be waited for from inside a capture): a plan that a graph replays must not be
+ *   refilled while the graph may run.  On error the plan keeps its previous pack.
+ * Errors: INVALID_ARG for a NULL plan, the wrong kind of plan, bad cu_seqlens; HIP for a failed runtime call.
+ */
+hspmd_status hspmd_attn_plan_update(hspmd_attn_plan* plan, const int32_t* cu_seqlens_host, int32_t num_seqs);
+/* hipFree of the lists' device storage: waits for the device to go idle.  NULL is accepted. */
+hspmd_status hspmd_attn_plan_destroy(hspmd_attn_plan* plan);
 int64_t hspmd_attn_plan_total_tokens(const hspmd_attn_plan* plan); /* -1 on NULL */
 int64_t hspmd_attn_plan_num_items(const hspmd_attn_plan* plan, hspmd_list_kind kind); /* slots incl. padding */
 
@@ -190,7 +209,8 @@ size_t hspmd_attn_bwd_workspace_bytes(const hspmd_attn_plan* plan);
  *   k,v bf16 [T, local_kv_heads, head_dim]; token stride kv_token_stride (same for k and v)
  *       Strides are in elements and let q/k/v be views into a fused QKV projection output;
  *       they must be multiples of 8 (16-byte rows) and >= heads*head_dim; base pointers 16-byte aligned.
- *   softmax_scale   <= 0 selects 1/sqrt(head_dim)
+ *   softmax_scale   <= 0 selects 1/sqrt(head_dim); a positive value must be finite and lie in [2^-60, 2^60]
+ *                   (INVALID_ARG otherwise: the backward carries lse / scale in fp32)
  *   o   bf16 [T, local_q_heads, head_dim], contiguous, written
  *   lse fp32 [local_q_heads, T], natural-log logsumexp of the scaled scores, written
  * T == 0 returns OK without launching.
@@ -311,6 +331,9 @@ hspmd_status hspmd_attn_block_plan_create(const int32_t* cu_q_host, const int32_
                                           const int32_t* k_pos_host, int32_t num_seqs, int32_t local_q_heads,
                                           int32_t local_kv_heads, int32_t head_dim, void* stream, hspmd_attn_plan** out);
 int64_t hspmd_attn_plan_total_kv_tokens(const hspmd_attn_plan* plan);   /* -1 on NULL */
+/* hspmd_attn_plan_update for a block plan: the chunks of the next ring step or the next pack. */
+hspmd_status hspmd_attn_block_plan_update(hspmd_attn_plan* plan, const int32_t* cu_q_host, const int32_t* cu_k_host,
+                                          const int32_t* q_pos_host, const int32_t* k_pos_host, int32_t num_seqs);
 
 /*
  * Forward of one block.  q bf16 [Tq, Hq, d], k / v bf16 [Tk, Hkv, d] (strides as in hspmd_attn_varlen_fwd).
@@ -364,8 +387,9 @@ hspmd_status hspmd_attn_block_bwd(const hspmd_attn_plan* plan, const void* q, co
  *                 itself), 2 backward dQ pass, 3 backward dK/dV pass,
  *                 4 rotary embedding of q and k
  *   ms, launches  host, [HSPMD_NUM_KERNELS] each, accumulated into (the caller zeroes them)
- * Not thread-safe: enable, launch and read from one thread.  Events are created on first use and
- * reused; enabling allocates nothing on the device.
+ * The switch is process-wide: while it is on, launches from every thread are recorded (the records are guarded by a
+ * lock) and a read returns all of them.  Events are created on first use and reused; enabling allocates nothing on
+ * the device.
  */
 #define HSPMD_NUM_KERNELS 5
 hspmd_status hspmd_profile_enable(int32_t on);

@@ -322,7 +322,9 @@ int oracle_attn_rows(const double *q, const double *k, const double *v, const do
 }
 
 /* Sampled keys: for n (token, kv head) pairs, dK_j [n,d] and dV_j [n,d].  LSE_r and D_r of
- * the rows r >= j are evaluated row by row first; cost O((L - j) L d G) per sample. */
+ * the rows r >= j are evaluated row by row first; samples that share a (sequence, kv head) share
+ * that evaluation (from the smallest sampled j on): cost O((L - j_min) L d G) per such group
+ * plus O((L - j) d G) per sample. */
 int oracle_attn_keys(const double *q, const double *k, const double *v, const double *d_o,
                      const int32_t *cu, int32_t B, int32_t Hq, int32_t Hkv, int32_t d, double scale,
                      int32_t n, const int32_t *tokens, const int32_t *kv_heads,
@@ -339,12 +341,26 @@ int oracle_attn_keys(const double *q, const double *k, const double *v, const do
     double *scratch = (double *)malloc(sizeof(double) * 2 * row_len * (size_t)oracle_num_threads());
     double *lse = (double *)malloc(sizeof(double) * row_len * (size_t)G);
     double *Dr = (double *)malloc(sizeof(double) * row_len * (size_t)G);
-    if (!scratch || !lse || !Dr) { free(scratch); free(lse); free(Dr); return ORACLE_NO_MEM; }
+    int32_t *seq_of = (int32_t *)malloc(sizeof(int32_t) * (size_t)(n > 0 ? n : 1));
+    char *done = (char *)calloc((size_t)(n > 0 ? n : 1), 1);
+    if (!scratch || !lse || !Dr || !seq_of || !done) {
+        free(scratch); free(lse); free(Dr); free(seq_of); free(done);
+        return ORACLE_NO_MEM;
+    }
     for (int32_t x = 0; x < n; ++x) {
         int32_t i = 0;
-        while (cu[i + 1] <= tokens[x]) ++i;
+        while (cu[i + 1] <= tokens[x]) ++i;   /* the sequence that holds this token */
+        seq_of[x] = i;
+    }
+    for (int32_t x = 0; x < n; ++x) {
+        if (done[x]) continue;
+        /* the group of samples with this sample's sequence and kv head, and its first key */
+        const int32_t i = seq_of[x], g = kv_heads[x];
         const int64_t t0 = cu[i];
-        const int32_t L = cu[i + 1] - cu[i], j = tokens[x] - cu[i], g = kv_heads[x];
+        const int32_t L = cu[i + 1] - cu[i];
+        int32_t j_min = tokens[x] - cu[i];
+        for (int32_t y = x + 1; y < n; ++y)
+            if (seq_of[y] == i && kv_heads[y] == g && tokens[y] - cu[i] < j_min) j_min = tokens[y] - cu[i];
         const double *kh = k + (int64_t)g * d;
         const double *vh = v + (int64_t)g * d;
 #pragma omp parallel
@@ -354,20 +370,28 @@ int oracle_attn_keys(const double *q, const double *k, const double *v, const do
             for (int32_t hg = 0; hg < G; ++hg) {
                 const int32_t h = g * G + hg;
 #pragma omp for schedule(dynamic, 4) nowait
-                for (int32_t r = j; r < L; ++r) {
+                for (int32_t r = j_min; r < L; ++r) {
                     const double *q_row = q + (t0 + r) * qs + (int64_t)h * d;
                     const double *do_row = d_o + (t0 + r) * qs + (int64_t)h * d;
-                    lse[(int64_t)hg * row_len + (r - j)] = row_forward(q_row, kh, vh, ks, t0, r, d, scale, p, NULL);
-                    Dr[(int64_t)hg * row_len + (r - j)] = row_backward(do_row, kh, vh, ks, t0, r, d, scale, p, dp, NULL);
+                    lse[(int64_t)hg * row_len + (r - j_min)] = row_forward(q_row, kh, vh, ks, t0, r, d, scale, p, NULL);
+                    Dr[(int64_t)hg * row_len + (r - j_min)] = row_backward(do_row, kh, vh, ks, t0, r, d, scale, p, dp, NULL);
                 }
             }
         }
-        const int64_t kv = (t0 + j) * ks + (int64_t)g * d;
-        key_backward(q, d_o, k + kv, v + kv, qs, t0, L, j, g, G, d, scale, lse, Dr, (int64_t)row_len, j,
-                     dk_rows + (int64_t)x * d, dv_rows + (int64_t)x * d);
+#pragma omp parallel for schedule(dynamic, 1)
+        for (int32_t y = x; y < n; ++y) {
+            if (seq_of[y] != i || kv_heads[y] != g) continue;
+            const int32_t j = tokens[y] - cu[i];
+            const int64_t kv = (t0 + j) * ks + (int64_t)g * d;
+            key_backward(q, d_o, k + kv, v + kv, qs, t0, L, j, g, G, d, scale, lse, Dr, (int64_t)row_len, j_min,
+                         dk_rows + (int64_t)y * d, dv_rows + (int64_t)y * d);
+            done[y] = 1;
+        }
     }
     free(scratch);
     free(lse);
     free(Dr);
+    free(seq_of);
+    free(done);
     return ORACLE_OK;
 }

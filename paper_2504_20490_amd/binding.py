@@ -73,6 +73,10 @@ def load_library():
     lib.hspmd_attn_plan_create.restype = ctypes.c_int
     lib.hspmd_attn_plan_create.argtypes = [i32p, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32,
                                            vp, ctypes.POINTER(vp)]
+    lib.hspmd_attn_plan_update.restype = ctypes.c_int
+    lib.hspmd_attn_plan_update.argtypes = [vp, i32p, ctypes.c_int32]
+    lib.hspmd_attn_block_plan_update.restype = ctypes.c_int
+    lib.hspmd_attn_block_plan_update.argtypes = [vp, i32p, i32p, i32p, i32p, ctypes.c_int32]
     lib.hspmd_attn_plan_destroy.restype = ctypes.c_int
     lib.hspmd_attn_plan_destroy.argtypes = [vp]
     lib.hspmd_attn_plan_total_tokens.restype = ctypes.c_int64
@@ -208,6 +212,13 @@ class Plan:
             raise HspmdError(1, "plan already destroyed")
         return self._h
 
+    def update(self, cu_seqlens: Sequence[int]) -> None:
+        """Refill with the next pack (same head counts, head_dim and order): no device allocation in the steady state."""
+        lib = load_library()
+        cu = _i32(cu_seqlens)
+        _check(lib.hspmd_attn_plan_update(self.handle, _ptr32(cu), len(cu) - 1))
+        self.total_tokens = int(lib.hspmd_attn_plan_total_tokens(self.handle))
+
     def num_items(self, kind: int) -> int:
         return int(load_library().hspmd_attn_plan_num_items(self.handle, kind))
 
@@ -242,8 +253,8 @@ def attn_varlen_fwd(plan: Plan, q, k, v, o, lse, softmax_scale: float = 0.0, str
     o bf16 [T,Hq,d] contiguous and lse fp32 [Hq,T] are written."""
     lib = load_library()
     _check(lib.hspmd_attn_varlen_fwd(plan.handle, _dev_ptr(q), _dev_ptr(k), _dev_ptr(v),
-                                     q.stride(0) if q.dim() == 3 and q.shape[0] > 1 else plan.q_heads * plan.head_dim,
-                                     k.stride(0) if k.dim() == 3 and k.shape[0] > 1 else plan.kv_heads * plan.head_dim,
+                                     _token_stride(q, plan.q_heads, plan.head_dim),
+                                     _token_stride(k, plan.kv_heads, plan.head_dim),
                                      float(softmax_scale), _dev_ptr(o), _dev_ptr(lse), _stream_handle(stream)))
 
 
@@ -254,8 +265,8 @@ def attn_varlen_bwd(plan: Plan, q, k, v, o, lse, d_o, dq, dk, dv, workspace, sof
     lib = load_library()
     _check(lib.hspmd_attn_varlen_bwd(plan.handle, _dev_ptr(q), _dev_ptr(k), _dev_ptr(v), _dev_ptr(o), _dev_ptr(lse),
                                      _dev_ptr(d_o),
-                                     q.stride(0) if q.dim() == 3 and q.shape[0] > 1 else plan.q_heads * plan.head_dim,
-                                     k.stride(0) if k.dim() == 3 and k.shape[0] > 1 else plan.kv_heads * plan.head_dim,
+                                     _token_stride(q, plan.q_heads, plan.head_dim),
+                                     _token_stride(k, plan.kv_heads, plan.head_dim),
                                      float(softmax_scale), _dev_ptr(dq), _dev_ptr(dk), _dev_ptr(dv), int(grad_dtype),
                                      _dev_ptr(workspace), workspace.numel() * workspace.element_size(),
                                      _stream_handle(stream)))
@@ -377,9 +388,15 @@ class BlockPlan(Plan):
         self.total_tokens = int(lib.hspmd_attn_plan_total_tokens(handle))
         self.total_kv_tokens = int(lib.hspmd_attn_plan_total_kv_tokens(handle))
 
-
-def _token_stride(t, heads: int, head_dim: int) -> int:
-    return t.stride(0) if t.dim() == 3 and t.shape[0] > 1 else heads * head_dim
+    def update(self, cu_q: Sequence[int], cu_k: Sequence[int], q_pos: Sequence[int], k_pos: Sequence[int]) -> None:
+        """Refill with the chunks of the next ring step or pack: no device allocation in the steady state."""
+        lib = load_library()
+        cq, ck, qp, kp = _i32(cu_q), _i32(cu_k), _i32(q_pos), _i32(k_pos)
+        if not (len(cq) == len(ck) == len(qp) + 1 == len(kp) + 1):
+            raise HspmdError(1, "per-sequence arrays differ in length")
+        _check(lib.hspmd_attn_block_plan_update(self.handle, _ptr32(cq), _ptr32(ck), _ptr32(qp), _ptr32(kp), len(qp)))
+        self.total_tokens = int(lib.hspmd_attn_plan_total_tokens(self.handle))
+        self.total_kv_tokens = int(lib.hspmd_attn_plan_total_kv_tokens(self.handle))
 
 
 def _opt_ptr(t) -> ctypes.c_void_p:

@@ -15,6 +15,22 @@ HIPCC_FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall",
                "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
 
 
+# what decides a kernel's HBM traffic: the attention kernels, their shared device code and the launch order
+KERNEL_SOURCES = ["fwd_kernel.hip", "bwd_kernels.hip", "bwd_dkv_kernel.hip", "attn_device.hpp", "kernels.hpp",
+                  "schedule.hpp", "schedule.cpp"]
+
+
+def sources_digest() -> str:
+    """sha256 (first 16 hex digits) over the attention kernels' sources: names the kernels a measurement was
+    taken with, so that a stored figure can be told from one of an older build."""
+    import hashlib
+    h = hashlib.sha256()
+    for name in sorted(KERNEL_SOURCES):
+        with open(os.path.join(CSRC, name), "rb") as f:
+            h.update(name.encode() + b"\0" + f.read())
+    return h.hexdigest()[:16]
+
+
 def _stale() -> bool:
     if not os.path.exists(LIBRARY):
         return True

@@ -2,6 +2,7 @@
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
+#include <atomic>
 #include <cmath>
 #include <cstdio>
 #include <cstring>
@@ -40,11 +41,14 @@ struct ProfileRecord {
     int kernel;
     hipEvent_t start, stop;
 };
-bool g_profile_on = false;
+// The switch is read on every launch from any thread; the records and the event pool are shared by all
+// threads and guarded by one mutex (taken only while timing is on).
+std::atomic<bool> g_profile_on{false};
+std::mutex g_profile_mutex;
 std::vector<ProfileRecord> g_records;
 std::vector<hipEvent_t> g_event_pool;
 
-hipError_t take_event(hipEvent_t* ev) {
+hipError_t take_event(hipEvent_t* ev) {   // g_profile_mutex held
     if (!g_event_pool.empty()) {
         *ev = g_event_pool.back();
         g_event_pool.pop_back();
@@ -56,7 +60,8 @@ hipError_t take_event(hipEvent_t* ev) {
 // Runs `launch` on `stream`; when profiling is on, brackets it with two events.
 template <typename F>
 hipError_t timed_launch(int kernel, hipStream_t stream, F&& launch) {
-    if (!g_profile_on) return launch();
+    if (!g_profile_on.load(std::memory_order_relaxed)) return launch();
+    std::lock_guard<std::mutex> lock(g_profile_mutex);
     ProfileRecord r{kernel, nullptr, nullptr};
     hipError_t e = take_event(&r.start);
     if (e != hipSuccess) return e;
@@ -103,6 +108,7 @@ hipError_t upload_blocking(void* dst, const void* src, size_t bytes) {
 // waits for the recorded events, hands every launch's elapsed time to `sink(kernel, ms)` and forgets the records
 template <typename Sink>
 hspmd_status drain_profile_records(Sink&& sink) {
+    std::lock_guard<std::mutex> lock(g_profile_mutex);
     hspmd_status rc = HSPMD_OK;
     for (const ProfileRecord& r : g_records) {
         hipError_t e = hipEventSynchronize(r.stop);
@@ -119,19 +125,165 @@ hspmd_status drain_profile_records(Sink&& sink) {
 
 }  // namespace
 
+// One copy of a plan's work lists on the device.  A plan owns a small ring of these: a refill
+// (hspmd_attn_plan_update) writes the slot that was used longest ago while launches that read the current one may
+// still be running, and waits (on the host) only for the event that the last launch reading THAT slot recorded.
+struct ListSlot {
+    void* block = nullptr;          // device memory
+    size_t capacity = 0;            // bytes
+    hipEvent_t last_use = nullptr;  // recorded on the launch stream after a launch that reads the slot
+    bool recorded = false;
+};
+constexpr int kPlanSlots = 3;
+
 struct hspmd_attn_plan {
     int32_t num_seqs = 0;
     int32_t q_heads = 0, kv_heads = 0, head_dim = 0;
     int64_t total_tokens = 0;
     int32_t max_position = 0;      // positions inside a sequence that the plan's tokens occupy: 0 .. max_position-1
     int64_t count[3] = {0, 0, 0};
-    hspmd_work_item* items[3] = {nullptr, nullptr, nullptr};   // device; three views into one allocation
-    void* device_block = nullptr;
+    hspmd_work_item* items[3] = {nullptr, nullptr, nullptr};   // device; three views into the current slot
+    hspmd_order order = HSPMD_ORDER_XCD_COST;
     // block variant (hspmd_attn_block_plan_create): total_tokens counts query tokens
     bool is_block = false;
     int64_t total_kv_tokens = 0;
     hspmd_block_item* block_items[3] = {nullptr, nullptr, nullptr};
+    // device copies of the lists
+    ListSlot slots[kPlanSlots];
+    int current = 0;
+    mutable std::mutex use_mutex;   // launches from several threads record the current slot's event
 };
+
+namespace {
+
+// Marks the plan's current slot as read by work just enqueued on `stream` (a later refill of that slot waits for
+// it).  Nothing is recorded while the stream is being captured into a graph: a plan that a graph replays must not be
+// refilled while the graph may run, and that is the caller's to ensure.
+hipError_t mark_use(const hspmd_attn_plan* plan, hipStream_t stream) {
+    hipStreamCaptureStatus capturing = hipStreamCaptureStatusNone;
+    if (stream != nullptr) {
+        const hipError_t e = hipStreamIsCapturing(stream, &capturing);
+        if (e != hipSuccess) return e;
+    }
+    if (capturing != hipStreamCaptureStatusNone) return hipSuccess;
+    std::lock_guard<std::mutex> lock(plan->use_mutex);
+    ListSlot& slot = const_cast<hspmd_attn_plan*>(plan)->slots[plan->current];
+    if (!slot.last_use) return hipSuccess;
+    const hipError_t e = hipEventRecord(slot.last_use, stream);
+    if (e == hipSuccess) slot.recorded = true;
+    return e;
+}
+
+// Puts `bytes` of host data into the plan's next slot and makes it the current one.  Steady state (the slot has been
+// used before and is large enough): no allocation, no free, no device-wide synchronisation -- one wait for that
+// slot's own last launch (long finished when the ring has gone round) and one copy on the library's copy stream.
+hspmd_status install_lists(hspmd_attn_plan* plan, const void* host, size_t bytes, bool first) {
+    const int next = first ? 0 : (plan->current + 1) % kPlanSlots;
+    ListSlot& slot = plan->slots[next];
+    hipError_t e = hipSuccess;
+    if (slot.recorded) {
+        e = hipEventSynchronize(slot.last_use);
+        if (e != hipSuccess) return fail_hip(e, "hipEventSynchronize(work list slot)");
+        slot.recorded = false;
+    }
+    if (!slot.last_use) {
+        e = hipEventCreateWithFlags(&slot.last_use, hipEventDisableTiming);
+        if (e != hipSuccess) return fail_hip(e, "hipEventCreate(work list slot)");
+    }
+    if (bytes > slot.capacity) {
+        // grow only, with headroom, so that packs of similar size stop allocating after the first few refills
+        if (slot.block) {
+            e = hipFree(slot.block);
+            slot.block = nullptr;
+            slot.capacity = 0;
+            if (e != hipSuccess) return fail_hip(e, "hipFree(work lists)");
+        }
+        const size_t want = first ? bytes : bytes + bytes / 4;
+        e = hipMalloc(&slot.block, want);
+        if (e != hipSuccess) return fail_hip(e, "hipMalloc(work lists)");
+        slot.capacity = want;
+    }
+    if (bytes > 0) {
+        e = upload_blocking(slot.block, host, bytes);
+        if (e != hipSuccess) return fail_hip(e, "hipMemcpyAsync(work lists)");
+    }
+    plan->current = next;
+    return HSPMD_OK;
+}
+
+// Builds the three packed lists of a pack on the host (forward and dQ share one copy) and installs them.
+hspmd_status fill_packed_plan(hspmd_attn_plan* plan, const int32_t* cu, int32_t num_seqs, bool first) {
+    std::vector<hspmd_work_item> all;
+    size_t offset[3] = {0, 0, 0};
+    int64_t count[3] = {0, 0, 0};
+    try {
+        for (int kind = 0; kind < 3; ++kind) {
+            if (kind == HSPMD_LIST_DQ) {
+                // same items, costs and order as the forward list: one copy serves both passes
+                count[kind] = count[HSPMD_LIST_FWD];
+                offset[kind] = offset[HSPMD_LIST_FWD];
+                continue;
+            }
+            const std::vector<hspmd_work_item> list = hspmd::build_work_list(
+                (hspmd_list_kind)kind, cu, num_seqs, plan->q_heads, plan->kv_heads, hspmd::kNumXcd, plan->order);
+            count[kind] = (int64_t)list.size();
+            offset[kind] = all.size();
+            all.insert(all.end(), list.begin(), list.end());
+        }
+    } catch (const std::bad_alloc&) {
+        return fail(HSPMD_ERR_INVALID_ARG, "out of host memory while building the work lists");
+    }
+    if (hspmd_status rc = install_lists(plan, all.data(), all.size() * sizeof(hspmd_work_item), first)) return rc;
+    plan->num_seqs = num_seqs;
+    plan->total_tokens = cu[num_seqs];
+    plan->max_position = 0;
+    for (int32_t i = 0; i < num_seqs; ++i) plan->max_position = std::max(plan->max_position, cu[i + 1] - cu[i]);
+    for (int kind = 0; kind < 3; ++kind) {
+        plan->count[kind] = count[kind];
+        plan->items[kind] = count[kind] > 0 ? static_cast<hspmd_work_item*>(plan->slots[plan->current].block) + offset[kind]
+                                            : nullptr;
+    }
+    return HSPMD_OK;
+}
+
+hspmd_status fill_block_plan(hspmd_attn_plan* plan, const int32_t* cu_q, const int32_t* cu_k, const int32_t* q_pos,
+                             const int32_t* k_pos, int32_t num_seqs, bool first) {
+    std::vector<hspmd_block_item> all;
+    size_t offset[3] = {0, 0, 0};
+    int64_t count[3] = {0, 0, 0};
+    try {
+        for (int kind = 0; kind < 3; ++kind) {
+            if (kind == HSPMD_LIST_DQ) {
+                count[kind] = count[HSPMD_LIST_FWD];
+                offset[kind] = offset[HSPMD_LIST_FWD];
+                continue;
+            }
+            const std::vector<hspmd_block_item> list = hspmd::build_block_list(
+                (hspmd_list_kind)kind, cu_q, cu_k, q_pos, k_pos, num_seqs, plan->q_heads, plan->kv_heads, hspmd::kNumXcd);
+            count[kind] = (int64_t)list.size();
+            offset[kind] = all.size();
+            all.insert(all.end(), list.begin(), list.end());
+        }
+    } catch (const std::bad_alloc&) {
+        return fail(HSPMD_ERR_INVALID_ARG, "out of host memory while building the work lists");
+    }
+    if (hspmd_status rc = install_lists(plan, all.data(), all.size() * sizeof(hspmd_block_item), first)) return rc;
+    plan->num_seqs = num_seqs;
+    plan->total_tokens = cu_q[num_seqs];
+    plan->total_kv_tokens = cu_k[num_seqs];
+    plan->max_position = 0;
+    for (int32_t i = 0; i < num_seqs; ++i)
+        plan->max_position = std::max(plan->max_position, std::max(q_pos[i] + (cu_q[i + 1] - cu_q[i]),
+                                                                   k_pos[i] + (cu_k[i + 1] - cu_k[i])));
+    for (int kind = 0; kind < 3; ++kind) {
+        plan->count[kind] = count[kind];
+        plan->block_items[kind] =
+            count[kind] > 0 ? static_cast<hspmd_block_item*>(plan->slots[plan->current].block) + offset[kind] : nullptr;
+    }
+    return HSPMD_OK;
+}
+
+}  // namespace
 
 extern "C" {
 
@@ -205,49 +357,16 @@ hspmd_status hspmd_attn_plan_create_ordered(const int32_t* cu_seqlens_host, int3
         return fail(HSPMD_ERR_INVALID_ARG, "unknown order");
     hspmd_attn_plan* plan = new (std::nothrow) hspmd_attn_plan();
     if (!plan) return fail(HSPMD_ERR_INVALID_ARG, "out of host memory");
-    plan->num_seqs = num_seqs;
     plan->q_heads = local_q_heads;
     plan->kv_heads = local_kv_heads;
     plan->head_dim = head_dim;
-    plan->total_tokens = cu_seqlens_host[num_seqs];
-    for (int32_t i = 0; i < num_seqs; ++i)
-        plan->max_position = std::max(plan->max_position, cu_seqlens_host[i + 1] - cu_seqlens_host[i]);
-    // the three lists back to back in one host vector -> one allocation, one copy, one synchronisation
-    std::vector<hspmd_work_item> all;
-    size_t offset[3] = {0, 0, 0};
-    try {
-        for (int kind = 0; kind < 3; ++kind) {
-            if (kind == HSPMD_LIST_DQ) {
-                // same items, costs and order as the forward list: one copy serves both passes
-                plan->count[kind] = plan->count[HSPMD_LIST_FWD];
-                offset[kind] = offset[HSPMD_LIST_FWD];
-                continue;
-            }
-            const std::vector<hspmd_work_item> list = hspmd::build_work_list(
-                (hspmd_list_kind)kind, cu_seqlens_host, num_seqs, local_q_heads, local_kv_heads, hspmd::kNumXcd, order);
-            plan->count[kind] = (int64_t)list.size();
-            offset[kind] = all.size();
-            all.insert(all.end(), list.begin(), list.end());
-        }
-    } catch (const std::bad_alloc&) {
-        delete plan;
-        return fail(HSPMD_ERR_INVALID_ARG, "out of host memory while building the work lists");
-    }
+    plan->order = order;
     (void)stream;   // kept in the signature; the upload uses the library's copy stream
-    if (!all.empty()) {
-        const size_t bytes = all.size() * sizeof(hspmd_work_item);
-        hipError_t e = hipMalloc(&plan->device_block, bytes);
-        if (e != hipSuccess) {
-            delete plan;
-            return fail_hip(e, "hipMalloc(work lists)");
-        }
-        e = upload_blocking(plan->device_block, all.data(), bytes);   // `all` dies at the end of this scope
-        if (e != hipSuccess) {
-            hspmd_attn_plan_destroy(plan);
-            return fail_hip(e, "hipMemcpyAsync(work lists)");
-        }
-        for (int kind = 0; kind < 3; ++kind)
-            if (plan->count[kind] > 0) plan->items[kind] = static_cast<hspmd_work_item*>(plan->device_block) + offset[kind];
+    if (hspmd_status rc = fill_packed_plan(plan, cu_seqlens_host, num_seqs, true)) {
+        const std::string why_failed = g_last_error;
+        hspmd_attn_plan_destroy(plan);
+        g_last_error = why_failed;
+        return rc;
     }
     *out = plan;
     return HSPMD_OK;
@@ -260,12 +379,36 @@ hspmd_status hspmd_attn_plan_create(const int32_t* cu_seqlens_host, int32_t num_
                                           HSPMD_ORDER_XCD_COST, stream, out);
 }
 
+hspmd_status hspmd_attn_plan_update(hspmd_attn_plan* plan, const int32_t* cu_seqlens_host, int32_t num_seqs) {
+    if (!plan) return fail(HSPMD_ERR_INVALID_ARG, "plan is NULL");
+    if (plan->is_block) return fail(HSPMD_ERR_INVALID_ARG, "plan was made by hspmd_attn_block_plan_create");
+    const std::string why = hspmd::check_pack(cu_seqlens_host, num_seqs, plan->q_heads, plan->kv_heads);
+    if (!why.empty()) return fail(HSPMD_ERR_INVALID_ARG, why);
+    return fill_packed_plan(plan, cu_seqlens_host, num_seqs, false);
+}
+
+hspmd_status hspmd_attn_block_plan_update(hspmd_attn_plan* plan, const int32_t* cu_q_host, const int32_t* cu_k_host,
+                                          const int32_t* q_pos_host, const int32_t* k_pos_host, int32_t num_seqs) {
+    if (!plan) return fail(HSPMD_ERR_INVALID_ARG, "plan is NULL");
+    if (!plan->is_block) return fail(HSPMD_ERR_INVALID_ARG, "plan was not made by hspmd_attn_block_plan_create");
+    const std::string why =
+        hspmd::check_block_pack(cu_q_host, cu_k_host, q_pos_host, k_pos_host, num_seqs, plan->q_heads, plan->kv_heads);
+    if (!why.empty()) return fail(HSPMD_ERR_INVALID_ARG, why);
+    return fill_block_plan(plan, cu_q_host, cu_k_host, q_pos_host, k_pos_host, num_seqs, false);
+}
+
 hspmd_status hspmd_attn_plan_destroy(hspmd_attn_plan* plan) {
     if (!plan) return HSPMD_OK;
     hspmd_status rc = HSPMD_OK;
-    if (plan->device_block) {
-        const hipError_t e = hipFree(plan->device_block);
-        if (e != hipSuccess) rc = fail_hip(e, "hipFree(work lists)");
+    for (ListSlot& slot : plan->slots) {
+        if (slot.block) {
+            const hipError_t e = hipFree(slot.block);   // waits for the device: launches that read the slot have ended
+            if (e != hipSuccess) rc = fail_hip(e, "hipFree(work lists)");
+        }
+        if (slot.last_use) {
+            const hipError_t e = hipEventDestroy(slot.last_use);
+            if (e != hipSuccess) rc = fail_hip(e, "hipEventDestroy(work list slot)");
+        }
     }
     delete plan;
     return rc;
@@ -292,6 +435,19 @@ static hspmd_status check_strides(const hspmd_attn_plan* plan, int64_t q_token_s
     return HSPMD_OK;
 }
 
+// softmax_scale <= 0 selects 1/sqrt(head_dim).  A positive scale must be finite and lie in [2^-60, 2^60]: the backward
+// carries the logsumexp in units of raw scores (lse / scale), which must neither overflow nor fall into the
+// denormal range of fp32.
+static hspmd_status resolve_scale(float softmax_scale, int32_t head_dim, float* scale) {
+    if (!(softmax_scale <= 0.f)) {
+        if (!std::isfinite(softmax_scale)) return fail(HSPMD_ERR_INVALID_ARG, "softmax_scale is not finite");
+        if (softmax_scale < 0x1p-60f || softmax_scale > 0x1p60f)
+            return fail(HSPMD_ERR_INVALID_ARG, "a positive softmax_scale must lie in [2^-60, 2^60]");
+    }
+    *scale = softmax_scale > 0.f ? softmax_scale : 1.0f / std::sqrt((float)head_dim);
+    return HSPMD_OK;
+}
+
 hspmd_status hspmd_attn_varlen_fwd(const hspmd_attn_plan* plan, const void* q, const void* k, const void* v,
                                    int64_t q_token_stride, int64_t kv_token_stride, float softmax_scale,
                                    void* o, float* lse, void* stream) {
@@ -302,8 +458,8 @@ hspmd_status hspmd_attn_varlen_fwd(const hspmd_attn_plan* plan, const void* q, c
     if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(o))
         return fail(HSPMD_ERR_INVALID_ARG, "q, k, v, o must be 16-byte aligned");
     if (hspmd_status rc = check_strides(plan, q_token_stride, kv_token_stride)) return rc;
-    if (!(softmax_scale <= 0.f) && !std::isfinite(softmax_scale)) return fail(HSPMD_ERR_INVALID_ARG, "softmax_scale is not finite");
-    const float scale = softmax_scale > 0.f ? softmax_scale : 1.0f / std::sqrt((float)plan->head_dim);
+    float scale = 0.f;
+    if (hspmd_status rc = resolve_scale(softmax_scale, plan->head_dim, &scale)) return rc;
     hspmd::FwdParams p{};
     p.q = static_cast<const uint16_t*>(q);
     p.k = static_cast<const uint16_t*>(k);
@@ -321,6 +477,7 @@ hspmd_status hspmd_attn_varlen_fwd(const hspmd_attn_plan* plan, const void* q, c
     hipStream_t s = static_cast<hipStream_t>(stream);
     const hipError_t e = timed_launch(0, s, [&] { return hspmd::launch_fwd(p, plan->head_dim, plan->count[HSPMD_LIST_FWD], false, s); });
     if (e != hipSuccess) return fail_hip(e, "forward launch");
+    if (const hipError_t m = mark_use(plan, s)) return fail_hip(m, "hipEventRecord(work list slot)");
     return HSPMD_OK;
 }
 
@@ -342,8 +499,8 @@ static hspmd_status varlen_bwd(const hspmd_attn_plan* plan, const void* q, const
     if (hspmd_status rc = check_strides(plan, q_token_stride, kv_token_stride)) return rc;
     if (workspace_bytes < hspmd_attn_bwd_workspace_bytes(plan))
         return fail(HSPMD_ERR_WORKSPACE_TOO_SMALL, "workspace smaller than hspmd_attn_bwd_workspace_bytes(plan)");
-    if (!(softmax_scale <= 0.f) && !std::isfinite(softmax_scale)) return fail(HSPMD_ERR_INVALID_ARG, "softmax_scale is not finite");
-    const float scale = softmax_scale > 0.f ? softmax_scale : 1.0f / std::sqrt((float)plan->head_dim);
+    float scale = 0.f;
+    if (hspmd_status rc = resolve_scale(softmax_scale, plan->head_dim, &scale)) return rc;
     hspmd::BwdParams p{};
     p.q = static_cast<const uint16_t*>(q);
     p.k = static_cast<const uint16_t*>(k);
@@ -376,6 +533,7 @@ static hspmd_status varlen_bwd(const hspmd_attn_plan* plan, const void* q, const
     p.items = plan->items[HSPMD_LIST_DKV];
     e = timed_launch(3, s, [&] { return hspmd::launch_bwd_dkv(p, plan->head_dim, plan->count[HSPMD_LIST_DKV], false, s); });
     if (e != hipSuccess) return fail_hip(e, "backward dK/dV launch");
+    if (const hipError_t m = mark_use(plan, s)) return fail_hip(m, "hipEventRecord(work list slot)");
     return HSPMD_OK;
 }
 
@@ -453,10 +611,12 @@ hspmd_status hspmd_rope_qk(const hspmd_attn_plan* plan, const void* q, const voi
         p.block_items = plan->block_items[HSPMD_LIST_DKV];
         e = timed_launch(4, s, [&] { return hspmd::launch_rope_block(p, plan->count[HSPMD_LIST_DKV], true, s); });
         if (e != hipSuccess) return fail_hip(e, "rope launch (key chunks)");
+        if (const hipError_t m = mark_use(plan, s)) return fail_hip(m, "hipEventRecord(work list slot)");
         return HSPMD_OK;
     }
     const hipError_t e = timed_launch(4, s, [&] { return hspmd::launch_rope_qk(p, plan->count[HSPMD_LIST_FWD], s); });
     if (e != hipSuccess) return fail_hip(e, "rope launch");
+    if (const hipError_t m = mark_use(plan, s)) return fail_hip(m, "hipEventRecord(work list slot)");
     return HSPMD_OK;
 }
 
@@ -525,52 +685,15 @@ hspmd_status hspmd_attn_block_plan_create(const int32_t* cu_q_host, const int32_
     hspmd_attn_plan* plan = new (std::nothrow) hspmd_attn_plan();
     if (!plan) return fail(HSPMD_ERR_INVALID_ARG, "out of host memory");
     plan->is_block = true;
-    plan->num_seqs = num_seqs;
     plan->q_heads = local_q_heads;
     plan->kv_heads = local_kv_heads;
     plan->head_dim = head_dim;
-    plan->total_tokens = cu_q_host[num_seqs];
-    plan->total_kv_tokens = cu_k_host[num_seqs];
-    for (int32_t i = 0; i < num_seqs; ++i)
-        plan->max_position = std::max(plan->max_position, std::max(q_pos_host[i] + (cu_q_host[i + 1] - cu_q_host[i]),
-                                                                   k_pos_host[i] + (cu_k_host[i + 1] - cu_k_host[i])));
-    std::vector<hspmd_block_item> all;
-    size_t offset[3] = {0, 0, 0};
-    try {
-        for (int kind = 0; kind < 3; ++kind) {
-            if (kind == HSPMD_LIST_DQ) {
-                // same items, costs and order as the forward list: one copy serves both passes
-                plan->count[kind] = plan->count[HSPMD_LIST_FWD];
-                offset[kind] = offset[HSPMD_LIST_FWD];
-                continue;
-            }
-            const std::vector<hspmd_block_item> list =
-                hspmd::build_block_list((hspmd_list_kind)kind, cu_q_host, cu_k_host, q_pos_host, k_pos_host, num_seqs,
-                                        local_q_heads, local_kv_heads, hspmd::kNumXcd);
-            plan->count[kind] = (int64_t)list.size();
-            offset[kind] = all.size();
-            all.insert(all.end(), list.begin(), list.end());
-        }
-    } catch (const std::bad_alloc&) {
-        delete plan;
-        return fail(HSPMD_ERR_INVALID_ARG, "out of host memory while building the work lists");
-    }
     (void)stream;   // kept in the signature; the upload uses the library's copy stream
-    if (!all.empty()) {
-        const size_t bytes = all.size() * sizeof(hspmd_block_item);
-        hipError_t e = hipMalloc(&plan->device_block, bytes);
-        if (e != hipSuccess) {
-            delete plan;
-            return fail_hip(e, "hipMalloc(work lists)");
-        }
-        e = upload_blocking(plan->device_block, all.data(), bytes);
-        if (e != hipSuccess) {
-            hspmd_attn_plan_destroy(plan);
-            return fail_hip(e, "hipMemcpyAsync(work lists)");
-        }
-        for (int kind = 0; kind < 3; ++kind)
-            if (plan->count[kind] > 0)
-                plan->block_items[kind] = static_cast<hspmd_block_item*>(plan->device_block) + offset[kind];
+    if (hspmd_status rc = fill_block_plan(plan, cu_q_host, cu_k_host, q_pos_host, k_pos_host, num_seqs, true)) {
+        const std::string why_failed = g_last_error;
+        hspmd_attn_plan_destroy(plan);
+        g_last_error = why_failed;
+        return rc;
     }
     *out = plan;
     return HSPMD_OK;
@@ -592,8 +715,8 @@ hspmd_status hspmd_attn_block_fwd(const hspmd_attn_plan* plan, const void* q, co
     if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(o_partial))
         return fail(HSPMD_ERR_INVALID_ARG, "q, k, v, o_partial must be 16-byte aligned");
     if (hspmd_status rc = check_strides(plan, q_token_stride, kv_token_stride)) return rc;
-    if (!(softmax_scale <= 0.f) && !std::isfinite(softmax_scale)) return fail(HSPMD_ERR_INVALID_ARG, "softmax_scale is not finite");
-    const float scale = softmax_scale > 0.f ? softmax_scale : 1.0f / std::sqrt((float)plan->head_dim);
+    float scale = 0.f;
+    if (hspmd_status rc = resolve_scale(softmax_scale, plan->head_dim, &scale)) return rc;
     hspmd::FwdParams p{};
     p.q = static_cast<const uint16_t*>(q);
     p.k = static_cast<const uint16_t*>(k);
@@ -611,6 +734,7 @@ hspmd_status hspmd_attn_block_fwd(const hspmd_attn_plan* plan, const void* q, co
     hipStream_t s = static_cast<hipStream_t>(stream);
     const hipError_t e = timed_launch(0, s, [&] { return hspmd::launch_fwd(p, plan->head_dim, plan->count[HSPMD_LIST_FWD], true, s); });
     if (e != hipSuccess) return fail_hip(e, "block forward launch");
+    if (const hipError_t m = mark_use(plan, s)) return fail_hip(m, "hipEventRecord(work list slot)");
     return HSPMD_OK;
 }
 
@@ -655,8 +779,8 @@ static hspmd_status block_bwd(const hspmd_attn_plan* plan, const void* q, const 
     if (hspmd_status rc = check_strides(plan, q_token_stride, kv_token_stride)) return rc;
     if (workspace_bytes < hspmd_attn_bwd_workspace_bytes(plan))
         return fail(HSPMD_ERR_WORKSPACE_TOO_SMALL, "workspace smaller than hspmd_attn_bwd_workspace_bytes(plan)");
-    if (!(softmax_scale <= 0.f) && !std::isfinite(softmax_scale)) return fail(HSPMD_ERR_INVALID_ARG, "softmax_scale is not finite");
-    const float scale = softmax_scale > 0.f ? softmax_scale : 1.0f / std::sqrt((float)plan->head_dim);
+    float scale = 0.f;
+    if (hspmd_status rc = resolve_scale(softmax_scale, plan->head_dim, &scale)) return rc;
     hspmd::BwdParams p{};
     p.q = static_cast<const uint16_t*>(q);
     p.k = static_cast<const uint16_t*>(k);
@@ -694,6 +818,7 @@ static hspmd_status block_bwd(const hspmd_attn_plan* plan, const void* q, const 
     p.block_items = plan->block_items[HSPMD_LIST_DKV];
     e = timed_launch(3, s, [&] { return hspmd::launch_bwd_dkv(p, plan->head_dim, plan->count[HSPMD_LIST_DKV], true, s); });
     if (e != hipSuccess) return fail_hip(e, "block backward dK/dV launch");
+    if (const hipError_t m = mark_use(plan, s)) return fail_hip(m, "hipEventRecord(work list slot)");
     return HSPMD_OK;
 }
 
@@ -718,7 +843,7 @@ hspmd_status hspmd_attn_block_bwd_rope(const hspmd_attn_plan* plan, const void* 
 }
 
 hspmd_status hspmd_profile_enable(int32_t on) {
-    g_profile_on = on != 0;
+    g_profile_on.store(on != 0, std::memory_order_relaxed);
     return HSPMD_OK;
 }
 

@@ -317,3 +317,12 @@ def test_bench_refuses_more_than_one_gpu():
     r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True, timeout=120)
     assert r.returncode != 0
     assert "one GPU" in r.stderr and r.stdout.strip() == ""
+
+
+def test_plan_update_rejects_bad_arguments_without_a_gpu():
+    lib = A.load_library()
+    cu = np.array([0, 5], dtype=np.int32)
+    p32 = cu.ctypes.data_as(ctypes.POINTER(ctypes.c_int32))
+    assert lib.hspmd_attn_plan_update(None, p32, 1) == 1
+    assert b"NULL" in lib.hspmd_last_error()
+    assert lib.hspmd_attn_block_plan_update(None, p32, p32, p32, p32, 1) == 1

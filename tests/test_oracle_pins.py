@@ -249,6 +249,12 @@ def test_sampled_rows_and_keys_equal_the_full_evaluation():
     tok = np.repeat(np.arange(T), hkv); hd = np.tile(np.arange(hkv), T)
     dk_r, dv_r = oracle.attn_keys(q, k, v, do, lengths, s, tok, hd)
     assert np.array_equal(dk_r.reshape(T, hkv, d), dk) and np.array_equal(dv_r.reshape(T, hkv, d), dv)
+    # a shuffled subset with repeats: samples that share a (sequence, kv head) share their row statistics, whichever
+    # of them comes first
+    rng = np.random.default_rng(131)
+    pick = rng.integers(0, T * hkv, size=40)
+    dk_s, dv_s = oracle.attn_keys(q, k, v, do, lengths, s, tok[pick], hd[pick])
+    assert np.array_equal(dk_s, dk[tok[pick], hd[pick]]) and np.array_equal(dv_s, dv[tok[pick], hd[pick]])
 
 
 def test_zero_length_sequences_and_empty_pack():
