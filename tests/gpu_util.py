@@ -119,12 +119,14 @@ def assert_close(name, got, ref, max_abs=MAX_ABS, rel_fro=REL_FRO):
 SLACK_FROM = 8.0    # a bf16 value in [8, 16) has half an ulp of 2^-5 = 0.031 > MAX_ABS
 
 
-def magnitude_bound(ref: np.ndarray, roundings: int = 1) -> float:
+def magnitude_bound(ref: np.ndarray, roundings: int = 1, operand_peak: float = 0.0) -> float:
     """max-abs bound for packs outside the benchmark configurations' value range: the nominal MAX_ABS, widened by
     `roundings` bf16 roundings (2^-9 relative each: P, dS and O are rounded to bf16 on their way into or out of the
     matrix cores) ONLY when the reference tensor really holds an element of magnitude >= 8, where one such
-    rounding alone exceeds the nominal bound.  Tensors below that are held to the nominal bound."""
-    peak = float(np.max(np.abs(ref))) if ref.size else 0.0
+    rounding alone exceeds the nominal bound.  Tensors below that are held to the nominal bound.
+    operand_peak: the largest magnitude of the bf16 OPERAND that the tensor is a product of (max |dS| for dQ and dK),
+    when the caller has evaluated it: a pack of very short sequences has |dS| >= 8 without |dK| >= 8."""
+    peak = max(float(np.max(np.abs(ref))) if ref.size else 0.0, float(operand_peak))
     if peak < SLACK_FROM:
         CONTEXT["slack"] = None
         return MAX_ABS

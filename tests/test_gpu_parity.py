@@ -167,11 +167,49 @@ def test_strided_views_into_a_fused_qkv_buffer():
         assert torch.equal(getattr(a, name), getattr(b, name)), name
 
 
+def _max_abs_ds(lengths, q, k, v, do, s):
+    """max |dS| over a pack of short sequences, dense per (sequence, head): the magnitude of the bf16 operand that dQ
+    and dK are products of.  It feeds a tolerance, not an expected value."""
+    hq, hkv = q.shape[1], k.shape[1]
+    G = hq // hkv
+    cu = np.concatenate([[0], np.cumsum(lengths)])
+    peak = 0.0
+    for i, L in enumerate(lengths):
+        sl = slice(int(cu[i]), int(cu[i + 1]))
+        low = np.tril(np.ones((L, L), dtype=bool))
+        for h in range(hq):
+            S = np.where(low, s * q[sl, h] @ k[sl, h // G].T, -np.inf)
+            P = np.exp(S - S.max(axis=1, keepdims=True))
+            P /= P.sum(axis=1, keepdims=True)
+            dP = do[sl, h] @ v[sl, h // G].T
+            dS = P * (dP - (P * dP).sum(axis=1, keepdims=True))
+            peak = max(peak, float(np.abs(dS).max()))
+    return peak
+
+
 def test_many_tiny_sequences():
-    """3000 sequences of 1 .. 12 tokens: one work item per (sequence, head), most of every tile empty."""
+    """3000 sequences of 1 .. 12 tokens: one work item per (sequence, head), most of every tile empty.  Every row is
+    one of the first rows of its sequence: weights of 1/2 .. 1, so |dS| = |P (dP - D)| reaches 10.4 on this pack (70 of
+    its 359K pairs exceed 8) although no gradient element does, and D itself is taken from the bf16-rounded O of rows
+    that are close to single V rows.  The bf16 rounding of such a dS (half an ulp of 0.03 times |q| scale, two of them in
+    one dK element) is what the widened bound of dQ and dK stands for; O and dV are held to the nominal bound."""
     rng = np.random.default_rng(8)
     lengths = [int(x) for x in rng.integers(1, 13, size=3000)]
-    _full_check(lengths, 4, 2, 64, seed=61, magnitude_slack=True)   # 3000 x 8 heads of outliers: the bound follows max|ref|
+    hq, hkv, d, seed = 4, 2, 64, 61
+    gpu_util.CONTEXT["case"] = f"small pack {len(lengths)} seqs Hq{hq} Hkv{hkv} d{d} seed{seed}"
+    q, k, v, do = make_case(lengths, hq, hkv, d, seed)
+    run = GpuRun(lengths, q, k, v, do).run()
+    s = default_scale(d)
+    ro, rlse = oracle.attn_fwd(f64(q), f64(k), f64(v), lengths, s)
+    rdq, rdk, rdv = oracle.attn_bwd(f64(q), f64(k), f64(v), f64(do), lengths, s)
+    peak_ds = _max_abs_ds(lengths, f64(q), f64(k), f64(v), f64(do), s)
+    assert 8.0 <= peak_ds < 16.0, peak_ds
+    assert_close("O", run.host("o"), ro)
+    assert np.max(np.abs(run.host("lse") - rlse)) <= LSE_ABS
+    assert_close("dQ", run.host("dq"), rdq, max_abs=gpu_util.magnitude_bound(rdq, operand_peak=peak_ds))
+    assert_close("dK", run.host("dk"), rdk, max_abs=gpu_util.magnitude_bound(rdk, operand_peak=peak_ds))
+    gpu_util.CONTEXT["slack"] = None
+    assert_close("dV", run.host("dv"), rdv)
 
 
 def test_one_very_long_sequence_on_sampled_rows_and_keys():
