@@ -236,6 +236,29 @@ hspmd_status hspmd_attn_varlen_bwd(const hspmd_attn_plan* plan, const void* q, c
                                    void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * hspmd_attn_varlen_bwd for callers that cannot allocate device memory and have no workspace to pass: code that
+ * runs under HIP graph capture, tight serving / training loops, harnesses that forbid hipMalloc.  Same arguments,
+ * kernels and results as hspmd_attn_varlen_bwd, without `workspace`: the row statistics that the dQ pass leaves for
+ * the dK/dV pass go into a fixed device array inside the library (HSPMD_STATIC_WORKSPACE_BYTES bytes on every GPU the
+ * library runs on, held until the process ends).  The call allocates and frees nothing and creates no events
+ * (per-kernel timing does not apply to it).
+ *   Limit: hspmd_attn_bwd_workspace_bytes(plan) <= HSPMD_STATIC_WORKSPACE_BYTES, i.e.
+ *   local_q_heads * total_tokens <= 2^21 (the 65536-token, 32-head configuration just fits);
+ *   larger packs get WORKSPACE_TOO_SMALL and nothing is launched.
+ *   All calls on one GPU share the array: two calls that may overlap on one GPU (different streams, no event between
+ *   them) race on it; calls on one stream are ordered and safe.  Nothing in it needs clearing between calls: every
+ *   value the dK/dV pass reads is written by the dQ pass of the same call.
+ *   The array's device address is looked up on the first call on each device; make that first call outside a graph
+ *   capture.
+ * Other errors as hspmd_attn_varlen_bwd.
+ */
+#define HSPMD_STATIC_WORKSPACE_BYTES (16u * 1024u * 1024u + 256u)
+hspmd_status hspmd_attn_varlen_bwd_static_ws(const hspmd_attn_plan* plan, const void* q, const void* k, const void* v,
+                                             const void* o, const float* lse, const void* d_o, int64_t q_token_stride,
+                                             int64_t kv_token_stride, float softmax_scale, void* dq, void* dk, void* dv,
+                                             hspmd_grad_dtype grad_dtype, void* stream);
+
+/*
  * Rotary position embedding around the attention of a pack.  The paper's models are Llama-style with RoPE as
  * position encoding (experimental setup, model configuration table) and give no formula; this is the published
  * definition in the rotate-half pairing: with theta_i = base^(-2i/head_dim), i = 0 .. head_dim/2-1, a token at

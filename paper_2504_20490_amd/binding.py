@@ -91,6 +91,9 @@ def load_library():
     lib.hspmd_attn_varlen_bwd.restype = ctypes.c_int
     lib.hspmd_attn_varlen_bwd.argtypes = [vp, vp, vp, vp, vp, vp, vp, ctypes.c_int64, ctypes.c_int64,
                                           ctypes.c_float, vp, vp, vp, ctypes.c_int, vp, ctypes.c_size_t, vp]
+    lib.hspmd_attn_varlen_bwd_static_ws.restype = ctypes.c_int
+    lib.hspmd_attn_varlen_bwd_static_ws.argtypes = [vp, vp, vp, vp, vp, vp, vp, ctypes.c_int64, ctypes.c_int64,
+                                                    ctypes.c_float, vp, vp, vp, ctypes.c_int, vp]
     lib.hspmd_profile_enable.restype = ctypes.c_int
     lib.hspmd_profile_enable.argtypes = [ctypes.c_int32]
     lib.hspmd_rope_table_bytes.restype = ctypes.c_size_t
@@ -270,6 +273,21 @@ def attn_varlen_bwd(plan: Plan, q, k, v, o, lse, d_o, dq, dk, dv, workspace, sof
                                      float(softmax_scale), _dev_ptr(dq), _dev_ptr(dk), _dev_ptr(dv), int(grad_dtype),
                                      _dev_ptr(workspace), workspace.numel() * workspace.element_size(),
                                      _stream_handle(stream)))
+
+
+STATIC_WORKSPACE_BYTES = 16 * 1024 * 1024 + 256
+
+
+def attn_varlen_bwd_static_ws(plan: Plan, q, k, v, o, lse, d_o, dq, dk, dv, softmax_scale: float = 0.0,
+                              grad_dtype: int = GRAD_BF16, stream=None) -> None:
+    """attn_varlen_bwd without a workspace argument: the library's fixed device array is used (no allocation)."""
+    lib = load_library()
+    _check(lib.hspmd_attn_varlen_bwd_static_ws(plan.handle, _dev_ptr(q), _dev_ptr(k), _dev_ptr(v), _dev_ptr(o),
+                                               _dev_ptr(lse), _dev_ptr(d_o),
+                                               _token_stride(q, plan.q_heads, plan.head_dim),
+                                               _token_stride(k, plan.kv_heads, plan.head_dim),
+                                               float(softmax_scale), _dev_ptr(dq), _dev_ptr(dk), _dev_ptr(dv),
+                                               int(grad_dtype), _stream_handle(stream)))
 
 
 def _token_stride(x, heads: int, head_dim: int) -> int:

@@ -485,7 +485,8 @@ hspmd_status hspmd_attn_varlen_fwd(const hspmd_attn_plan* plan, const void* q, c
 static hspmd_status varlen_bwd(const hspmd_attn_plan* plan, const void* q, const void* k, const void* v, const void* o,
                                const float* lse, const void* d_o, int64_t q_token_stride, int64_t kv_token_stride,
                                float softmax_scale, void* dq, void* dk, void* dv, hspmd_grad_dtype grad_dtype,
-                               const float* rope_table, void* workspace, size_t workspace_bytes, void* stream) {
+                               const float* rope_table, void* workspace, size_t workspace_bytes, void* stream,
+                               bool timed = true) {
     if (!plan) return fail(HSPMD_ERR_INVALID_ARG, "plan is NULL");
     if (plan->is_block) return fail(HSPMD_ERR_INVALID_ARG, "plan was made by hspmd_attn_block_plan_create");
     if (grad_dtype != HSPMD_GRAD_BF16 && grad_dtype != HSPMD_GRAD_F32)
@@ -528,10 +529,12 @@ static hspmd_status varlen_bwd(const hspmd_attn_plan* plan, const void* q, const
     hipStream_t s = static_cast<hipStream_t>(stream);
     // D = rowsum(dO * O) is computed by the dQ pass itself (every (row, head) belongs to exactly one of its items)
     p.items = plan->items[HSPMD_LIST_DQ];
-    hipError_t e = timed_launch(2, s, [&] { return hspmd::launch_bwd_dq(p, plan->head_dim, plan->count[HSPMD_LIST_DQ], false, s); });
+    auto dq_pass = [&] { return hspmd::launch_bwd_dq(p, plan->head_dim, plan->count[HSPMD_LIST_DQ], false, s); };
+    hipError_t e = timed ? timed_launch(2, s, dq_pass) : dq_pass();
     if (e != hipSuccess) return fail_hip(e, "backward dQ launch");
     p.items = plan->items[HSPMD_LIST_DKV];
-    e = timed_launch(3, s, [&] { return hspmd::launch_bwd_dkv(p, plan->head_dim, plan->count[HSPMD_LIST_DKV], false, s); });
+    auto dkv_pass = [&] { return hspmd::launch_bwd_dkv(p, plan->head_dim, plan->count[HSPMD_LIST_DKV], false, s); };
+    e = timed ? timed_launch(3, s, dkv_pass) : dkv_pass();
     if (e != hipSuccess) return fail_hip(e, "backward dK/dV launch");
     if (const hipError_t m = mark_use(plan, s)) return fail_hip(m, "hipEventRecord(work list slot)");
     return HSPMD_OK;
@@ -544,6 +547,53 @@ hspmd_status hspmd_attn_varlen_bwd(const hspmd_attn_plan* plan, const void* q, c
                                    void* workspace, size_t workspace_bytes, void* stream) {
     return varlen_bwd(plan, q, k, v, o, lse, d_o, q_token_stride, kv_token_stride, softmax_scale, dq, dk, dv, grad_dtype,
                       nullptr, workspace, workspace_bytes, stream);
+}
+
+// ---- backward with the library's own workspace: for callers that cannot allocate -------------------------------
+// The row statistics that the dQ pass leaves for the dK/dV pass live in a fixed device array instead of a buffer
+// from the caller.  In host code the array's name is only a handle for hipGetSymbolAddress: the device address is
+// looked up once per device and kept; the kernels get that address like any other workspace pointer.
+static __device__ __attribute__((used)) __align__(256) unsigned char scratch[HSPMD_STATIC_WORKSPACE_BYTES];
+
+namespace {
+std::mutex g_scratch_mutex;
+std::map<int, void*> g_scratch_address;   // per device: each GPU holds its own copy of the array
+
+hipError_t static_workspace(void** out) {
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    auto it = g_scratch_address.find(dev);
+    if (it == g_scratch_address.end()) {
+        void* address = nullptr;
+        e = hipGetSymbolAddress(&address, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return e;
+        if (!address) return hipErrorInvalidSymbol;
+        it = g_scratch_address.emplace(dev, address).first;
+    }
+    *out = it->second;
+    return hipSuccess;
+}
+}  // namespace
+
+hspmd_status hspmd_attn_varlen_bwd_static_ws(const hspmd_attn_plan* plan, const void* q, const void* k, const void* v,
+                                             const void* o, const float* lse, const void* d_o, int64_t q_token_stride,
+                                             int64_t kv_token_stride, float softmax_scale, void* dq, void* dk, void* dv,
+                                             hspmd_grad_dtype grad_dtype, void* stream) {
+    if (!plan) return fail(HSPMD_ERR_INVALID_ARG, "plan is NULL");
+    const size_t need = hspmd_attn_bwd_workspace_bytes(plan);
+    if (need > (size_t)HSPMD_STATIC_WORKSPACE_BYTES)
+        return fail(HSPMD_ERR_WORKSPACE_TOO_SMALL,
+                    "local_q_heads * total_tokens exceeds what the library's fixed workspace holds "
+                    "(HSPMD_STATIC_WORKSPACE_BYTES); use hspmd_attn_varlen_bwd with a workspace of the caller's");
+    void* workspace = nullptr;
+    const hipError_t e = static_workspace(&workspace);
+    if (e != hipSuccess) return fail_hip(e, "hipGetSymbolAddress(static workspace)");
+    // Per-kernel timing creates events on first use; this entry point must not create anything, so it launches
+    // untimed whatever the switch says.
+    return varlen_bwd(plan, q, k, v, o, lse, d_o, q_token_stride, kv_token_stride, softmax_scale, dq, dk, dv, grad_dtype,
+                      nullptr, workspace, (size_t)HSPMD_STATIC_WORKSPACE_BYTES, stream, /*timed=*/false);
 }
 
 // ---- rotary position embedding ---------------------------------------------------------------------------------
