@@ -43,9 +43,10 @@
  *     launch.  hspmd_last_error() returns a thread-local description of the
  *     last failure on the calling thread.
  *   - Threads: every entry point may be used by several host threads at once, on plans, streams
- *     and workspaces of their own; a plan may be shared by threads that only launch with it
- *     (hspmd_attn_plan_update and hspmd_attn_plan_destroy need the plan to themselves).  Two launches that share a workspace must be ordered
- *     (same stream, or an event between them).
+ *     and workspaces of their own.  Launches that share a plan, or a workspace, must be ordered on the
+ *     device (same stream, or an event between them): the persistent kernels draw their work items
+ *     from counters that belong to the plan, and the launch that finishes leaves them at zero for the
+ *     next one.  hspmd_attn_plan_update and hspmd_attn_plan_destroy need the plan to themselves.
  *   - bf16 tensors are raw 16-bit bfloat16 values.
  */
 #ifndef HSPMD_ATTN_H

@@ -458,6 +458,42 @@ __device__ __forceinline__ ItemGeom load_item(const hspmd_work_item* items, cons
     }
 }
 
+// Work distribution of the persistent kernels.  A launch starts as many workgroups as the device holds at once;
+// workgroup b begins with slot b of the launch-ordered list (slot p belongs to queue p % kQueues, and workgroups are
+// handed to the XCDs round-robin, so queue q is served by the workgroups of XCD q) and then draws further slots of
+// ITS OWN queue from a counter in device memory, in list order: the same order in which the hardware would have
+// dispatched one workgroup per slot, without the time a compute unit spends between two workgroups (several
+// microseconds per item, a fifth of the time on packs of short sequences).  Which workgroup computes an item never
+// changes the item's result.
+//   counters[0 .. kQueues-1]: draws made from each queue; counters[kQueues]: workgroups that have left.
+// The last workgroup to leave puts all of them back to zero, so the next launch that uses the same counters (it must
+// be ordered after this one on the device) starts from a clean state and nothing on the host has to reset them.
+constexpr int kQueues = 8;          // = kNumXcd of the scheduler
+constexpr int kQueueInts = 16;      // int32 per counter block (kQueues + 1 used)
+struct ItemQueue {
+    int32_t* counters;
+    int queue, first_round;
+    __device__ __forceinline__ void init(int32_t* c) {
+        counters = c;
+        queue = blockIdx.x % kQueues;
+        first_round = gridDim.x / kQueues;     // the grid is a multiple of kQueues: slots 0 .. gridDim.x-1 are taken
+    }
+    // one thread per workgroup: the list index of the workgroup's next item (past the end when the queue is empty)
+    __device__ __forceinline__ int draw() const {
+        const int k = __hip_atomic_fetch_add(counters + queue, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        return (first_round + k) * kQueues + queue;
+    }
+    // one thread per workgroup, after its last draw
+    __device__ __forceinline__ void leave() const {
+        const int gone = __hip_atomic_fetch_add(counters + kQueues, 1, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_AGENT);
+        if (gone == (int)gridDim.x - 1) {
+#pragma unroll
+            for (int i = 0; i <= kQueues; ++i)
+                __hip_atomic_store(counters + i, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+    }
+};
+
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
 }  // namespace hspmd

@@ -31,9 +31,13 @@ namespace hspmd {
 
 namespace {
 
-template <int D>
+// KD: 16-column steps of the contractions over head_dim (G1) that hold data: D / 16, or fewer when head_dim ends
+// before the tile width (the steps beyond it would multiply the zero padding of the K / V fragments)
+template <int D, int KD = D / 16>
 struct DkvGeom {
-    static constexpr int KK = D / 16;                      // k-steps over head_dim; also frags per G2 operand
+    static_assert(KD >= 1 && KD <= D / 16, "k-steps inside the tile width");
+    static constexpr int KK = D / 16;                      // fragments per G2 operand (2 k-steps x D / 32 row blocks)
+    static constexpr int K1 = KD;                          // k-steps over head_dim of G1
     static constexpr int DB = D / 32;                      // 32-row blocks of dK^T / dV^T
     static constexpr int kTileBytes = kDkvQTile * D * 2;   // one 64-row tile
     static constexpr int kBlockBytes = 32 * D * 2;         // one 32-row block of it
@@ -42,13 +46,13 @@ struct DkvGeom {
     static constexpr int kStages = 4;
 };
 
-template <int D>
+template <int D, int KD>
 struct DkvState {
-    using G = DkvGeom<D>;
-    bf16x8 kf[G::KK], vf[G::KK];           // this wave's 32 keys: K rows, V rows (B operands)
+    using G = DkvGeom<D, KD>;
+    bf16x8 kf[G::K1], vf[G::K1];           // this wave's 32 keys: K rows, V rows (B operands)
     f32x16 dk[G::DB], dv[G::DB];           // dK^T, dV^T accumulators
     f32x16 s[2], dp[2];                    // S - LSE/scale and dP - D: [i & 1] of block i, [~i & 1] of block i+1
-    bf16x8 qf[G::KK], dof[G::KK];          // Q, dO rows of block i+1 (A operands of G1), live inside an iteration
+    bf16x8 qf[G::K1], dof[G::K1];          // Q, dO rows of block i+1 (A operands of G1), live inside an iteration
     bf16x8 qtf[G::KK], dotf[G::KK];        // Q^T, dO^T of block i-1 (A operands of G2), index tt*DB + db
     bf16x8 pprev[2], dsprev[2];            // P, dS of block i-1 as bf16 B operands
 };
@@ -111,11 +115,11 @@ __device__ __forceinline__ bf16x8 lds_read_tr(const char* lds, int a0, int a1) {
 // SPREAD: the iteration also issues its share of the copies of a later tile (`load`), one instruction at a
 // time at fixed places among its LDS reads (the copies are ordered against LDS accesses, the reads are tied
 // to the MFMAs by the scheduling hints): pieces 0-3 in the first iteration of a tile, 4-8 in the second.
-template <int D, int RB, bool MASK, bool SPREAD>
-__device__ __forceinline__ void dkv_iteration(DkvState<D>& st, const char* lds, const DkvAddr<D>& ahead,
+template <int D, int KD, int RB, bool MASK, bool SPREAD>
+__device__ __forceinline__ void dkv_iteration(DkvState<D, KD>& st, const char* lds, const DkvAddr<D>& ahead,
                                               const DkvAddr<D>& cur, int dkey, float c, const DkvTileLoad<D>& load) {
-    using G = DkvGeom<D>;
-    constexpr int KK = G::KK, DB = G::DB;
+    using G = DkvGeom<D, KD>;
+    constexpr int KK = G::KK, DB = G::DB, K1 = G::K1;
     constexpr int NRB = RB ^ 1;   // block i+1 sits at the other position (of the next tile when RB == 1)
     constexpr int P0 = RB == 0 ? 0 : 4;   // first piece of this iteration
 
@@ -142,7 +146,7 @@ __device__ __forceinline__ void dkv_iteration(DkvState<D>& st, const char* lds, 
         for (int j = 0; j < 4; ++j) { st.s[NRB][4 * i4 + j] = a[j]; st.dp[NRB][4 * i4 + j] = b[j]; }
     }
 #pragma unroll
-    for (int kk = 0; kk < KK; ++kk) {
+    for (int kk = 0; kk < K1; ++kk) {
         st.qf[kk] = lds_read128(lds, ahead.rm[kk] + NRB * G::kBlockBytes);
         st.dof[kk] = lds_read128(lds, ahead.rm[kk] + NRB * G::kBlockBytes + G::kTileBytes);
         if constexpr (SPREAD) {
@@ -183,7 +187,7 @@ __device__ __forceinline__ void dkv_iteration(DkvState<D>& st, const char* lds, 
     // G1(i+1) on top of the statistics
     // the two accumulation chains alternate: an MFMA that continues a chain does not follow its predecessor directly
 #pragma unroll
-    for (int kk = 0; kk < KK; ++kk) {
+    for (int kk = 0; kk < K1; ++kk) {
         st.s[NRB] = mfma(st.qf[kk], st.kf[kk], st.s[NRB]);
         st.dp[NRB] = mfma(st.dof[kk], st.vf[kk], st.dp[NRB]);
     }
@@ -191,17 +195,18 @@ __device__ __forceinline__ void dkv_iteration(DkvState<D>& st, const char* lds, 
     softmax_half(1, pw1, dw1);
     cv.u = pw1; st.pprev[1] = cv.v;
     cv.u = dw1; st.dsprev[1] = cv.v;
-    InterleaveHint<2 * KK, 2, (MASK ? 4 : 3), 1, 0x402>::apply();   // per MFMA: 2 of the 4*KK transpose reads, VALU share
+    // per MFMA: a share of the 4 * KK transpose reads (2 each, 3 when the phase has fewer MFMAs), VALU share
+    InterleaveHint<2 * K1, (K1 == KK ? 2 : 3), (MASK ? 4 : 3), 1, 0x402>::apply();
     __builtin_amdgcn_sched_barrier(0);
 }
 
 }  // namespace
 
-template <int D, bool BLOCK>
+template <int D, bool BLOCK, int KD = D / 16>
 __global__ __launch_bounds__(kThreads, 1) void bwd_dkv_kernel(BwdParams p) {
-    using G = DkvGeom<D>;
+    using G = DkvGeom<D, KD>;
     constexpr int BKV = kDkvKTile, BQ = kDkvQTile;
-    constexpr int KK = G::KK, DB = G::DB;
+    constexpr int KK = G::KK, DB = G::DB, K1 = G::K1;
     __shared__ __attribute__((aligned(1024))) char lds[G::kStages * G::kStageBytes];
 
     const ItemGeom item = load_item<BLOCK>(p.items, p.block_items, blockIdx.x);
@@ -275,9 +280,9 @@ __global__ __launch_bounds__(kThreads, 1) void bwd_dkv_kernel(BwdParams p) {
     if (n_tiles > 1) load_tile(1, 1);
     if (n_tiles > 2) load_tile(2, 2);
 
-    DkvState<D> st;
+    DkvState<D, KD> st;
 #pragma unroll
-    for (int kk = 0; kk < KK; ++kk) {
+    for (int kk = 0; kk < K1; ++kk) {
         union { u32x4 u; bf16x8 v; } a, b;
         a.u = u32x4{0u, 0u, 0u, 0u};
         b.u = u32x4{0u, 0u, 0u, 0u};
@@ -335,7 +340,7 @@ __global__ __launch_bounds__(kThreads, 1) void bwd_dkv_kernel(BwdParams p) {
             for (int j = 0; j < 4; ++j) { st.s[0][4 * i4 + j] = a[j]; st.dp[0][4 * i4 + j] = b[j]; }
         }
 #pragma unroll
-        for (int kk = 0; kk < KK; ++kk) {
+        for (int kk = 0; kk < K1; ++kk) {
             st.s[0] = mfma(lds_read128(lds, a0.rm[kk]), st.kf[kk], st.s[0]);
             st.dp[0] = mfma(lds_read128(lds, a0.rm[kk] + G::kTileBytes), st.vf[kk], st.dp[0]);
         }
@@ -368,8 +373,8 @@ __global__ __launch_bounds__(kThreads, 1) void bwd_dkv_kernel(BwdParams p) {
         const int to_next = (stage1 - stage) * G::kStageBytes;
         const DkvAddr<D> next = shifted(off, u + 1 < n_tiles ? to_next : 0);
         const int dkey0 = my_key - shift - qt * BQ - 4 * hh;
-        dkv_iteration<D, 0, kMask, false>(st, lds, off, off, dkey0, c, no_load);
-        dkv_iteration<D, 1, kMask, false>(st, lds, next, off, dkey0 - 32, c, no_load);
+        dkv_iteration<D, KD, 0, kMask, false>(st, lds, off, off, dkey0, c, no_load);
+        dkv_iteration<D, KD, 1, kMask, false>(st, lds, next, off, dkey0 - 32, c, no_load);
         off = shifted(off, to_next);
         stage = stage1;
     };
@@ -389,8 +394,8 @@ __global__ __launch_bounds__(kThreads, 1) void bwd_dkv_kernel(BwdParams p) {
         const int to_next = (stage1 - stage) * G::kStageBytes;
         const DkvAddr<D> next = shifted(off, to_next);
         const int dkey0 = my_key - shift - qt * BQ - 4 * hh;
-        dkv_iteration<D, 0, false, true>(st, lds, off, off, dkey0, c, load);
-        dkv_iteration<D, 1, false, true>(st, lds, next, off, dkey0 - 32, c, load);
+        dkv_iteration<D, KD, 0, false, true>(st, lds, off, off, dkey0, c, load);
+        dkv_iteration<D, KD, 1, false, true>(st, lds, next, off, dkey0 - 32, c, load);
         off = shifted(off, to_next);
         load.q_row -= (int64_t)BQ * p.q_stride;
         load.do_row -= (int64_t)BQ * p.q_heads * hd;
@@ -460,8 +465,13 @@ hipError_t launch_bwd_dkv(const BwdParams& p, int head_dim, int64_t num_items, b
     if (num_items == 0) return hipSuccess;
     const dim3 grid((unsigned)num_items), threads(kThreads);
     if (tile_width(head_dim) == 128) {
-        if (block) hipLaunchKernelGGL((bwd_dkv_kernel<128, true>), grid, threads, 0, stream, p);
-        else hipLaunchKernelGGL((bwd_dkv_kernel<128, false>), grid, threads, 0, stream, p);
+        if (contraction_steps(head_dim) <= 7) {
+            if (block) hipLaunchKernelGGL((bwd_dkv_kernel<128, true, 7>), grid, threads, 0, stream, p);
+            else hipLaunchKernelGGL((bwd_dkv_kernel<128, false, 7>), grid, threads, 0, stream, p);
+        } else {
+            if (block) hipLaunchKernelGGL((bwd_dkv_kernel<128, true>), grid, threads, 0, stream, p);
+            else hipLaunchKernelGGL((bwd_dkv_kernel<128, false>), grid, threads, 0, stream, p);
+        }
     } else {
         if (block) hipLaunchKernelGGL((bwd_dkv_kernel<64, true>), grid, threads, 0, stream, p);
         else hipLaunchKernelGGL((bwd_dkv_kernel<64, false>), grid, threads, 0, stream, p);

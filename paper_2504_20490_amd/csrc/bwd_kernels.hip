@@ -49,10 +49,13 @@ __global__ __launch_bounds__(kThreads) void bwd_dsum_kernel(BwdParams p) {
 }
 
 // --------------------------------------------------------------------------------- dQ pass
-template <int D, bool BLOCK>
+// KD: 16-column steps of the contractions over head_dim (S^T = K Q^T, dP^T = V dO^T) that hold data: D / 16, or fewer
+// when head_dim ends before the tile width (the steps beyond it would multiply the zero padding of the Q / dO fragments)
+template <int D, bool BLOCK, int KD = D / 16>
 __global__ __launch_bounds__(kThreads, 2) void bwd_dq_kernel(BwdParams p) {
+    static_assert(KD >= 1 && KD <= D / 16, "k-steps inside the tile width");
     constexpr int BQ = kFwdQTile, BK = kFwdKTile;
-    constexpr int KK = D / 16, DB = D / 32;
+    constexpr int KK = KD, DB = D / 32;
     constexpr int kTileBytes = BK * D * 2;
     __shared__ __attribute__((aligned(1024))) char lds[2 * 2 * kTileBytes];   // {K, V} x 2 stages
 
@@ -329,8 +332,13 @@ hipError_t launch_bwd_dq(const BwdParams& p, int head_dim, int64_t num_items, bo
     if (num_items == 0) return hipSuccess;
     const dim3 grid((unsigned)num_items), threads(kThreads);
     if (tile_width(head_dim) == 128) {
-        if (block) hipLaunchKernelGGL((bwd_dq_kernel<128, true>), grid, threads, 0, stream, p);
-        else hipLaunchKernelGGL((bwd_dq_kernel<128, false>), grid, threads, 0, stream, p);
+        if (contraction_steps(head_dim) <= 7) {
+            if (block) hipLaunchKernelGGL((bwd_dq_kernel<128, true, 7>), grid, threads, 0, stream, p);
+            else hipLaunchKernelGGL((bwd_dq_kernel<128, false, 7>), grid, threads, 0, stream, p);
+        } else {
+            if (block) hipLaunchKernelGGL((bwd_dq_kernel<128, true>), grid, threads, 0, stream, p);
+            else hipLaunchKernelGGL((bwd_dq_kernel<128, false>), grid, threads, 0, stream, p);
+        }
     } else {
         if (block) hipLaunchKernelGGL((bwd_dq_kernel<64, true>), grid, threads, 0, stream, p);
         else hipLaunchKernelGGL((bwd_dq_kernel<64, false>), grid, threads, 0, stream, p);

@@ -17,6 +17,32 @@
 #include "kernels.hpp"
 #include "schedule.hpp"
 
+namespace hspmd {
+
+// compute units of the current device (queried once per device)
+int persistent_grid(int64_t num_items, int per_cu) {
+    static std::mutex mutex;
+    static std::map<int, int> compute_units;
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return 0;
+    int cus = 0;
+    {
+        std::lock_guard<std::mutex> lock(mutex);
+        auto it = compute_units.find(dev);
+        if (it == compute_units.end()) {
+            if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0) return 0;
+            compute_units[dev] = cus;
+        } else {
+            cus = it->second;
+        }
+    }
+    // a multiple of the queue count, like the list length
+    const int64_t resident = (int64_t)(cus * per_cu / kNumXcd) * kNumXcd;
+    return (int)std::min<int64_t>(num_items, std::max<int64_t>(resident, kNumXcd));
+}
+
+}  // namespace hspmd
+
 namespace {
 
 thread_local std::string g_last_error;
@@ -135,6 +161,9 @@ struct ListSlot {
     bool recorded = false;
 };
 constexpr int kPlanSlots = 3;
+// the draw counters of one pass (16 int32) in units of list items
+constexpr size_t kCounterItems = 16 * sizeof(int32_t) / sizeof(hspmd_work_item);
+constexpr size_t kCounterBlockItems = 16 * sizeof(int32_t) / sizeof(hspmd_block_item);
 
 struct hspmd_attn_plan {
     int32_t num_seqs = 0;
@@ -148,6 +177,7 @@ struct hspmd_attn_plan {
     bool is_block = false;
     int64_t total_kv_tokens = 0;
     hspmd_block_item* block_items[3] = {nullptr, nullptr, nullptr};
+    int32_t* queue[3] = {nullptr, nullptr, nullptr};   // device: draw counters of the three passes (zero between launches)
     // device copies of the lists
     ListSlot slots[kPlanSlots];
     int current = 0;
@@ -233,7 +263,17 @@ hspmd_status fill_packed_plan(hspmd_attn_plan* plan, const int32_t* cu, int32_t 
     } catch (const std::bad_alloc&) {
         return fail(HSPMD_ERR_INVALID_ARG, "out of host memory while building the work lists");
     }
+    // behind the lists: the draw counters of the three passes, uploaded as zeros (one list item = 16 bytes = 4 counters)
+    const size_t counters_at = all.size();
+    try {
+        all.resize(all.size() + 3 * kCounterItems, hspmd_work_item{0, 0, 0, 0});
+    } catch (const std::bad_alloc&) {
+        return fail(HSPMD_ERR_INVALID_ARG, "out of host memory while building the work lists");
+    }
     if (hspmd_status rc = install_lists(plan, all.data(), all.size() * sizeof(hspmd_work_item), first)) return rc;
+    for (int kind = 0; kind < 3; ++kind)
+        plan->queue[kind] = reinterpret_cast<int32_t*>(static_cast<hspmd_work_item*>(plan->slots[plan->current].block) +
+                                                       counters_at + kind * kCounterItems);
     plan->num_seqs = num_seqs;
     plan->total_tokens = cu[num_seqs];
     plan->max_position = 0;
@@ -267,7 +307,16 @@ hspmd_status fill_block_plan(hspmd_attn_plan* plan, const int32_t* cu_q, const i
     } catch (const std::bad_alloc&) {
         return fail(HSPMD_ERR_INVALID_ARG, "out of host memory while building the work lists");
     }
+    const size_t counters_at = all.size();
+    try {
+        all.resize(all.size() + 3 * kCounterBlockItems, hspmd_block_item{0, 0, 0, 0, 0, 0, 0, 0});
+    } catch (const std::bad_alloc&) {
+        return fail(HSPMD_ERR_INVALID_ARG, "out of host memory while building the work lists");
+    }
     if (hspmd_status rc = install_lists(plan, all.data(), all.size() * sizeof(hspmd_block_item), first)) return rc;
+    for (int kind = 0; kind < 3; ++kind)
+        plan->queue[kind] = reinterpret_cast<int32_t*>(static_cast<hspmd_block_item*>(plan->slots[plan->current].block) +
+                                                       counters_at + kind * kCounterBlockItems);
     plan->num_seqs = num_seqs;
     plan->total_tokens = cu_q[num_seqs];
     plan->total_kv_tokens = cu_k[num_seqs];
@@ -474,6 +523,8 @@ hspmd_status hspmd_attn_varlen_fwd(const hspmd_attn_plan* plan, const void* q, c
     p.group = plan->q_heads / plan->kv_heads;
     p.head_dim = plan->head_dim;
     p.scale_log2 = scale * 1.4426950408889634f;
+    p.num_items = (int32_t)plan->count[HSPMD_LIST_FWD];
+    p.queue = plan->queue[HSPMD_LIST_FWD];
     hipStream_t s = static_cast<hipStream_t>(stream);
     const hipError_t e = timed_launch(0, s, [&] { return hspmd::launch_fwd(p, plan->head_dim, plan->count[HSPMD_LIST_FWD], false, s); });
     if (e != hipSuccess) return fail_hip(e, "forward launch");
@@ -781,6 +832,8 @@ hspmd_status hspmd_attn_block_fwd(const hspmd_attn_plan* plan, const void* q, co
     p.group = plan->q_heads / plan->kv_heads;
     p.head_dim = plan->head_dim;
     p.scale_log2 = scale * 1.4426950408889634f;
+    p.num_items = (int32_t)plan->count[HSPMD_LIST_FWD];
+    p.queue = plan->queue[HSPMD_LIST_FWD];
     hipStream_t s = static_cast<hipStream_t>(stream);
     const hipError_t e = timed_launch(0, s, [&] { return hspmd::launch_fwd(p, plan->head_dim, plan->count[HSPMD_LIST_FWD], true, s); });
     if (e != hipSuccess) return fail_hip(e, "block forward launch");

@@ -21,6 +21,8 @@ struct FwdParams {
     int32_t q_heads, group;
     int32_t head_dim;              // elements per head in memory (a multiple of 8, at most the kernel's tile width)
     float scale_log2;              // softmax_scale * log2(e)
+    int32_t num_items;             // slots of the work list (padding included)
+    int32_t* queue;                // this pass's draw counters (ItemQueue), zero between launches
 };
 
 struct BwdParams {
@@ -48,11 +50,20 @@ struct BwdParams {
                                    // then leave as gradients with respect to the q and k BEFORE the rotary embedding
     float scale;                   // softmax_scale
     float scale_log2;              // softmax_scale * log2(e)
+    int32_t num_items;             // slots of the current pass's work list (padding included)
+    int32_t* queue;                // the current pass's draw counters (ItemQueue), zero between launches
 };
 
 // The kernels exist for tile widths 64 and 128 (LDS rows, MFMA contraction); a head_dim below the tile width runs
 // on the next width up: register fragments are zero beyond head_dim, LDS pad columns repeat a valid chunk.
 inline int tile_width(int head_dim) { return head_dim <= 64 ? 64 : 128; }
+// 16-column steps of a contraction over head_dim that hold data; the kernels of tile width 128 also exist with 7
+// steps (head_dim 97 .. 112, such as the 104 of the paper's 32B model), which skip the step that is all padding
+inline int contraction_steps(int head_dim) { return (head_dim + 15) / 16; }
+
+// Workgroups that a persistent kernel starts: as many as the current device holds at once at `per_cu` workgroups per
+// compute unit, and not more than the list has slots (the list length is a multiple of the queue count).
+int persistent_grid(int64_t num_items, int per_cu);
 
 // `block`: the items are hspmd_block_item (separate query / key chunks, shifted causal mask)
 hipError_t launch_fwd(const FwdParams& p, int head_dim, int64_t num_items, bool block, hipStream_t stream);
