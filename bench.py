@@ -52,6 +52,48 @@ def read_traffic(kernel: str, workload: str):
     return value, f"{rel} (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of these kernel sources, not this run)"
 
 
+class PowerSampler:
+    """Socket power (W) and shader clock (MHz) of GPU 0 while the timed steps run, read with the system management
+    tools (`amd-smi metric -p`, `rocm-smi --showclocks`) from a side thread about twice a second.  Needs a timed region
+    of several seconds (--steps in the thousands): the tools take a few hundred milliseconds per reading, and the
+    readings are averages over about a second.  Evidence for the power limit the kernels run into, not a benchmark
+    figure; absent tools give no readings."""
+
+    def __init__(self):
+        import threading
+        self.power, self.sclk = [], []
+        self._stop = threading.Event()
+        self._thread = threading.Thread(target=self._run, daemon=True)
+
+    def _run(self):
+        import re
+        import subprocess
+        if self._stop.wait(1.5):            # let the clocks settle under the load
+            return
+        while not self._stop.is_set():
+            try:
+                out = subprocess.run(["amd-smi", "metric", "-p"], capture_output=True, text=True, timeout=10).stdout
+                m = re.search(r"SOCKET_POWER:\s*([0-9.]+)\s*W", out)
+                if m:
+                    self.power.append(float(m.group(1)))
+                out = subprocess.run(["rocm-smi", "--showclocks"], capture_output=True, text=True, timeout=10).stdout
+                m = re.search(r"sclk clock level:[^(]*\(([0-9.]+)Mhz\)", out)
+                if m:
+                    self.sclk.append(float(m.group(1)))
+            except (OSError, subprocess.SubprocessError):
+                return
+            self._stop.wait(0.3)
+
+    def start(self):
+        self._thread.start()
+
+    def stop(self):
+        self._stop.set()
+        self._thread.join(timeout=30)
+        mean = lambda v: round(sum(v) / len(v), 1) if v else None
+        return {"socket_power_w": mean(self.power), "sclk_mhz": mean(self.sclk), "readings": len(self.power)}
+
+
 def cpu_baseline(cfg, lengths, q, k, v, do, rope=False):
     """The fp64 oracle, as it stands, on a bounded sample of the same pack: whole sequences of the
     pack (shortest first, up to a pair budget) and eight KV groups, forward + backward (with `rope`:
@@ -261,6 +303,9 @@ def main() -> int:
     ap.add_argument("--inputs", default="workload", choices=["workload", "zeros"],
                     help="zeros: all-zero q, k, v, dO (same instruction stream, almost no switching activity): shows how "
                          "much of the kernel time is the power-limited clock.  A side measurement, not a benchmark result")
+    ap.add_argument("--sample-power", action="store_true",
+                    help="read the socket power and the shader clock with amd-smi / rocm-smi while the timed steps run "
+                         "(use several thousand --steps: the readings are one-second averages); reported under 'power'")
     ap.add_argument("--rope", action="store_true",
                     help="add rotary embedding to the step: q, k rotated by the elementwise kernel before the forward, "
                          "dQ and dK turned back inside the backward epilogues (side measurement)")
@@ -341,14 +386,26 @@ def main() -> int:
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
-    A.profile_enable(True)
+    sampler = PowerSampler() if args.sample_power else None
+    A.profile_enable(not args.sample_power)      # a long power run would pile up two events per launch: timing off
     torch.cuda.synchronize()
+    if sampler:
+        sampler.start()
     t0 = time.perf_counter()
-    for _ in range(args.steps):
+    for i in range(args.steps):
         step()
+        if sampler and i % 64 == 63:
+            torch.cuda.synchronize()             # keep the launch queue short; the device stays busy
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
+    power = sampler.stop() if sampler else None
     A.profile_enable(False)
+    if args.sample_power:                        # per-kernel times from a short timed run of the same step
+        A.profile_enable(True)
+        for _ in range(20):
+            step()
+        torch.cuda.synchronize()
+        A.profile_enable(False)
     stats = A.profile_read_stats()
     prof = {name: (st["mean"] * st["launches"], st["launches"]) for name, st in stats.items()}
 
@@ -415,6 +472,8 @@ def main() -> int:
                      "note": f"{GEMMS[dominant]} GEMMs over the visible pairs; avg of {prof[dominant][1]} launches "
                              "timed with HIP events on the launch stream"},
     }
+    if power is not None:
+        out["power"] = power
     if args.inputs == "zeros":
         out["metric"] = "varlen causal attn fwd+bwd on ALL-ZERO inputs (clock-dependence probe, not a benchmark result)"
         out["data"] = "zeros"
