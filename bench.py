@@ -135,6 +135,34 @@ def cpu_baseline(cfg, lengths, q, k, v, do, rope=False):
                       f"fwd+bwd in fp64, {dt:.1f} s"}
 
 
+def run_probe(args) -> int:
+    """The matrix-core probes (hspmd_probe_mfma_rate), each run for a few seconds with the socket power and the shader
+    clock read beside it: which MFMA shape delivers more inside the chip's power limit, what streaming an operand
+    from LDS costs, and whether idle time of the matrix pipes is returned as clock.  A side measurement: prints one
+    JSON line of its own kind."""
+    import torch
+    import paper_2504_20490_amd as A
+
+    if not torch.cuda.is_available():
+        print("bench.py needs a GPU", file=sys.stderr)
+        return 2
+    A.load_library()
+    torch.cuda.set_device(0)
+    scratch = torch.empty(A.probe_scratch_bytes(), dtype=torch.uint8, device="cuda:0")
+    rows = []
+    for name, mode in A.PROBE_MODES.items():
+        A.probe_mfma_rate(mode, scratch, mfma_per_wave=1 << 16)
+        sampler = PowerSampler()
+        sampler.start()
+        t0, rate = time.perf_counter(), 0.0
+        while time.perf_counter() - t0 < args.probe_seconds:
+            rate = A.probe_mfma_rate(mode, scratch, mfma_per_wave=1 << 20)
+        rows.append({"probe": name, "tflops": round(rate, 1), **sampler.stop()})
+    print(json.dumps({"metric": "dense bf16 MFMA rate of register-level probes (side measurement)", "unit": "TFLOP/s",
+                      "n_gpus": 1, "peak": PEAK_BF16_TFLOPS, "probes": rows}))
+    return 0
+
+
 def run_ring(args) -> int:
     """One rank of an emulated context-parallel ring: every sequence of the pack is cut into N chunks by position,
     this rank owns chunk `--ring-rank` of every sequence as queries and meets the N key/value chunks one after the
@@ -306,6 +334,9 @@ def main() -> int:
     ap.add_argument("--sample-power", action="store_true",
                     help="read the socket power and the shader clock with amd-smi / rocm-smi while the timed steps run "
                          "(use several thousand --steps: the readings are one-second averages); reported under 'power'")
+    ap.add_argument("--probe", action="store_true",
+                    help="run the matrix-core probes instead of the attention step (see run_probe)")
+    ap.add_argument("--probe-seconds", type=float, default=4.0, help="how long each probe runs while power is sampled")
     ap.add_argument("--rope", action="store_true",
                     help="add rotary embedding to the step: q, k rotated by the elementwise kernel before the forward, "
                          "dQ and dK turned back inside the backward epilogues (side measurement)")
@@ -315,6 +346,8 @@ def main() -> int:
               "build (no collectives, no sharding across GPUs).", file=sys.stderr)
         return 2
 
+    if args.probe:
+        return run_probe(args)
     if args.ring > 0:
         return run_ring(args)
 

@@ -443,6 +443,28 @@ hspmd_status hspmd_probe_mfma_tflops(int64_t mfma_per_wave, void* scratch_out, s
 hspmd_status hspmd_probe_mfma_tflops_varied(int64_t mfma_per_wave, void* scratch_out, size_t scratch_bytes,
                                      void* stream, double* tflops);
 
+/*
+ * Variants of the matrix-core rate probe, all on varying operands unless named constant (measurement only; not part
+ * of the paper's method).  They answer the questions the attention kernels raise about the chip they run on:
+ * which MFMA shape delivers more flops inside the chip's power limit, what streaming the A operand from LDS costs,
+ * and whether idle time of the matrix pipes is returned as clock (the limit is an average one, not an instantaneous one).
+ * Arguments, scratch and synchronisation as hspmd_probe_mfma_tflops; one round is 16 products 32x32x16 or 32 products
+ * 16x16x32 (the same flops).  INVALID_ARG for an unknown mode.
+ */
+typedef enum {
+    HSPMD_PROBE_32X32X16_CONSTANT = 0,   /* = hspmd_probe_mfma_tflops */
+    HSPMD_PROBE_32X32X16 = 1,            /* register operands, two waves per SIMD */
+    HSPMD_PROBE_16X16X32 = 2,
+    HSPMD_PROBE_32X32X16_LDS = 3,        /* every A fragment read from LDS (1 KB per 32x32x16 product), B in registers */
+    HSPMD_PROBE_16X16X32_LDS = 4,        /* every A fragment read from LDS and used by two products */
+    HSPMD_PROBE_IDLE_0 = 5,              /* one wave per SIMD, no idle time */
+    HSPMD_PROBE_IDLE_256 = 6,            /* ... 256 clocks of s_sleep after every 512 clocks of products */
+    HSPMD_PROBE_IDLE_512 = 7,
+    HSPMD_PROBE_IDLE_1024 = 8
+} hspmd_probe_mode;
+hspmd_status hspmd_probe_mfma_rate(hspmd_probe_mode mode, int64_t mfma_per_wave, void* scratch_out, size_t scratch_bytes,
+                                   void* stream, double* tflops);
+
 #ifdef __cplusplus
 }
 #endif

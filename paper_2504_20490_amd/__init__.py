@@ -10,5 +10,5 @@ from .binding import (  # noqa: F401
     attn_varlen_fwd, attn_varlen_bwd, profile_enable, profile_read, profile_read_stats, probe_scratch_bytes, probe_mfma_tflops,
     BlockPlan, block_schedule, attn_block_fwd, attn_merge, attn_block_bwd, estimate_ms,
     rope_table_bytes, rope_table, rope_qk, attn_varlen_bwd_rope, attn_block_bwd_rope,
-    attn_varlen_bwd_static_ws, STATIC_WORKSPACE_BYTES,
+    attn_varlen_bwd_static_ws, STATIC_WORKSPACE_BYTES, probe_mfma_rate, PROBE_MODES,
 )

@@ -137,6 +137,9 @@ def load_library():
                                             ctypes.POINTER(ctypes.c_double)]
     lib.hspmd_probe_mfma_tflops_varied.restype = ctypes.c_int
     lib.hspmd_probe_mfma_tflops_varied.argtypes = lib.hspmd_probe_mfma_tflops.argtypes
+    lib.hspmd_probe_mfma_rate.restype = ctypes.c_int
+    lib.hspmd_probe_mfma_rate.argtypes = [ctypes.c_int, ctypes.c_int64, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p,
+                                          ctypes.POINTER(ctypes.c_double)]
     lib.hspmd_profile_read.restype = ctypes.c_int
     lib.hspmd_profile_read.argtypes = [ctypes.POINTER(ctypes.c_double), i64p]
     lib.hspmd_profile_read_stats.restype = ctypes.c_int
@@ -368,6 +371,22 @@ def probe_mfma_tflops(scratch, mfma_per_wave: int = 1 << 18, stream=None, varied
     fn = lib.hspmd_probe_mfma_tflops_varied if varied_operands else lib.hspmd_probe_mfma_tflops
     _check(fn(int(mfma_per_wave), _dev_ptr(scratch), scratch.numel() * scratch.element_size(), _stream_handle(stream),
               ctypes.byref(out)))
+    return float(out.value)
+
+
+PROBE_MODES = {"32x32x16 constant operands": 0, "32x32x16": 1, "16x16x32": 2, "32x32x16, A from LDS": 3,
+               "16x16x32, A from LDS": 4, "32x32x16, one wave per SIMD": 5,
+               "32x32x16, one wave per SIMD, 256 idle clocks per 512": 6,
+               "32x32x16, one wave per SIMD, 512 idle clocks per 512": 7,
+               "32x32x16, one wave per SIMD, 1024 idle clocks per 512": 8}
+
+
+def probe_mfma_rate(mode: int, scratch, mfma_per_wave: int = 1 << 18, stream=None) -> float:
+    """Dense bf16 rate (TFLOP/s) of one variant of the matrix-core probe (PROBE_MODES); synchronises the stream."""
+    out = ctypes.c_double(0.0)
+    _check(load_library().hspmd_probe_mfma_rate(int(mode), int(mfma_per_wave), _dev_ptr(scratch),
+                                                scratch.numel() * scratch.element_size(), _stream_handle(stream),
+                                                ctypes.byref(out)))
     return float(out.value)
 
 

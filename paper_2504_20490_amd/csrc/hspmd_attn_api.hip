@@ -1010,6 +1010,39 @@ static hspmd_status probe_mfma(int64_t mfma_per_wave, bool varied_operands, void
     return HSPMD_OK;
 }
 
+hspmd_status hspmd_probe_mfma_rate(hspmd_probe_mode mode, int64_t mfma_per_wave, void* scratch_out, size_t scratch_bytes,
+                                   void* stream, double* tflops) {
+    if (mode < HSPMD_PROBE_32X32X16_CONSTANT || mode > HSPMD_PROBE_IDLE_1024) return fail(HSPMD_ERR_INVALID_ARG, "unknown probe mode");
+    if (!scratch_out || !tflops) return fail(HSPMD_ERR_INVALID_ARG, "null pointer");
+    if (mfma_per_wave <= 0) return fail(HSPMD_ERR_INVALID_ARG, "mfma_per_wave must be positive");
+    if (scratch_bytes < hspmd_probe_scratch_bytes()) return fail(HSPMD_ERR_WORKSPACE_TOO_SMALL, "probe scratch too small");
+    int dev = 0, cus = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e == hipSuccess) e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
+    if (e != hipSuccess) return fail_hip(e, "device query");
+    const int grid = hspmd::probe_mode_grid(mode, cus);
+    if (grid <= 0 || grid > hspmd::kProbeMaxGrid) return fail(HSPMD_ERR_UNSUPPORTED, "unexpected compute unit count");
+    const int64_t rounds = (mfma_per_wave + 15) / 16;
+    hipStream_t s = (hipStream_t)stream;
+    hipEvent_t start = nullptr, stop = nullptr;
+    e = hipEventCreate(&start);
+    if (e == hipSuccess) e = hipEventCreate(&stop);
+    if (e == hipSuccess) e = hspmd::launch_mfma_probe_mode(mode, (float*)scratch_out, rounds, grid, s);   // untimed
+    if (e == hipSuccess) e = hipEventRecord(start, s);
+    if (e == hipSuccess) e = hspmd::launch_mfma_probe_mode(mode, (float*)scratch_out, rounds, grid, s);
+    if (e == hipSuccess) e = hipEventRecord(stop, s);
+    if (e == hipSuccess) e = hipEventSynchronize(stop);
+    float ms = 0.f;
+    if (e == hipSuccess) e = hipEventElapsedTime(&ms, start, stop);
+    if (start) (void)hipEventDestroy(start);
+    if (stop) (void)hipEventDestroy(stop);
+    if (e != hipSuccess) return fail_hip(e, "mfma probe");
+    // a round = 16 products 32x32x16 (or 32 products 16x16x32) = 16 * 2 * 32 * 32 * 16 flops; 4 waves per workgroup
+    const double flops = (double)grid * 4.0 * (double)(rounds * 16) * 32768.0;
+    *tflops = ms > 0.f ? flops / ((double)ms * 1e-3) / 1e12 : 0.0;
+    return HSPMD_OK;
+}
+
 hspmd_status hspmd_probe_mfma_tflops(int64_t mfma_per_wave, void* scratch_out, size_t scratch_bytes, void* stream,
                                      double* tflops) {
     return probe_mfma(mfma_per_wave, false, scratch_out, scratch_bytes, stream, tflops);

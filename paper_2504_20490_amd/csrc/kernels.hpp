@@ -110,5 +110,8 @@ constexpr int kProbeMaxGrid = 4096;
 constexpr int kProbeThreads = 256;
 int probe_grid(int compute_units);
 hipError_t launch_mfma_probe(float* out, int64_t rounds, int grid, bool varied_operands, hipStream_t stream);
+// the variants of hspmd_probe_mfma_rate (mode = hspmd_probe_mode)
+int probe_mode_grid(int mode, int compute_units);
+hipError_t launch_mfma_probe_mode(int mode, float* out, int64_t rounds, int grid, hipStream_t stream);
 
 }  // namespace hspmd

@@ -305,3 +305,11 @@ def test_mfma_rate_probe_is_plausible():
         A.probe_mfma_tflops(scratch[:16])
     with pytest.raises(A.HspmdError):
         A.probe_mfma_tflops(scratch, mfma_per_wave=0)
+    # the variants: every mode runs and lands in a plausible range; idle time lowers the rate, never raises it
+    rates = {name: A.probe_mfma_rate(mode, scratch, mfma_per_wave=1 << 16) for name, mode in A.PROBE_MODES.items()}
+    assert all(300.0 < r < 2700.0 for r in rates.values()), rates
+    idle = [rates[n] for n in A.PROBE_MODES if "one wave per SIMD" in n]
+    assert idle[0] > idle[1] > idle[2] > idle[3], idle
+    assert rates["32x32x16, A from LDS"] < 1.05 * rates["32x32x16"]
+    with pytest.raises(A.HspmdError):
+        A.probe_mfma_rate(99, scratch)
