@@ -180,8 +180,8 @@ std::vector<hspmd_work_item> build_work_list(hspmd_list_kind kind, const int32_t
 // kernels of this library.  Fitted by relative least squares to 40 packs per head_dim: mean absolute error
 // 6-9 %, at most 15-29 % (on packs that take about a hundred microseconds).
 PassCost pass_cost_coefficients(hspmd_list_kind kind, int32_t head_dim) {
-    static const PassCost k128[3] = {{8.1, 1.910, 8.17}, {8.0, 2.353, 17.61}, {26.2, 1.653, 11.36}};
-    static const PassCost k64[3] = {{7.4, 1.190, 4.20}, {8.6, 1.312, 8.69}, {18.6, 1.024, 6.44}};
+    static const PassCost k128[3] = {{13.1, 1.655, 10.37}, {7.6, 2.168, 18.64}, {24.8, 1.620, 11.66}};
+    static const PassCost k64[3] = {{13.1, 1.045, 6.22}, {7.6, 1.239, 9.02}, {18.5, 1.062, 6.41}};
     return (head_dim == 64 ? k64 : k128)[(int)kind];
 }
 
