@@ -468,6 +468,7 @@ def main() -> int:
     dom_ms = kern[dominant]
     achieved = GEMMS[dominant] * pair_flops / (dom_ms * 1e-3) / 1e12 if dom_ms > 0 else 0.0
 
+    from paper_2504_20490_amd.build import sources_digest
     traffic, traffic_source = read_traffic(dominant, cfg.name.split("_")[0])
     out = {
         "metric": "varlen causal attn fwd+bwd TFLOP/s and % bf16 MFMA peak, 32k-token mix",
@@ -486,6 +487,7 @@ def main() -> int:
                    "head_dim": d, "num_seqs": len(lengths), "lengths": lengths,
                    "sum_L_Lplus1": 2 * w.causal_pairs(lengths), "fwd_useful_flops": fwd,
                    "grad_dtype": args.grad_dtype, "order": args.order,
+                   "kernel_sources_sha256_16": sources_digest(),
                    "step": "build_cu_seqlens + work lists (plan refill, no device allocation) + fwd + "
                            "bwd(dQ pass with the row statistic D, dK/dV pass)"},
         "pct_of_bf16_mfma_peak": round(100.0 * tflops / PEAK_BF16_TFLOPS, 2),

@@ -178,7 +178,7 @@ std::vector<hspmd_work_item> build_work_list(hspmd_list_kind kind, const int32_t
 // The paper's planner dispatches mixed-length sequences with a cost model evaluated on the CPU (Appendix
 // "Scenario-specific Planning", mixed-length case); this is the per-operator predictor for the attention
 // kernels of this library.  Fitted by relative least squares to 40 packs per head_dim: mean absolute error
-// 6-9 %, at most 15-29 % (on packs that take about a hundred microseconds).
+// 6-8 %, at most 15-32 % (on packs that take about a hundred microseconds).
 PassCost pass_cost_coefficients(hspmd_list_kind kind, int32_t head_dim) {
     static const PassCost k128[3] = {{13.1, 1.655, 10.37}, {7.6, 2.168, 18.64}, {24.8, 1.620, 11.66}};
     static const PassCost k64[3] = {{13.1, 1.045, 6.22}, {7.6, 1.239, 9.02}, {18.5, 1.062, 6.41}};
