@@ -109,34 +109,57 @@ __global__ __launch_bounds__(kThreads, 2) void bwd_dq_kernel(BwdParams p) {
     // what bwd_dsum_kernel wrote (the statistics of the merged rows are shared by all blocks of a row).
     bf16x8 qf[KK], dof[KK];
     float d_part = 0.f;
+    float stat_a, stat_b = 0.f;   // the row's saved statistics, requested together with its Q / dO / O
+    {
+        // All loads first, from addresses that exist for every lane (a lane past the end of the chunk reads the tile's
+        // first row, a column chunk past head_dim reads the head's last one), the selection afterwards: loads under a
+        // per-lane condition end up in one conditional block per step, each waiting for its own data before the
+        // next block's loads are issued: eight memory round trips in a row at the start of every item.
+        const int lrow = valid ? my_row : q_row0;
+        const int64_t lstat = (int64_t)h * p.total_tokens + item.q_start + lrow;
+        if constexpr (BLOCK) {
+            stat_a = p.nlse[lstat];
+            stat_b = p.negd[lstat];
+        } else {
+            stat_a = p.lse[lstat];
+        }
+        const uint16_t* qrow = qbase + (int64_t)lrow * p.q_stride;
+        const int64_t row_elem = (int64_t)lrow * p.q_heads * hd;
+        const uint16_t* dorow = dobase + row_elem;
+        const uint16_t* orow = p.o + ((int64_t)item.q_start * p.q_heads + h) * hd + row_elem;
+        u32x4 qa[KK], da[KK], oa[KK];
 #pragma unroll
-    for (int kk = 0; kk < KK; ++kk) {
-        union { u32x4 u; bf16x8 v; } a, b;
-        a.u = u32x4{0u, 0u, 0u, 0u};
-        b.u = u32x4{0u, 0u, 0u, 0u};
-        if (valid && kk * 16 + hh * 8 < hd) {
-            const int64_t row_elem = (int64_t)my_row * p.q_heads * hd + kk * 16 + hh * 8;
-            a.u = *reinterpret_cast<const u32x4*>(qbase + (int64_t)my_row * p.q_stride + kk * 16 + hh * 8);
-            b.u = *reinterpret_cast<const u32x4*>(dobase + row_elem);
+        for (int kk = 0; kk < KK; ++kk) {
+            const int col = min(kk * 16 + hh * 8, hd - 8);
+            qa[kk] = *reinterpret_cast<const u32x4*>(qrow + col);
+            da[kk] = *reinterpret_cast<const u32x4*>(dorow + col);
+            if constexpr (!BLOCK) oa[kk] = *reinterpret_cast<const u32x4*>(orow + col);
+        }
+#pragma unroll
+        for (int kk = 0; kk < KK; ++kk) {
+            const bool keep = valid && kk * 16 + hh * 8 < hd;
+            union { u32x4 u; bf16x8 v; } a, b;
+            a.u = keep ? qa[kk] : u32x4{0u, 0u, 0u, 0u};
+            b.u = keep ? da[kk] : u32x4{0u, 0u, 0u, 0u};
             if constexpr (!BLOCK) {
                 union { u32x4 u; bf16x8 v; } o;
-                o.u = *reinterpret_cast<const u32x4*>(p.o + ((int64_t)item.q_start * p.q_heads + h) * hd + row_elem);
+                o.u = oa[kk];
 #pragma unroll
-                for (int i = 0; i < 8; ++i) d_part += (float)b.v[i] * (float)o.v[i];
+                for (int i = 0; i < 8; ++i) d_part += (float)b.v[i] * (float)o.v[i];   // b = 0 where nothing is kept
             }
+            qf[kk] = a.v;
+            dof[kk] = b.v;
         }
-        qf[kk] = a.v;
-        dof[kk] = b.v;
     }
     const int64_t stat = (int64_t)h * p.total_tokens + item.q_start + my_row;
     const float c = p.scale_log2;
     float nlse2, negd;
     if constexpr (BLOCK) {
-        nlse2 = valid ? p.nlse[stat] * c : -INFINITY;   // -LSE log2(e); rows past the end get P = 0
-        negd = valid ? p.negd[stat] : 0.f;
+        nlse2 = valid ? stat_a * c : -INFINITY;   // -LSE log2(e); rows past the end get P = 0
+        negd = valid ? stat_b : 0.f;
     } else {
         negd = -(d_part + partner32(d_part));            // the two half rows of lanes l and l + 32
-        const float nlse = valid ? -p.lse[stat] / p.scale : -INFINITY;   // rows past the end get P = 0
+        const float nlse = valid ? -stat_a / p.scale : -INFINITY;   // rows past the end get P = 0
         nlse2 = nlse * c;                                                // -LSE log2(e)
         if (valid && hh == 0) {
             p.negd[stat] = negd;
