@@ -122,6 +122,15 @@ def test_gqa_group_of_four_multi_tile():
     _full_check([515, 1, 900], 8, 2, 128, seed=22)
 
 
+@pytest.mark.parametrize("hq,hkv,d", [(16, 2, 128), (8, 1, 64), (16, 1, 104)])
+def test_gqa_groups_of_eight_and_sixteen(hq, hkv, d):
+    """Eight and sixteen query heads per KV head: the dK/dV workgroup walks the whole group, head after head, over
+    several q tiles each, and sums it into one dK / dV tile.  With N(0,1) values the sum over sixteen heads carries
+    dV of a sequence's first tokens to |dV| = 17.6 (one KV head) and dK to 8.2: those tensors take the bound for
+    references of magnitude >= 8, the others the nominal one."""
+    _full_check([300, 777, 64], hq, hkv, d, seed=23 + hq + d, magnitude_slack=True)
+
+
 def test_explicit_scale_and_small_values():
     _full_check([130, 260], 2, 1, 128, seed=23, value_scale=1.0 / 128 ** 0.5, scale=0.2)
 
